@@ -1,0 +1,28 @@
+"""Compile the CPU oracle into oracle/liboracle.so (g++, no fast-math, no contraction)."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(HERE, "liboracle.so")
+
+
+def build(verbose: bool = False) -> str:
+    cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+           "-shared", "-fPIC", os.path.join(HERE, "oracle.cpp"), "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+def ensure_built() -> str:
+    src = os.path.join(HERE, "oracle.cpp")
+    hdr = os.path.join(HERE, "oracle.h")
+    if (not os.path.exists(LIB) or os.path.getmtime(LIB) < max(os.path.getmtime(src),
+                                                              os.path.getmtime(hdr))):
+        build()
+    return LIB
+
+
+if __name__ == "__main__":
+    build(verbose=True)

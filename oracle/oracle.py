@@ -1,0 +1,153 @@
+"""ctypes face of the CPU oracle (oracle.cpp).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this module; the
+HIP library and its Python binding never do.  Arrays are numpy, host memory.
+"""
+import ctypes as C
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import build as _build
+
+F_OVERFLOW, F_NONFINITE, F_EXHAUSTED = 1, 2, 4
+
+
+class _Result(C.Structure):
+    _fields_ = [("nnz", C.c_uint32), ("rounds", C.c_uint32), ("count", C.c_uint32 * 4),
+                ("flags", C.c_uint32), ("thres_f32", C.c_float), ("mean", C.c_double),
+                ("std", C.c_double), ("z", C.c_double), ("thres0", C.c_double),
+                ("thres", C.c_double), ("topk_key", C.c_uint32), ("topk_ties_taken", C.c_uint32)]
+
+
+@dataclass
+class Result:
+    nnz: int
+    rounds: int
+    count: tuple
+    flags: int
+    thres_f32: np.float32
+    mean: float
+    std: float
+    z: float
+    thres0: float
+    thres: float
+    topk_key: int
+    topk_ties_taken: int
+
+    @staticmethod
+    def of(r: _Result) -> "Result":
+        return Result(r.nnz, r.rounds, tuple(r.count), r.flags, np.float32(r.thres_f32), r.mean,
+                      r.std, r.z, r.thres0, r.thres, r.topk_key, r.topk_ties_taken)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(_build.ensure_built())
+        fp, up, ip = C.POINTER(C.c_float), C.POINTER(C.c_uint32), C.POINTER(C.c_int64)
+        L.oracle_accumulate.argtypes = [C.c_int64, fp, fp, fp]
+        L.oracle_accumulate.restype = None
+        L.oracle_moments.argtypes = [C.c_int64, fp, C.c_int32, C.POINTER(C.c_double),
+                                     C.POINTER(C.c_double)]
+        L.oracle_moments.restype = None
+        L.oracle_norm_isf.argtypes = [C.c_double]
+        L.oracle_norm_isf.restype = C.c_double
+        L.oracle_sqnorm.argtypes = [C.c_int64, fp]
+        L.oracle_sqnorm.restype = C.c_double
+        L.oracle_topk.argtypes = [C.c_int64, C.c_int64, fp, up, fp, fp, C.POINTER(_Result)]
+        L.oracle_gaussiank.argtypes = [C.c_int64, C.c_int64, fp, C.c_int64, C.c_double, C.c_int32,
+                                       up, fp, fp, C.POINTER(_Result)]
+        L.oracle_randk_dense.argtypes = [C.c_int64, C.c_int64, fp, up, fp]
+        L.oracle_segmented.argtypes = [C.c_int32, ip, ip, C.c_int32, fp, ip, C.c_double, C.c_int32,
+                                       up, fp, fp, C.POINTER(_Result)]
+        _lib = L
+    return _lib
+
+
+def _f(a):
+    assert a.dtype == np.float32 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def _u(a):
+    assert a.dtype == np.uint32 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.POINTER(C.c_uint32))
+
+
+def _i(a):
+    assert a.dtype == np.int64 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+def accumulate(g: np.ndarray, eps: np.ndarray) -> np.ndarray:
+    acc = np.empty_like(g)
+    lib().oracle_accumulate(g.size, _f(g), _f(eps), _f(acc))
+    return acc
+
+
+def moments(acc: np.ndarray, ddof: int = 1):
+    m, s = C.c_double(), C.c_double()
+    lib().oracle_moments(acc.size, _f(acc), ddof, C.byref(m), C.byref(s))
+    return m.value, s.value
+
+
+def norm_isf(q: float) -> float:
+    return lib().oracle_norm_isf(q)
+
+
+def sqnorm(x: np.ndarray) -> float:
+    return lib().oracle_sqnorm(x.size, _f(x))
+
+
+def topk(acc: np.ndarray, k: int):
+    """-> (idx[k] ascending, val[k], eps_out[d], Result)"""
+    idx = np.empty(max(k, 1), np.uint32)
+    val = np.empty(max(k, 1), np.float32)
+    eps = np.empty_like(acc)
+    r = _Result()
+    rc = lib().oracle_topk(acc.size, k, _f(acc), _u(idx), _f(val), _f(eps), C.byref(r))
+    if rc != 0:
+        raise ValueError("oracle_topk: invalid arguments")
+    return idx[:r.nnz], val[:r.nnz], eps, Result.of(r)
+
+
+def gaussiank(acc: np.ndarray, k: int, cap: int = None, tail_div: float = 2.0, ddof: int = 1):
+    """-> (idx[nnz] ascending, val[nnz], eps_out[d], Result)"""
+    cap = acc.size if cap is None else cap
+    idx = np.empty(max(cap, 1), np.uint32)
+    val = np.empty(max(cap, 1), np.float32)
+    eps = np.empty_like(acc)
+    r = _Result()
+    rc = lib().oracle_gaussiank(acc.size, k, _f(acc), cap, tail_div, ddof, _u(idx), _f(val),
+                                _f(eps), C.byref(r))
+    if rc != 0:
+        raise ValueError("oracle_gaussiank: invalid arguments")
+    return idx[:r.nnz], val[:r.nnz], eps, Result.of(r)
+
+
+def randk_dense(acc: np.ndarray, chosen: np.ndarray) -> np.ndarray:
+    out = np.empty_like(acc)
+    rc = lib().oracle_randk_dense(acc.size, chosen.size, _f(acc), _u(chosen), _f(out))
+    if rc != 0:
+        raise ValueError("oracle_randk_dense: invalid arguments")
+    return out
+
+
+def segmented(acc: np.ndarray, seg_off: np.ndarray, seg_k: np.ndarray, mode: int,
+              out_off: np.ndarray, tail_div: float = 2.0, ddof: int = 1):
+    """-> (idx[out_off[-1]], val[...], eps_out[d], [Result]*L); segment l's pairs occupy
+    idx[out_off[l] : out_off[l] + results[l].nnz]."""
+    L = seg_k.size
+    idx = np.zeros(max(int(out_off[-1]), 1), np.uint32)
+    val = np.zeros(max(int(out_off[-1]), 1), np.float32)
+    eps = np.empty_like(acc)
+    res = (_Result * L)()
+    rc = lib().oracle_segmented(L, _i(seg_off), _i(seg_k), mode, _f(acc), _i(out_off), tail_div,
+                                ddof, _u(idx), _f(val), _f(eps), res)
+    if rc != 0:
+        raise ValueError("oracle_segmented: invalid arguments")
+    return idx, val, eps, [Result.of(res[l]) for l in range(L)]

@@ -1,0 +1,64 @@
+"""Compile the native parts in-tree.
+
+libsparsify.so  -- the HIP kernels and their C ABI (hipcc, gfx950 only)
+libsynth.so     -- the seeded input generator (plain C, host)
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
+LIB_SPARSIFY = os.path.join(HERE, "libsparsify.so")
+LIB_SYNTH = os.path.join(HERE, "libsynth.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+             "-ffp-contract=off", "-fno-fast-math", "-fno-gpu-flush-denormals-to-zero",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def _run(cmd, verbose):
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+
+
+def build_sparsify(verbose: bool = False) -> str:
+    srcs = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
+    _run([HIPCC, *HIP_FLAGS, "-I", INCLUDE, "-I", CSRC, *srcs, "-o", LIB_SPARSIFY], verbose)
+    return LIB_SPARSIFY
+
+
+def build_synth(verbose: bool = False) -> str:
+    _run(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", os.path.join(CSRC, "synth.c"),
+          "-o", LIB_SYNTH, "-lm"], verbose)
+    return LIB_SYNTH
+
+
+def build_all(verbose: bool = False) -> None:
+    build_synth(verbose)
+    build_sparsify(verbose)
+
+
+def _stale(lib, srcs):
+    return (not os.path.exists(lib)) or any(os.path.getmtime(s) > os.path.getmtime(lib)
+                                            for s in srcs)
+
+
+def ensure_synth() -> str:
+    if not os.path.exists(LIB_SYNTH):
+        build_synth()
+    return LIB_SYNTH
+
+
+def ensure_sparsify() -> str:
+    """Path of the built HIP library; builds it only if no built library is there."""
+    if not os.path.exists(LIB_SPARSIFY):
+        build_sparsify()
+    return LIB_SPARSIFY
+
+
+if __name__ == "__main__":
+    build_all(verbose=True)

@@ -1,0 +1,411 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (CPU only).
+
+Each test names the passage it pins.  None of the expected values comes from the oracle or
+from the HIP path: they are brute force on tiny inputs, closed forms, library routines
+(scipy's normal distribution, numpy's moments) or the tabulated quantiles in tests/golden.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy.stats import norm
+
+from oracle import oracle as O
+from paper_1911_08772_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def key_of(x):
+    return x.view(np.uint32) & np.uint32(0x7FFFFFFF)
+
+
+def brute_topk(acc, k):
+    """Definition of Top_k (Sec. 1) by a full stable sort: |.| descending, index ascending."""
+    key = key_of(acc).astype(np.int64)
+    order = np.lexsort((np.arange(acc.size), -key))
+    return np.sort(order[:k]).astype(np.uint32)
+
+
+def tiny_vectors(d, rng):
+    """Vectors with planted ties, zeros, +/- pairs, denormals, infinities."""
+    out = []
+    out.append(rng.standard_normal(d).astype(np.float32))
+    out.append(rng.integers(-3, 4, d).astype(np.float32))                 # many ties and zeros
+    v = rng.standard_normal(d).astype(np.float32)
+    v[rng.integers(0, d, max(1, d // 3))] = np.float32(1.5)
+    v[rng.integers(0, d, max(1, d // 3))] = np.float32(-1.5)              # +/- pairs tie in |.|
+    out.append(v)
+    w = (rng.integers(-4, 5, d) * np.float32(1e-45)).astype(np.float32)   # denormals, -0
+    w[rng.integers(0, d)] = np.float32(-0.0)
+    out.append(w)
+    out.append(np.zeros(d, np.float32))
+    u = rng.standard_normal(d).astype(np.float32)
+    u[rng.integers(0, d)] = np.float32(np.inf)
+    u[rng.integers(0, d)] = np.float32(-np.inf)
+    out.append(u)
+    return out
+
+
+# ---- P1/P2/P3: Top_k definition, exactly k survivors, residual identity ---------------------
+
+def test_topk_matches_brute_force_sort_on_tiny_vectors():
+    rng = np.random.default_rng(1)
+    cases = 0
+    for d in list(range(1, 33)) + [47, 64]:
+        for acc in tiny_vectors(d, rng):
+            for k in range(1, d + 1):
+                idx, val, eps, res = O.topk(acc, k)
+                want = brute_topk(acc, k)
+                assert res.nnz == k and idx.size == k
+                assert np.array_equal(idx, want), (d, k, acc)
+                assert np.array_equal(val.view(np.uint32), acc[want].view(np.uint32))
+                # key of the k-th and number of kept entries sharing it
+                kth = int(np.sort(key_of(acc))[::-1][k - 1])
+                assert res.topk_key == kth
+                assert res.topk_ties_taken == int(np.sum(key_of(acc[want]) == kth))
+                cases += 1
+    assert cases > 3000
+
+
+def check_residual_identity(acc, idx, val, eps):
+    """Eq. (2): acc == Comp_k(acc) + eps' elementwise, supports disjoint, eps' = +0 on the set."""
+    dense = np.zeros_like(acc)
+    dense[idx] = val
+    assert np.array_equal(val.view(np.uint32), acc[idx].view(np.uint32))
+    sel = np.zeros(acc.size, bool)
+    sel[idx] = True
+    assert np.array_equal(eps[sel].view(np.uint32), np.zeros(int(sel.sum()), np.uint32))
+    assert np.array_equal(eps[~sel].view(np.uint32), acc[~sel].view(np.uint32))
+    assert np.all((dense == 0) | (eps == 0))
+    finite = np.isfinite(acc)
+    assert np.array_equal((dense + eps)[finite], acc[finite])
+
+
+def test_residual_identity_topk_and_gaussiank():
+    rng = np.random.default_rng(2)
+    for d, k in [(1, 1), (7, 3), (1000, 10), (50_000, 50), (50_000, 5000)]:
+        acc = (rng.standard_normal(d) * 0.01).astype(np.float32)
+        idx, val, eps, res = O.topk(acc, k)
+        assert res.nnz == k
+        check_residual_identity(acc, idx, val, eps)
+        idx, val, eps, res = O.gaussiank(acc, k)
+        assert res.nnz == idx.size
+        check_residual_identity(acc, idx, val, eps)
+
+
+# ---- P4/P5: Eq. (4) -------------------------------------------------------------------------
+
+def test_topk_error_not_above_randk_error_and_randk_expectation():
+    d, k, draws = 10_000, 100, 2000
+    acc = synth.normal(d, 7, 0, 1.0)
+    norm2 = O.sqnorm(acc)
+    _, _, eps_top, _ = O.topk(acc, k)
+    err_top = O.sqnorm(eps_top)
+    rng = np.random.default_rng(3)
+    errs = np.empty(draws)
+    for t in range(draws):
+        chosen = rng.permutation(d)[:k].astype(np.uint32)
+        dense = O.randk_dense(acc, chosen)
+        errs[t] = O.sqnorm(acc - dense)
+        assert err_top <= errs[t]
+    want = (1.0 - k / d) * norm2
+    stderr = errs.std(ddof=1) / math.sqrt(draws)
+    assert abs(errs.mean() - want) < 3.5 * stderr, (errs.mean(), want, stderr)
+    # the norm helper itself against numpy
+    assert math.isclose(norm2, float(np.sum(acc.astype(np.float64) ** 2)), rel_tol=1e-12)
+
+
+# ---- P6: Theorem 1 and the Gaussian closed form of the error ratio (Sec. 4.2 experiment) -----
+
+@pytest.mark.parametrize("rho", [0.001, 0.01, 0.1, 0.5])
+def test_topk_error_ratio_on_gaussian_vector(rho):
+    d = 100_000
+    k = int(round(rho * d))
+    u = synth.normal(d, 11, 0, 1.0)
+    _, _, eps, _ = O.topk(u, k)
+    ratio = O.sqnorm(eps) / O.sqnorm(u)
+    assert ratio <= (1 - k / d) ** 2 <= (1 - k / d)
+    # E[x^2 1{|x|<t}] = P(|x|<t) - 2 t pdf(t) with t the two-sided quantile
+    t = norm.isf(rho / 2)
+    closed = (1 - rho) - 2 * t * norm.pdf(t)
+    assert abs(ratio - closed) < 0.01, (ratio, closed)
+
+
+# ---- P7: normal quantile --------------------------------------------------------------------
+
+def test_norm_isf_against_tabulated_values_and_library():
+    rows = [ln.split("#")[0].split() for ln in open(os.path.join(GOLDEN, "normal_quantiles.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    assert len(rows) >= 15
+    for q, z in rows:
+        got = O.norm_isf(float(q))
+        assert math.isclose(got, float(z), rel_tol=2e-15), (q, got, z)
+    for q in np.concatenate([np.logspace(-12, -0.31, 60), [0.5, 0.6, 0.9, 0.999]]):
+        got, want = O.norm_isf(float(q)), float(norm.isf(q))
+        assert math.isclose(got, want, rel_tol=1e-11, abs_tol=1e-15), (q, got, want)
+        if 0 < q < 1:
+            assert math.isclose(float(norm.sf(got)), q, rel_tol=1e-12)
+    assert O.norm_isf(0.5) == 0.0
+    assert O.norm_isf(1.0) == -math.inf and O.norm_isf(0.0) == math.inf
+
+
+# ---- P8: moments ----------------------------------------------------------------------------
+
+def test_moments_closed_form_arithmetic_progression():
+    # x_j = a + j*h, j = 0..d-1: mean = a + (d-1)h/2, sum of squared deviations = h^2 d (d^2-1)/12
+    d, a, h = 40_001, 0.25, 2.0 ** -9
+    x = (a + np.arange(d) * h).astype(np.float32)
+    assert np.array_equal(x.astype(np.float64), a + np.arange(d) * h)  # exactly representable
+    for ddof in (0, 1):
+        mean, std = O.moments(x, ddof)
+        assert mean == a + (d - 1) * h / 2
+        var = Fraction(h) ** 2 * d * (d * d - 1) / 12 / (d - ddof)
+        assert math.isclose(std, math.sqrt(var), rel_tol=1e-13)
+
+
+def test_moments_against_numpy_and_one_pass():
+    rng = np.random.default_rng(5)
+    x = (3.0 + 0.01 * rng.standard_normal(200_000)).astype(np.float32)
+    x64 = x.astype(np.float64)
+    for ddof in (0, 1):
+        mean, std = O.moments(x, ddof)
+        assert math.isclose(mean, math.fsum(x64) / x.size, rel_tol=1e-13)
+        assert math.isclose(std, float(np.std(x64, ddof=ddof)), rel_tol=1e-11)
+        s1, s2 = math.fsum(x64), math.fsum(x64 * x64)
+        one_pass = math.sqrt((s2 - s1 * s1 / x.size) / (x.size - ddof))
+        assert math.isclose(std, one_pass, rel_tol=1e-7)
+    assert O.moments(np.float32([2.5]), 1) == (2.5, 0.0)
+
+
+# ---- Algorithm 1: the count-and-nudge walk on vectors whose counts are known exactly ---------
+
+def two_level_vector(d, levels, small=2.0 ** -12):
+    """+/- `small` everywhere except, for each (count, magnitude) in levels, `count` entries of
+    that magnitude with alternating sign.  Returns the vector and its exact population moments."""
+    x = np.full(d, small, np.float32)
+    x[1::2] = -small
+    pos = 0
+    for cnt, mag in levels:
+        x[pos:pos + cnt] = mag
+        x[pos + 1:pos + cnt:2] = -mag
+        pos += cnt
+    xs = [Fraction(float(v)) for v in np.unique(x)]
+    cnts = [int(np.sum(x == np.float32(float(v)))) for v in xs]
+    mean = sum(c * v for c, v in zip(cnts, xs)) / d
+    m2 = sum(c * (v - mean) ** 2 for c, v in zip(cnts, xs))
+    return x, mean, m2
+
+
+def expected_walk(x, k, thres0):
+    """Alg. 1 steps 5-13 replayed with exact arithmetic on the known level structure."""
+    mags = np.abs(x.astype(np.float64))
+    counts, t = [], thres0
+    for rnd in range(4):
+        t32 = float(np.float32(t))
+        est = int(np.sum(mags > t32))
+        counts.append(est)
+        last = t
+        if 3 * est < 2 * k:
+            nxt = 0.5 * t
+        elif 3 * est > 4 * k:
+            nxt = 1.5 * t
+        else:
+            return counts, last, True
+        if rnd < 3:
+            t = nxt
+    return counts, last, False
+
+
+@pytest.mark.parametrize("k,levels,want_counts,want_rounds,want_exhausted", [
+    # (the bulk of the vector sits at +/-2^-12 for the first case, +/-0.3125 for the others, so
+    # that the standard deviation puts the starting threshold where the comment says)
+    # first count too large -> x1.5 lands between the levels -> in band at round 2
+    (90, [(100, 10.0), (400, 1.0)], [500, 100], 2, False),
+    # x1.5, x1.5 overshoots to zero, x0.5 comes back: four evaluations, last mask kept
+    (90, [(180, 2.0)], [180, 180, 0, 180], 4, True),
+    # band edges are inclusive: 2k/3 = 60 and 4k/3 = 120 both stop at once
+    (90, [(60, 2.0)], [60], 1, False),
+    (90, [(120, 2.0)], [120], 1, False),
+    (90, [(59, 2.0)], None, None, None),
+    (90, [(121, 2.0)], None, None, None),
+])
+def test_gaussiank_walk_on_level_vectors(k, levels, want_counts, want_rounds, want_exhausted):
+    d = 200_000
+    x, mean, m2 = two_level_vector(d, levels, 2.0 ** -12 if len(levels) == 2 else 0.3125)
+    std = math.sqrt(m2 / (d - 1))
+    z = float(norm.isf(k / (2.0 * d)))
+    thres0 = float(mean) + std * z
+    counts, last, in_band = expected_walk(x, k, thres0)
+    if want_counts is not None:
+        assert counts == want_counts and in_band == (not want_exhausted)
+    else:  # one outside the band edge: the first evaluation must NOT stop the walk
+        assert len(counts) > 1
+    idx, val, eps, res = O.gaussiank(x, k)
+    assert math.isclose(res.mean, float(mean), abs_tol=1e-18)
+    assert math.isclose(res.std, std, rel_tol=1e-10)  # sequential fp64 sums of d terms
+    assert math.isclose(res.z, z, rel_tol=1e-12)
+    assert math.isclose(res.thres0, thres0, rel_tol=1e-10)
+    assert res.rounds == len(counts)
+    assert list(res.count[:res.rounds]) == counts
+    assert list(res.count[res.rounds:]) == [0] * (4 - res.rounds)
+    assert math.isclose(res.thres, last, rel_tol=1e-10)
+    assert float(res.thres_f32) == float(np.float32(res.thres))
+    assert bool(res.flags & O.F_EXHAUSTED) == (not in_band)
+    # the mask is the one of the last evaluation
+    want_idx = np.nonzero(np.abs(x) > res.thres_f32)[0].astype(np.uint32)
+    assert res.nnz == counts[-1] == want_idx.size
+    assert np.array_equal(idx, want_idx)
+    check_residual_identity(x, idx, val, eps)
+
+
+def test_gaussiank_walk_on_uniform_grid_goes_down_up_down():
+    # x_j = j*h, j = -m..m: lighter tails than a Gaussian, so the quantile threshold starts
+    # above the maximum: count 0 -> x0.5 -> too many -> x1.5 -> 0 -> x0.5 -> too many.
+    m, h, k = 50_000, 2.0 ** -10, 100
+    d = 2 * m + 1
+    x = (np.arange(-m, m + 1) * h).astype(np.float32)
+    std = math.sqrt(Fraction(h) ** 2 * 2 * m * (m + 1) * (2 * m + 1) / 6 / (d - 1))
+    t0 = std * float(norm.isf(k / (2.0 * d)))
+    ts = [t0, 0.5 * t0, 1.5 * (0.5 * t0), 0.5 * (1.5 * (0.5 * t0))]
+    want = [2 * max(0, m - math.floor(float(np.float32(t)) / h)) for t in ts]
+    assert want[0] == 0 and want[2] == 0 and want[1] > 4 * k / 3 and want[3] > want[1]
+    idx, val, eps, res = O.gaussiank(x, k)
+    assert res.mean == 0.0 and math.isclose(res.std, std, rel_tol=1e-13)
+    assert res.rounds == 4 and list(res.count) == want
+    assert res.flags == O.F_EXHAUSTED
+    assert math.isclose(res.thres, ts[3], rel_tol=1e-12)
+    assert res.nnz == want[3]
+    check_residual_identity(x, idx, val, eps)
+
+
+def test_gaussiank_printed_quantile_oscillates_on_gaussian_data():
+    # With the quantile exactly as printed (1 - k/d) against the two-sided mask, a Gaussian
+    # vector gives about 2k, then (threshold x1.5) almost nothing, then (x0.5 -> 0.75 t) far
+    # too many, then (x1.5 -> 1.125 t) about k/2: expected counts follow from the normal tail.
+    d, k, sigma = 4_000_000, 4000, 1e-3
+    x = synth.normal(d, 13, 0, sigma)
+    z = float(norm.isf(k / d))
+    want = [2 * d * norm.sf(f * z) for f in (1.0, 1.5, 0.75, 1.125)]
+    _, _, _, res = O.gaussiank(x, k, tail_div=1.0)
+    assert res.rounds == 4 and (res.flags & O.F_EXHAUSTED)
+    for got, w in zip(res.count, want):
+        assert abs(got - w) < 6 * math.sqrt(w) + 0.02 * w + 3, (res.count, want)
+    assert math.isclose(res.thres / res.thres0, 1.125, rel_tol=1e-15)
+
+
+# ---- P9: ideal data -> one evaluation, count close to k -------------------------------------
+
+@pytest.mark.parametrize("d,rho_den,sigma", [(269_722, 1000, 0.01), (2_000_000, 1000, 1e-3),
+                                              (2_000_000, 100, 1e-3)])
+def test_gaussiank_on_gaussian_data_needs_one_evaluation(d, rho_den, sigma):
+    k = synth.k_of(d, rho_den)
+    x = synth.normal(d, 17, 0, sigma)
+    idx, val, eps, res = O.gaussiank(x, k)
+    assert res.rounds == 1 and res.flags == 0
+    assert abs(int(res.count[0]) - k) <= 5 * math.sqrt(k)
+    assert res.nnz == res.count[0]
+    assert math.isclose(res.z, float(norm.isf(k / (2.0 * d))), rel_tol=1e-13)
+    m, s = float(np.mean(x.astype(np.float64))), float(np.std(x.astype(np.float64), ddof=1))
+    assert math.isclose(res.thres0, m + s * res.z, rel_tol=1e-11)
+
+
+# ---- P10/P11: mask given the threshold; link between the two selectors -----------------------
+
+def test_gaussiank_mask_is_strict_fp32_compare_with_reported_threshold():
+    x = synth.student_t3(300_000, 19, 0, 1e-3)
+    for k in (30, 300, 3000):
+        idx, val, eps, res = O.gaussiank(x, k)
+        want = np.nonzero(np.abs(x) > np.float32(res.thres_f32))[0].astype(np.uint32)
+        assert np.array_equal(idx, want)
+        assert res.count[res.rounds - 1] == want.size == res.nnz
+        assert float(np.float32(res.thres)) == float(res.thres_f32)
+
+
+def test_thresholding_at_next_magnitude_reproduces_topk_when_no_tie():
+    x = synth.normal(100_000, 23, 0, 1.0)
+    mags = np.sort(np.abs(x))[::-1]
+    for k in (1, 10, 100, 5000):
+        assert mags[k - 1] > mags[k]
+        idx, _, _, res = O.topk(x, k)
+        want = np.nonzero(np.abs(x) > mags[k])[0].astype(np.uint32)
+        assert np.array_equal(idx, want)
+        assert res.topk_ties_taken == 1
+
+
+# ---- overflow rule, non-finite input, argument errors ---------------------------------------
+
+def test_gaussiank_overflow_selects_nothing_and_nan_input():
+    x = synth.normal(50_000, 29, 0, 1.0)
+    idx, val, eps, res = O.gaussiank(x, 50, cap=10)
+    assert res.flags & O.F_OVERFLOW and res.nnz == 0 and idx.size == 0
+    assert np.array_equal(eps.view(np.uint32), x.view(np.uint32))
+    y = x.copy()
+    y[123] = np.nan
+    idx, val, eps, res = O.gaussiank(y, 50)
+    assert res.flags & O.F_NONFINITE and res.flags & O.F_EXHAUSTED
+    assert res.rounds == 4 and res.nnz == 0 and list(res.count) == [0, 0, 0, 0]
+    assert np.array_equal(eps.view(np.uint32), y.view(np.uint32))
+    # Top_k ranks NaN (largest bit pattern) first, then Inf
+    y[7] = -np.inf
+    idx, val, _, _ = O.topk(y, 2)
+    assert list(idx) == [7, 123]
+
+
+def test_invalid_arguments_raise():
+    x = np.zeros(8, np.float32)
+    for k in (0, 9, -1):
+        with pytest.raises(ValueError):
+            O.topk(x, k)
+        with pytest.raises(ValueError):
+            O.gaussiank(x, k)
+    with pytest.raises(ValueError):
+        O.gaussiank(x, 1, tail_div=0.5)
+
+
+# ---- P12: segmented == flat routine on each segment -----------------------------------------
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_segmented_equals_flat_per_segment(mode):
+    sizes = np.array([64, 1, 1000, 37, 4096, 5000, 3], np.int64)
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    seg_k = np.maximum(1, (sizes + 99) // 100).astype(np.int64)
+    caps = np.maximum(4 * seg_k, 16)
+    caps[1] = 1
+    out_off = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+    x = np.empty(int(seg_off[-1]), np.float32)
+    for l in range(sizes.size):
+        x[seg_off[l]:seg_off[l + 1]] = synth.normal(int(sizes[l]), 31, l, 10.0 ** (-l))
+    idx, val, eps, results = O.segmented(x, seg_off, seg_k, mode, out_off)
+    for l in range(sizes.size):
+        a, b = int(seg_off[l]), int(seg_off[l + 1])
+        if mode == 0:
+            fi, fv, fe, fr = O.topk(x[a:b].copy(), int(seg_k[l]))
+        else:
+            fi, fv, fe, fr = O.gaussiank(x[a:b].copy(), int(seg_k[l]), cap=int(caps[l]))
+        assert results[l] == fr
+        o = int(out_off[l])
+        assert np.array_equal(idx[o:o + fr.nnz], fi + np.uint32(a))
+        assert np.array_equal(val[o:o + fr.nnz].view(np.uint32), fv.view(np.uint32))
+        assert np.array_equal(eps[a:b].view(np.uint32), fe.view(np.uint32))
+
+
+def test_gaussiank_compare_is_strict_on_constant_vectors():
+    # A constant vector has std 0, so the threshold equals the common value itself and the
+    # strict '>' of Alg. 1 step 6 selects nothing; '>=' would select everything.
+    for c in (0.0, 0.375, -0.375):
+        x = np.full(1000, c, np.float32)
+        idx, val, eps, res = O.gaussiank(x, 10)
+        assert res.mean == c and res.std == 0.0 and res.thres0 == c
+        assert res.rounds == 4 and res.flags == O.F_EXHAUSTED
+        if c == 0:      # thresholds 0, 0, 0, 0: |0| > 0 never holds
+            assert list(res.count) == [0, 0, 0, 0] and res.nnz == 0
+        elif c > 0:     # thresholds c, c/2, 3c/4, 9c/8: none, all, all, none
+            assert list(res.count) == [0, 1000, 1000, 0] and res.nnz == 0
+            assert res.thres == 1.125 * c
+        else:           # negative threshold: every |x| exceeds it, far above the band, x1.5 each time
+            assert list(res.count) == [1000] * 4 and res.nnz == 1000
+            assert res.thres == 3.375 * c
+        check_residual_identity(x, idx, val, eps)
