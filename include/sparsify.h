@@ -1,0 +1,143 @@
+/* sparsify.h -- C ABI of the MI355X (gfx950) gradient compressor.
+ *
+ * One call performs, for one worker and one iteration, the per-worker half of the
+ * error-compensated sparsified update (paper Eq. (2)):
+ *
+ *     acc  = grad + residual                    (accumulate, one fp32 add per element)
+ *     S    = Comp_k(acc)                        (Top_k of Sec. 1, or Gaussian_k of Algorithm 1)
+ *     out  = {(i, acc[i]) : i in S}             (compacted (index, value) pairs)
+ *     residual' = acc with the entries in S set to +0
+ *
+ * Every step runs in HIP kernels enqueued on the caller's stream; the calls return
+ * without synchronising and copy nothing to the host.
+ *
+ * Pointers.  Unless marked HOST, every pointer is a DEVICE pointer owned by the caller and
+ *   must be 16-byte aligned (`workspace` 256-byte).  The library allocates no device memory
+ *   and keeps no state between calls.  `grad` is only read.  `residual` holds eps on entry
+ *   and eps' on exit.  `acc` receives grad+residual; `acc == residual` is allowed (in-place
+ *   mode: the buffer then ends as eps').  Any other overlap between buffers is an error.
+ * Sizes.  1 <= k <= d < 2^31.  Indices are uint32 positions in the flat buffer.
+ * Output order.  Gaussian_k pairs come out in ascending index order; Top_k pairs in
+ *   unspecified order (treat them as a set).  Entries beyond `nnz` are not written.
+ * Errors.  Argument errors that the host can see return a non-zero sparsify_status before
+ *   anything is launched and touch no buffer.  Data-dependent conditions are reported in
+ *   sparsify_result.flags, never by the return code.
+ * Overlap.  Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef SPARSIFY_H_
+#define SPARSIFY_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPARSIFY_OK = 0,
+  SPARSIFY_E_INVALID = 1,   /* bad d/k/cap, null or misaligned pointer, forbidden overlap */
+  SPARSIFY_E_WORKSPACE = 2, /* workspace too small or misaligned */
+  SPARSIFY_E_LAUNCH = 3     /* the HIP runtime refused a launch */
+} sparsify_status;
+
+enum {
+  SPARSIFY_F_OVERFLOW = 1u,  /* more survivors than `cap`: nothing selected, residual' = acc */
+  SPARSIFY_F_NONFINITE = 2u, /* mean, std or threshold not finite */
+  SPARSIFY_F_EXHAUSTED = 4u, /* four count evaluations used, last one still outside the band */
+  SPARSIFY_F_BADSEGMENT = 8u /* segmented call: this segment's offsets or k are invalid;
+                                the segment is left untouched apart from acc */
+};
+
+/* Written on the stream; valid once the stream has been synchronised. */
+typedef struct {
+  uint32_t nnz;       /* pairs written */
+  uint32_t rounds;    /* Gaussian_k: count evaluations performed, 1..4.  Top_k: 0 */
+  uint32_t count[4];  /* Gaussian_k: estimated_k of each evaluation (Alg. 1, step 7) */
+  uint32_t flags;     /* SPARSIFY_F_* */
+  float thres_f32;    /* fp32 value the final mask compared against */
+  double mean, std;   /* Alg. 1 step 2 (std with divisor d - ddof) */
+  double z;           /* upper-tail normal quantile of k / (tail_div * d) */
+  double thres0;      /* mean + std * z (Alg. 1 step 4) */
+  double thres;       /* fp64 threshold of the evaluation that produced the mask */
+  uint32_t topk_key;        /* Top_k: bit pattern of the k-th largest |acc| */
+  uint32_t topk_ties_taken; /* Top_k: selected entries whose magnitude equals that one */
+} sparsify_result;
+
+/* HOST struct; pass NULL for the defaults. */
+typedef struct {
+  double tail_div; /* 2.0 (default): quantile 1 - k/(2d), consistent with the two-sided mask
+                      |acc| > thres of Alg. 1 step 6.  1.0: the quantile 1 - k/d as printed in
+                      Alg. 1 step 3.  Must be >= 1. */
+  int32_t ddof;    /* 1 (default): sample standard deviation; 0: population */
+  int32_t reserved;
+  void* trace;     /* NULL, or a sparsify_trace* to record per-kernel timings of this call */
+} sparsify_opts;
+
+/* Bytes of `workspace` needed for a vector of d_total elements in num_segments segments
+ * (1 for the flat calls).  Returns 0 for invalid arguments. */
+size_t sparsify_workspace_bytes(int64_t d_total, int32_t num_segments);
+
+/* Gaussian_k compressor (Algorithm 1; accumulate and residual of Eq. (2)).
+ *   d, k      vector length and target number of survivors
+ *   grad      fp32[d], read only
+ *   residual  fp32[d], eps in / eps' out
+ *   acc       fp32[d], out (may equal residual)
+ *   out_idx   uint32[cap], out_val fp32[cap]; cap >= 1.  The method may select more or fewer
+ *             than k entries (Appendix A.5); if the final count exceeds cap nothing is selected
+ *             and SPARSIFY_F_OVERFLOW is set.
+ *   result    one sparsify_result
+ *   opts      HOST, may be NULL
+ *   stream    hipStream_t passed as void* (NULL = the default stream)                         */
+int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                       uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
+                       void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
+                       void* stream);
+
+/* Exact Top_k compressor (definition in Sec. 1: the k entries largest in absolute value;
+ * among equal magnitudes the lower index wins).  Same arguments; cap >= k is required; exactly
+ * k pairs are written.  opts: only `trace` is used. */
+int sparsify_topk(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                  uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
+                  void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
+                  void* stream);
+
+/* Layer-wise form: the flat compressor applied independently to each of num_segments
+ * contiguous segments of one flat buffer, all in one call.
+ *   d_total   length of grad/residual/acc; must equal seg_off[num_segments]
+ *   seg_off   int64[num_segments+1], DEVICE: segment l is [seg_off[l], seg_off[l+1]), seg_off[0]=0,
+ *             strictly increasing
+ *   seg_k     int64[num_segments], DEVICE: 1 <= seg_k[l] <= length of segment l
+ *   mode      0 = Top_k, 1 = Gaussian_k
+ *   out_off   int64[num_segments+1], DEVICE, non-decreasing: segment l's pairs are written from
+ *             out_idx[out_off[l]] and its capacity is out_off[l+1]-out_off[l]
+ *   out_cap   number of elements in out_idx / out_val (>= out_off[num_segments])
+ *   results   sparsify_result[num_segments]
+ * Indices are positions in the flat buffer.  The three layout arrays are read on the device
+ * only; a segment whose entries are invalid gets SPARSIFY_F_BADSEGMENT and produces nothing. */
+int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg_off,
+                       const int64_t* seg_k, int32_t mode, const float* grad, float* residual,
+                       float* acc, uint32_t* out_idx, float* out_val, const int64_t* out_off,
+                       int64_t out_cap, sparsify_result* results, void* workspace,
+                       size_t workspace_bytes, const sparsify_opts* opts, void* stream);
+
+/* Optional per-kernel timing of one call (used by the benchmark for its roofline figure).
+ * A trace owns HIP events (host objects, no device memory).  Pass it in sparsify_opts.trace;
+ * after the stream has been synchronised, read the stages of the most recent traced call. */
+typedef struct sparsify_trace sparsify_trace;
+sparsify_trace* sparsify_trace_create(void);
+void sparsify_trace_destroy(sparsify_trace* t);
+int32_t sparsify_trace_num_stages(const sparsify_trace* t);
+/* name of stage i (kernel name), valid until the next traced call */
+const char* sparsify_trace_stage_name(const sparsify_trace* t, int32_t i);
+/* duration of stage i in milliseconds, and the elements it processed per launch; returns
+ * SPARSIFY_E_INVALID if i is out of range or the events are not complete */
+int sparsify_trace_stage_ms(sparsify_trace* t, int32_t i, float* ms);
+
+/* Library version string (static storage). */
+const char* sparsify_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSIFY_H_ */

@@ -80,7 +80,8 @@ int oracle_topk(int64_t d, int64_t k, const float* acc, uint32_t* idx, float* va
   clear_result(res);
   // Total order: larger |acc| first; among equal magnitudes the lower index first.
   // Encoded as one descending 64-bit order: (key, ~index).
-  std::vector<uint64_t> order((size_t)d);
+  static thread_local std::vector<uint64_t> order;  // scratch kept between calls
+  order.resize((size_t)d);
   for (int64_t i = 0; i < d; ++i)
     order[(size_t)i] = ((uint64_t)mag_key(acc[i]) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)i);
   std::nth_element(order.begin(), order.begin() + (k - 1), order.end(), std::greater<uint64_t>());

@@ -83,8 +83,8 @@ def _i(a):
     return a.ctypes.data_as(C.POINTER(C.c_int64))
 
 
-def accumulate(g: np.ndarray, eps: np.ndarray) -> np.ndarray:
-    acc = np.empty_like(g)
+def accumulate(g: np.ndarray, eps: np.ndarray, out: np.ndarray = None) -> np.ndarray:
+    acc = np.empty_like(g) if out is None else out
     lib().oracle_accumulate(g.size, _f(g), _f(eps), _f(acc))
     return acc
 
@@ -103,11 +103,13 @@ def sqnorm(x: np.ndarray) -> float:
     return lib().oracle_sqnorm(x.size, _f(x))
 
 
-def topk(acc: np.ndarray, k: int):
-    """-> (idx[k] ascending, val[k], eps_out[d], Result)"""
-    idx = np.empty(max(k, 1), np.uint32)
-    val = np.empty(max(k, 1), np.float32)
-    eps = np.empty_like(acc)
+def topk(acc: np.ndarray, k: int, eps_out: np.ndarray = None, idx: np.ndarray = None,
+         val: np.ndarray = None):
+    """-> (idx[k] ascending, val[k], eps_out[d], Result); the optional arrays are reused as
+    output storage (idx/val need at least k entries)."""
+    idx = np.empty(max(k, 1), np.uint32) if idx is None else idx
+    val = np.empty(max(k, 1), np.float32) if val is None else val
+    eps = np.empty_like(acc) if eps_out is None else eps_out
     r = _Result()
     rc = lib().oracle_topk(acc.size, k, _f(acc), _u(idx), _f(val), _f(eps), C.byref(r))
     if rc != 0:
@@ -115,12 +117,14 @@ def topk(acc: np.ndarray, k: int):
     return idx[:r.nnz], val[:r.nnz], eps, Result.of(r)
 
 
-def gaussiank(acc: np.ndarray, k: int, cap: int = None, tail_div: float = 2.0, ddof: int = 1):
-    """-> (idx[nnz] ascending, val[nnz], eps_out[d], Result)"""
+def gaussiank(acc: np.ndarray, k: int, cap: int = None, tail_div: float = 2.0, ddof: int = 1,
+              eps_out: np.ndarray = None, idx: np.ndarray = None, val: np.ndarray = None):
+    """-> (idx[nnz] ascending, val[nnz], eps_out[d], Result); the optional arrays are reused as
+    output storage (idx/val need at least cap entries)."""
     cap = acc.size if cap is None else cap
-    idx = np.empty(max(cap, 1), np.uint32)
-    val = np.empty(max(cap, 1), np.float32)
-    eps = np.empty_like(acc)
+    idx = np.empty(max(cap, 1), np.uint32) if idx is None else idx
+    val = np.empty(max(cap, 1), np.float32) if val is None else val
+    eps = np.empty_like(acc) if eps_out is None else eps_out
     r = _Result()
     rc = lib().oracle_gaussiank(acc.size, k, _f(acc), cap, tail_div, ddof, _u(idx), _f(val),
                                 _f(eps), C.byref(r))
@@ -138,13 +142,14 @@ def randk_dense(acc: np.ndarray, chosen: np.ndarray) -> np.ndarray:
 
 
 def segmented(acc: np.ndarray, seg_off: np.ndarray, seg_k: np.ndarray, mode: int,
-              out_off: np.ndarray, tail_div: float = 2.0, ddof: int = 1):
+              out_off: np.ndarray, tail_div: float = 2.0, ddof: int = 1,
+              eps_out: np.ndarray = None):
     """-> (idx[out_off[-1]], val[...], eps_out[d], [Result]*L); segment l's pairs occupy
     idx[out_off[l] : out_off[l] + results[l].nnz]."""
     L = seg_k.size
     idx = np.zeros(max(int(out_off[-1]), 1), np.uint32)
     val = np.zeros(max(int(out_off[-1]), 1), np.float32)
-    eps = np.empty_like(acc)
+    eps = np.empty_like(acc) if eps_out is None else eps_out
     res = (_Result * L)()
     rc = lib().oracle_segmented(L, _i(seg_off), _i(seg_k), mode, _f(acc), _i(out_off), tail_div,
                                 ddof, _u(idx), _f(val), _f(eps), res)

@@ -1,0 +1,110 @@
+// Per-call initialisation of the control blocks: for the segmented call, validation of the
+// device-resident layout, the tile numbering of the segments and the per-segment quantiles.
+#pragma once
+#include "common.h"
+#include "gaussiank.h"
+
+namespace sp {
+
+__device__ inline void clear_result(sparsify_result& r) {
+  r.nnz = 0;
+  r.rounds = 0;
+  r.count[0] = r.count[1] = r.count[2] = r.count[3] = 0;
+  r.flags = 0;
+  r.thres_f32 = 0.0f;
+  r.mean = r.std = r.z = r.thres0 = r.thres = 0.0;
+  r.topk_key = 0;
+  r.topk_ties_taken = 0;
+}
+
+__global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    p[i] = v;
+}
+
+// Flat Top_k: reset the selection state and the histogram (one block of 256 threads).
+__global__ __launch_bounds__(kBlock) void k_topk_init_flat(const Args a) {
+  a.hist[threadIdx.x] = 0;
+  if (threadIdx.x == 0) {
+    SegCtrl& c = a.ctrl[0];
+    c.prefix = 0;
+    c.k_rem = (uint32_t)a.flat_k;
+    c.n_eq = 0;
+    c.rank_ties = 0;
+    c.cursor = 0;
+    c.select_none = 0;
+    c.bad = 0;
+    sparsify_result& r = a.result[0];
+    clear_result(r);
+    r.nnz = (uint32_t)a.flat_k;
+  }
+}
+
+// Segmented calls: one block walks the segments in chunks of kBlock.
+// mode 0 = Top_k, 1 = Gaussian_k.
+__global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
+  __shared__ uint32_t lds_scan[kWaves + 1];
+  uint32_t carry = 0;  // tiles numbered so far (block-uniform, saturating)
+  for (int base = 0; base < a.L; base += kBlock) {
+    const int s = base + (int)threadIdx.x;
+    uint32_t nt = 0;
+    bool bad = true;
+    int64_t start = 0, end = 0, k = 0, o0 = 0, o1 = 0;
+    if (s < a.L) {
+      start = a.seg_off[s];
+      end = a.seg_off[s + 1];
+      k = a.seg_k[s];
+      o0 = a.out_off[s];
+      o1 = a.out_off[s + 1];
+      bad = !(start >= 0 && end > start && end <= a.d_total && k >= 1 && k <= end - start &&
+              o0 >= 0 && o1 >= o0 && o1 <= a.out_cap);
+      if (s == 0 && start != 0) bad = true;
+      if (s == a.L - 1 && end != a.d_total) bad = true;
+      if (!bad) nt = seg_ntiles(start, end);
+    }
+    uint32_t total;
+    const uint32_t excl = block_exclusive_scan(nt, lds_scan, &total);
+    if (s < a.L) {
+      const uint32_t tile0 = carry + excl;
+      // a layout whose valid segments overlap could number more tiles than the workspace holds
+      if (!bad && (uint64_t)tile0 + nt > (uint64_t)a.max_tiles) bad = true;
+      a.tile_start[s] = tile0;
+      SegCtrl& c = a.ctrl[s];
+      c.start = start;
+      c.end = end;
+      c.k = k;
+      c.cap = o1 - o0;
+      c.out_base = o0;
+      c.tile0 = tile0;
+      c.ntiles = bad ? 0u : nt;
+      c.bad = bad ? 1u : 0u;
+      c.prefix = 0;
+      c.k_rem = (uint32_t)k;
+      c.n_eq = 0;
+      c.rank_ties = 0;
+      c.cursor = 0;
+      c.select_none = 0;
+      c.t_final = 0.0f;
+      sparsify_result& r = a.result[s];
+      clear_result(r);
+      if (bad) {
+        r.flags = SPARSIFY_F_BADSEGMENT;
+      } else if (mode == 0) {
+        if (c.cap < k) {
+          c.select_none = 1;
+          r.flags = SPARSIFY_F_OVERFLOW;
+        } else {
+          r.nnz = (uint32_t)k;
+        }
+      } else {
+        c.z = norm_isf((double)k / (a.tail_div * (double)(end - start)));
+      }
+    }
+    const uint64_t next = (uint64_t)carry + total;
+    carry = next > 0x40000000ull ? 0x40000000u : (uint32_t)next;
+  }
+  if (threadIdx.x == 0) a.tile_start[a.L] = carry;
+}
+
+}  // namespace sp

@@ -1,0 +1,299 @@
+// C ABI of the gfx950 gradient compressor: argument checks, workspace carving, kernel launches.
+// Nothing here touches device memory from the host or synchronises the stream.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+#include "gaussiank.h"
+#include "setup.h"
+#include "sparsify.h"
+#include "topk.h"
+
+using namespace sp;
+
+// ---- per-kernel timing (optional) -----------------------------------------------------------
+constexpr int kMaxStages = 24;
+struct sparsify_trace {
+  hipEvent_t ev[kMaxStages + 1];
+  const char* name[kMaxStages];
+  int n;
+  bool ok;
+};
+
+namespace {
+
+struct Launcher {
+  hipStream_t stream;
+  sparsify_trace* tr;
+  hipError_t err = hipSuccess;
+
+  void begin() {
+    if (tr) {
+      tr->n = 0;
+      note(hipEventRecord(tr->ev[0], stream));
+    }
+  }
+  void note(hipError_t e) {
+    if (err == hipSuccess && e != hipSuccess) err = e;
+  }
+  template <class K, class... A>
+  void run(const char* name, K kernel, dim3 grid, dim3 block, A... args) {
+    if (err != hipSuccess) return;
+    kernel<<<grid, block, 0, stream>>>(args...);
+    note(hipGetLastError());
+    if (tr && tr->n < kMaxStages) {
+      tr->name[tr->n] = name;
+      ++tr->n;
+      note(hipEventRecord(tr->ev[tr->n], stream));
+    }
+  }
+};
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+uint32_t max_tiles_of(int64_t d_total, int32_t L) {
+  // each segment adds at most two tiles over d/kTile (ragged head and tail)
+  return (uint32_t)(d_total / kTile + 2 * (int64_t)L + 1);
+}
+
+struct Carve {
+  size_t ctrl, tile_start, partial, tile_counts, tile_base, hist, total;
+};
+Carve carve(int64_t d_total, int32_t L) {
+  const size_t mt = max_tiles_of(d_total, L);
+  Carve c;
+  size_t off = 0;
+  c.ctrl = off;        off = align_up(off + sizeof(SegCtrl) * (size_t)L);
+  c.tile_start = off;  off = align_up(off + sizeof(uint32_t) * ((size_t)L + 1));
+  c.partial = off;     off = align_up(off + sizeof(double) * 3 * mt);
+  c.tile_counts = off; off = align_up(off + sizeof(uint32_t) * kNumThres * mt);
+  c.tile_base = off;   off = align_up(off + sizeof(uint32_t) * mt);
+  c.hist = off;        off = align_up(off + sizeof(uint32_t) * 256 * (size_t)L);
+  c.total = off;
+  return c;
+}
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+struct Range {
+  uintptr_t b, e;
+};
+Range range_of(const void* p, size_t bytes) {
+  return Range{reinterpret_cast<uintptr_t>(p), reinterpret_cast<uintptr_t>(p) + bytes};
+}
+bool overlap(Range x, Range y) { return x.b < y.e && y.b < x.e; }
+
+// Common checks of the buffers; fills the workspace pointers of `a`.
+int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* residual, float* acc,
+            uint32_t* out_idx, float* out_val, int64_t out_cap, sparsify_result* result,
+            void* workspace, size_t workspace_bytes, const sparsify_opts* opts) {
+  if (L < 1 || L > (1 << 20) || d_total < 1 || d_total >= (int64_t(1) << 31)) return SPARSIFY_E_INVALID;
+  if (!grad || !residual || !acc || !out_idx || !out_val || !result || out_cap < 1)
+    return SPARSIFY_E_INVALID;
+  if (misaligned(grad, 16) || misaligned(residual, 16) || misaligned(acc, 16) ||
+      misaligned(out_idx, 16) || misaligned(out_val, 16) || misaligned(result, 8))
+    return SPARSIFY_E_INVALID;
+  double tail_div = 2.0;
+  int32_t ddof = 1;
+  if (opts) {
+    tail_div = opts->tail_div;
+    ddof = opts->ddof;
+    if (!(tail_div >= 1.0) || !(tail_div <= 1e300) || (ddof != 0 && ddof != 1))
+      return SPARSIFY_E_INVALID;
+  }
+  const Carve cv = carve(d_total, L);
+  if (!workspace || misaligned(workspace, kAlign) || workspace_bytes < cv.total)
+    return SPARSIFY_E_WORKSPACE;
+
+  const size_t vec = sizeof(float) * (size_t)d_total;
+  const Range rg = range_of(grad, vec), rr = range_of(residual, vec), ra = range_of(acc, vec);
+  const Range ri = range_of(out_idx, 4 * (size_t)out_cap), rv = range_of(out_val, 4 * (size_t)out_cap);
+  const Range rs = range_of(result, sizeof(sparsify_result) * (size_t)L);
+  const Range rw = range_of(workspace, cv.total);
+  const bool inplace = (acc == residual);
+  const Range all[] = {rg, rr, ra, ri, rv, rs, rw};
+  for (int i = 0; i < 7; ++i)
+    for (int j = i + 1; j < 7; ++j) {
+      if (inplace && i == 1 && j == 2) continue;
+      if (overlap(all[i], all[j])) return SPARSIFY_E_INVALID;
+    }
+
+  char* w = static_cast<char*>(workspace);
+  std::memset(&a, 0, sizeof(a));
+  a.L = L;
+  a.inplace = inplace ? 1 : 0;
+  a.d_total = d_total;
+  a.out_cap = out_cap;
+  a.grad = grad;
+  a.resid = residual;
+  a.acc = acc;
+  a.out_idx = out_idx;
+  a.out_val = out_val;
+  a.result = result;
+  a.ctrl = reinterpret_cast<SegCtrl*>(w + cv.ctrl);
+  a.tile_start = reinterpret_cast<uint32_t*>(w + cv.tile_start);
+  a.partial = reinterpret_cast<double*>(w + cv.partial);
+  a.tile_counts = reinterpret_cast<uint32_t*>(w + cv.tile_counts);
+  a.tile_base = reinterpret_cast<uint32_t*>(w + cv.tile_base);
+  a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
+  a.max_tiles = max_tiles_of(d_total, L);
+  a.ddof = ddof;
+  a.tail_div = tail_div;
+  return SPARSIFY_OK;
+}
+
+uint32_t persistent_grid(uint32_t tiles) {
+  const uint32_t want = 2048;  // 256 CUs x 8 workgroups of 256 threads
+  return tiles < want ? (tiles ? tiles : 1u) : want;
+}
+
+template <bool SEG>
+void launch_gaussiank(Launcher& ln, const Args& a, uint32_t tiles) {
+  const dim3 blk(kBlock);
+  ln.run("accum_moments", k_accum_moments<SEG>, dim3(tiles), blk, a);
+  ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), blk, a);
+  ln.run("gk_count", k_gk_count<SEG>, dim3(tiles), blk, a);
+  ln.run("gk_decide", k_gk_decide<SEG>, dim3(a.L), blk, a);
+  ln.run("gk_compact", k_gk_compact<SEG>, dim3(tiles), blk, a);
+}
+
+template <bool SEG>
+void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
+  const dim3 blk(kBlock);
+  const dim3 pg(persistent_grid(tiles));
+  ln.run("topk_accum_hist", k_topk_accum_hist<SEG>, pg, blk, a);
+  ln.run("topk_select0", k_topk_select<SEG>, dim3(a.L), blk, a, 0);
+  ln.run("topk_hist1", k_topk_hist<SEG>, pg, blk, a, 1);
+  ln.run("topk_select1", k_topk_select<SEG>, dim3(a.L), blk, a, 1);
+  ln.run("topk_hist2", k_topk_hist<SEG>, pg, blk, a, 2);
+  ln.run("topk_select2", k_topk_select<SEG>, dim3(a.L), blk, a, 2);
+  ln.run("topk_hist3", k_topk_hist<SEG>, pg, blk, a, 3);
+  ln.run("topk_select3", k_topk_select<SEG>, dim3(a.L), blk, a, 3);
+  ln.run("topk_tie_count", k_topk_tie_count<SEG>, dim3(tiles), blk, a);
+  ln.run("topk_tie_scan", k_topk_tie_scan<SEG>, dim3(a.L), blk, a);
+  ln.run("topk_compact", k_topk_compact<SEG>, pg, blk, a);
+}
+
+int flat_call(bool gaussian, int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+              uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
+              void* workspace, size_t workspace_bytes, const sparsify_opts* opts, void* stream) {
+  if (k < 1 || k > d) return SPARSIFY_E_INVALID;
+  if (!gaussian && cap < k) return SPARSIFY_E_INVALID;
+  Args a;
+  const int rc = prepare(a, 1, d, grad, residual, acc, out_idx, out_val, cap, result, workspace,
+                         workspace_bytes, gaussian ? opts : nullptr);
+  if (rc != SPARSIFY_OK) return rc;
+  a.flat_k = k;
+  a.flat_cap = cap;
+  Launcher ln{static_cast<hipStream_t>(stream),
+              opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
+  ln.begin();
+  const uint32_t tiles = seg_ntiles(0, d);
+  if (gaussian) {
+    launch_gaussiank<false>(ln, a, tiles);
+  } else {
+    ln.run("topk_init", k_topk_init_flat, dim3(1), dim3(kBlock), a);
+    launch_topk<false>(ln, a, tiles);
+  }
+  if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);
+  return ln.err == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sparsify_version(void) { return "sparsify 0.1 (gfx950)"; }
+
+size_t sparsify_workspace_bytes(int64_t d_total, int32_t num_segments) {
+  if (d_total < 1 || d_total >= (int64_t(1) << 31) || num_segments < 1 || num_segments > (1 << 20))
+    return 0;
+  return carve(d_total, num_segments).total;
+}
+
+int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                       uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
+                       void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
+                       void* stream) {
+  return flat_call(true, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
+                   workspace_bytes, opts, stream);
+}
+
+int sparsify_topk(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                  uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
+                  void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
+                  void* stream) {
+  return flat_call(false, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
+                   workspace_bytes, opts, stream);
+}
+
+int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg_off,
+                       const int64_t* seg_k, int32_t mode, const float* grad, float* residual,
+                       float* acc, uint32_t* out_idx, float* out_val, const int64_t* out_off,
+                       int64_t out_cap, sparsify_result* results, void* workspace,
+                       size_t workspace_bytes, const sparsify_opts* opts, void* stream) {
+  if ((mode != 0 && mode != 1) || !seg_off || !seg_k || !out_off) return SPARSIFY_E_INVALID;
+  if (misaligned(seg_off, 8) || misaligned(seg_k, 8) || misaligned(out_off, 8))
+    return SPARSIFY_E_INVALID;
+  Args a;
+  const int rc = prepare(a, num_segments, d_total, grad, residual, acc, out_idx, out_val, out_cap,
+                         results, workspace, workspace_bytes, opts);
+  if (rc != SPARSIFY_OK) return rc;
+  a.seg_off = seg_off;
+  a.seg_k = seg_k;
+  a.out_off = out_off;
+  Launcher ln{static_cast<hipStream_t>(stream),
+              opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
+  ln.begin();
+  const uint32_t tiles = a.max_tiles;  // upper bound; surplus blocks exit at once
+  ln.run("seg_setup", k_seg_setup, dim3(1), dim3(kBlock), a, (int)mode);
+  if (mode == 1) {
+    launch_gaussiank<true>(ln, a, tiles);
+  } else {
+    const size_t n = (size_t)256 * (size_t)num_segments;
+    ln.run("hist_zero", k_fill_u32, dim3((unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024)),
+           dim3(256), a.hist, n, 0u);
+    launch_topk<true>(ln, a, tiles);
+  }
+  if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);
+  return ln.err == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;
+}
+
+sparsify_trace* sparsify_trace_create(void) {
+  sparsify_trace* t = new (std::nothrow) sparsify_trace();
+  if (!t) return nullptr;
+  t->n = 0;
+  t->ok = false;
+  for (int i = 0; i <= kMaxStages; ++i) {
+    if (hipEventCreate(&t->ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(t->ev[j]);
+      delete t;
+      return nullptr;
+    }
+  }
+  return t;
+}
+
+void sparsify_trace_destroy(sparsify_trace* t) {
+  if (!t) return;
+  for (int i = 0; i <= kMaxStages; ++i) (void)hipEventDestroy(t->ev[i]);
+  delete t;
+}
+
+int32_t sparsify_trace_num_stages(const sparsify_trace* t) { return t ? t->n : 0; }
+
+const char* sparsify_trace_stage_name(const sparsify_trace* t, int32_t i) {
+  return (t && i >= 0 && i < t->n) ? t->name[i] : "";
+}
+
+int sparsify_trace_stage_ms(sparsify_trace* t, int32_t i, float* ms) {
+  if (!t || !ms || i < 0 || i >= t->n || !t->ok) return SPARSIFY_E_INVALID;
+  return hipEventElapsedTime(ms, t->ev[i], t->ev[i + 1]) == hipSuccess ? SPARSIFY_OK
+                                                                       : SPARSIFY_E_INVALID;
+}
+
+}  // extern "C"

@@ -34,6 +34,14 @@ static inline double normal01(uint64_t w0, uint64_t w1) {
   return sqrt(-2.0 * log(u_open0(w0))) * cos(two_pi * u_half(w1));
 }
 
+/* two independent standard normals from two words (both Box-Muller branches) */
+static inline void normal01_pair(uint64_t w0, uint64_t w1, double* a, double* b) {
+  const double two_pi = 6.283185307179586476925286766559;
+  const double r = sqrt(-2.0 * log(u_open0(w0))), t = two_pi * u_half(w1);
+  *a = r * cos(t);
+  *b = r * sin(t);
+}
+
 /* out[i] = sigma * N(0,1), i = 0..n-1, counters index0+i */
 void synth_normal(float* out, int64_t n, uint64_t seed, uint64_t stream, int64_t index0,
                   double sigma) {
@@ -61,10 +69,9 @@ void synth_student_t3(float* out, int64_t n, uint64_t seed, uint64_t stream, int
 #pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < n; ++i) {
     uint64_t c = (uint64_t)(index0 + i);
-    double z = normal01(word(seed, stream, c, 0), word(seed, stream, c, 1));
-    double a = normal01(word(seed, stream, c, 2), word(seed, stream, c, 3));
-    double b = normal01(word(seed, stream, c, 4), word(seed, stream, c, 5));
-    double e = normal01(word(seed, stream, c, 6), word(seed, stream, c, 7));
+    double z, a, b, e;
+    normal01_pair(word(seed, stream, c, 0), word(seed, stream, c, 1), &z, &a);
+    normal01_pair(word(seed, stream, c, 2), word(seed, stream, c, 3), &b, &e);
     out[i] = (float)(scale * z / sqrt((a * a + b * b + e * e) / 3.0));
   }
 }

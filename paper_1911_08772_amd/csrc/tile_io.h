@@ -1,0 +1,68 @@
+// Per-thread tile loads and stores.  Thread `tid` owns, in each of the kSlots slots, the four
+// consecutive elements starting at tbase + (slot*kBlock + tid)*4, so one wave instruction covers
+// 1 KiB of contiguous memory.  The FULL variants use aligned 16-byte accesses; the others
+// predicate every element against the tile's valid range [lo, hi).
+#pragma once
+#include "common.h"
+
+namespace sp {
+
+__device__ inline int64_t slot_index(const Tile& t, int slot) {
+  return t.tbase + (int64_t)(slot * kBlock + (int)threadIdx.x) * 4;
+}
+
+// returns the validity mask (bit e set if element e of this thread is inside the tile's range)
+template <bool FULL>
+__device__ inline uint32_t load_tile(const float* __restrict__ p, const Tile& t,
+                                     float (&v)[kPerThread]) {
+  if (FULL) {
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+      const float4 q = *reinterpret_cast<const float4*>(p + slot_index(t, j));
+      v[4 * j + 0] = q.x;
+      v[4 * j + 1] = q.y;
+      v[4 * j + 2] = q.z;
+      v[4 * j + 3] = q.w;
+    }
+    return 0xFFFFu;
+  }
+  uint32_t valid = 0;
+#pragma unroll
+  for (int j = 0; j < kSlots; ++j) {
+    const int64_t i0 = slot_index(t, j);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int64_t i = i0 + c;
+      const bool ok = (i >= t.lo) && (i < t.hi);
+      v[4 * j + c] = ok ? p[i] : 0.0f;
+      valid |= (ok ? 1u : 0u) << (4 * j + c);
+    }
+  }
+  return valid;
+}
+
+template <bool FULL>
+__device__ inline void store_tile(float* p, const Tile& t, const float (&v)[kPerThread],
+                                  uint32_t valid) {
+  if (FULL) {
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+      float4 q;
+      q.x = v[4 * j + 0];
+      q.y = v[4 * j + 1];
+      q.z = v[4 * j + 2];
+      q.w = v[4 * j + 3];
+      *reinterpret_cast<float4*>(p + slot_index(t, j)) = q;
+    }
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < kSlots; ++j) {
+    const int64_t i0 = slot_index(t, j);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if ((valid >> (4 * j + c)) & 1u) p[i0 + c] = v[4 * j + c];
+  }
+}
+
+}  // namespace sp

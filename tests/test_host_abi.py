@@ -1,0 +1,107 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every function that
+include/sparsify.h declares, sizes the workspace sensibly and rejects bad arguments before
+launching anything."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1911_08772_amd import sparsify as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sparsify.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sparsify_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert set(names) == set(S.EXPORTS), (names, S.EXPORTS)
+    for n in names:
+        assert getattr(S.lib, n) is not None
+    assert "gfx950" in S.version()
+
+
+def test_result_record_layout_matches_header():
+    assert S.RESULT_BYTES == 80
+    assert S.RESULT_DTYPE.fields["mean"][1] == 32 and S.RESULT_DTYPE.fields["topk_key"][1] == 72
+
+
+def test_workspace_bytes():
+    assert S.workspace_bytes(0, 1) == 0 and S.workspace_bytes(10, 0) == 0
+    assert S.workspace_bytes(1 << 31, 1) == 0
+    small, big = S.workspace_bytes(1000, 1), S.workspace_bytes(66_034_000, 1)
+    assert 0 < small < big < 4 * 1024 * 1024
+    assert S.workspace_bytes(25_557_032, 54) > S.workspace_bytes(25_557_032, 1)
+    assert small % 256 == 0 and big % 256 == 0
+
+
+BASE = 0x7000_0000_0000  # fake, 256-byte aligned "device" addresses; never dereferenced
+
+
+def flat_args(d=1000, k=10, cap=64, **over):
+    n = 4 * d
+    a = dict(d=d, k=k, grad=BASE, residual=BASE + (1 << 32), acc=BASE + (2 << 32),
+             out_idx=BASE + (3 << 32), out_val=BASE + (4 << 32), cap=cap,
+             result=BASE + (5 << 32), workspace=BASE + (6 << 32),
+             workspace_nbytes=S.workspace_bytes(max(d, 1), 1) if 0 < d < (1 << 31) else 1 << 20)
+    a.update(over)
+    return a, n
+
+
+@pytest.mark.parametrize("fn", [S.sparsify_gaussiank, S.sparsify_topk])
+def test_flat_calls_reject_bad_arguments_before_any_launch(fn):
+    def rc(**over):
+        a, _ = flat_args(**over)
+        return fn(a["d"], a["k"], a["grad"], a["residual"], a["acc"], a["out_idx"], a["out_val"],
+                  a["cap"], a["result"], a["workspace"], a["workspace_nbytes"], stream=0,
+                  check=False)
+    assert rc(d=0) == S.E_INVALID
+    assert rc(d=1 << 31) == S.E_INVALID
+    assert rc(k=0) == S.E_INVALID
+    assert rc(k=1001) == S.E_INVALID
+    assert rc(cap=0) == S.E_INVALID
+    assert rc(grad=0) == S.E_INVALID
+    assert rc(result=0) == S.E_INVALID
+    assert rc(grad=BASE + 4) == S.E_INVALID                       # misaligned
+    assert rc(acc=BASE + 8) == S.E_INVALID                        # acc overlaps grad
+    assert rc(residual=BASE + (2 << 32) + 16) == S.E_INVALID      # partial overlap acc/residual
+    assert rc(out_val=BASE + (3 << 32)) == S.E_INVALID            # out_val == out_idx
+    assert rc(workspace=0) == S.E_WORKSPACE
+    assert rc(workspace=BASE + (6 << 32) + 64) == S.E_WORKSPACE   # misaligned workspace
+    assert rc(workspace_nbytes=128) == S.E_WORKSPACE
+    if fn is S.sparsify_topk:
+        assert rc(k=100, cap=99) == S.E_INVALID                   # Top_k needs cap >= k
+
+
+def test_gaussiank_rejects_bad_options():
+    a, _ = flat_args()
+    for kw in (dict(tail_div=0.5), dict(tail_div=float("nan")), dict(ddof=2)):
+        rc = S.sparsify_gaussiank(a["d"], a["k"], a["grad"], a["residual"], a["acc"], a["out_idx"],
+                                  a["out_val"], a["cap"], a["result"], a["workspace"],
+                                  a["workspace_nbytes"], stream=0, check=False, **kw)
+        assert rc == S.E_INVALID
+
+
+def test_segmented_rejects_bad_arguments():
+    a, _ = flat_args()
+    seg = BASE + (7 << 32)
+
+    def rc(L=3, d=1000, mode=1, seg_off=seg, seg_k=seg + 4096, out_off=seg + 8192, **over):
+        b = dict(a)
+        b.update(over)
+        return S.sparsify_segmented(L, d, seg_off, seg_k, mode, b["grad"], b["residual"], b["acc"],
+                                    b["out_idx"], b["out_val"], out_off, b["cap"], b["result"],
+                                    b["workspace"], S.workspace_bytes(1000, 3), stream=0,
+                                    check=False)
+    assert rc(L=0) == S.E_INVALID
+    assert rc(mode=2) == S.E_INVALID
+    assert rc(seg_off=0) == S.E_INVALID
+    assert rc(seg_k=seg + 4) == S.E_INVALID
+    assert rc(d=0) == S.E_INVALID
+    assert rc(L=50) == S.E_WORKSPACE  # workspace sized for 3 segments
