@@ -116,3 +116,64 @@ def check_flat(selector, gpu: FlatGpu, g, eps_in, k, what="", **kw):
     assert_pairs_match(got, idx_o, val_o, what)
     assert same_bits(got["eps"], eps_o), what
     return eps_o
+
+
+class SegGpu:
+    """One layer-wise compressor instance: layout arrays resident on the device."""
+
+    def __init__(self, seg_off: np.ndarray, seg_k: np.ndarray, caps: np.ndarray,
+                 inplace: bool = False):
+        self.L = int(seg_k.size)
+        self.d = int(seg_off[-1])
+        self.seg_off, self.seg_k = seg_off.astype(np.int64), seg_k.astype(np.int64)
+        self.out_off = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+        self.out_cap = max(int(self.out_off[-1]), 1)
+        self.inplace = inplace
+        self.b = S.Buffers.allocate(self.d, self.out_cap, self.L, inplace, DEV)
+        self.grad = torch.empty(self.d, dtype=torch.float32, device=DEV)
+        self.d_seg_off = torch.from_numpy(self.seg_off).to(DEV)
+        self.d_seg_k = torch.from_numpy(self.seg_k).to(DEV)
+        self.d_out_off = torch.from_numpy(self.out_off).to(DEV)
+
+    def set_residual(self, eps: np.ndarray) -> None:
+        self.b.residual.copy_(torch.from_numpy(eps))
+
+    def step(self, mode: int, g: np.ndarray, **kw):
+        b = self.b
+        self.grad.copy_(torch.from_numpy(g))
+        b.out_idx.fill_(-1)
+        b.out_val.fill_(float("nan"))
+        S.sparsify_segmented(self.L, self.d, self.d_seg_off, self.d_seg_k, mode, self.grad,
+                             b.residual, b.acc, b.out_idx, b.out_val, self.d_out_off, self.out_cap,
+                             b.result, b.workspace, b.workspace_nbytes, **kw)
+        torch.cuda.synchronize()
+        return {"res": S.decode_results(b.result), "idx": b.out_idx.cpu().numpy(),
+                "val": b.out_val.cpu().numpy(), "eps": b.residual.cpu().numpy(),
+                "acc": None if self.inplace else b.acc.cpu().numpy()}
+
+
+def check_segmented(mode: int, gpu: SegGpu, g, eps_in, what="", **kw):
+    acc_o = O.accumulate(g, eps_in)
+    got = gpu.step(mode, g, **kw)
+    idx_o, val_o, eps_o, res_o = O.segmented(acc_o, gpu.seg_off, gpu.seg_k, mode, gpu.out_off,
+                                             tail_div=kw.get("tail_div", 2.0),
+                                             ddof=kw.get("ddof", 1))
+    if got["acc"] is not None:
+        assert same_bits(got["acc"], acc_o), what
+    for l in range(gpu.L):
+        w = f"{what} segment {l}"
+        res, ro = got["res"][l], res_o[l]
+        if mode == 1:
+            assert_gaussiank_result(res, ro, w)
+        else:
+            assert int(res["nnz"]) == ro.nnz and int(res["flags"]) == ro.flags, (w, res, ro)
+            assert int(res["topk_key"]) == ro.topk_key, (w, res, ro)
+            assert int(res["topk_ties_taken"]) == ro.topk_ties_taken, (w, res, ro)
+        o0, o1, n = int(gpu.out_off[l]), int(gpu.out_off[l + 1]), ro.nnz
+        gi, gv = got["idx"][o0:o0 + n].view(np.uint32), got["val"][o0:o0 + n]
+        order = np.argsort(gi, kind="stable")
+        assert np.array_equal(gi[order], idx_o[o0:o0 + n]), w
+        assert same_bits(gv[order], val_o[o0:o0 + n]), w
+        assert np.all(got["idx"][o0 + n:o1] == -1), w  # nothing beyond nnz in this range
+    assert same_bits(got["eps"], eps_o), what
+    return eps_o

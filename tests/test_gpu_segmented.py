@@ -1,0 +1,107 @@
+"""GPU parity of the layer-wise call: ragged, misaligned and tiny segments, k_l = 1, segments
+that overflow their output range, invalid layouts, and the 54-segment ResNet-50-sized workload."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_harness import SegGpu, check_segmented, progress, same_bits
+from paper_1911_08772_amd import sparsify as S
+from paper_1911_08772_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def layout(sizes, rho_den=100, cap_mult=4):
+    sizes = np.asarray(sizes, np.int64)
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    seg_k = np.maximum(1, (sizes + rho_den - 1) // rho_den).astype(np.int64)
+    caps = np.maximum(cap_mult * seg_k, 16).astype(np.int64)
+    return seg_off, seg_k, caps
+
+
+def seg_grad(seg_off, seed, step, sigmas):
+    g = np.empty(int(seg_off[-1]), np.float32)
+    for l in range(len(sigmas)):
+        a, b = int(seg_off[l]), int(seg_off[l + 1])
+        synth.normal(b - a, seed, step, float(sigmas[l]), g[a:b], index0=a)
+    return g
+
+
+SMALL_LAYOUTS = [
+    [64, 1, 1000, 37, 4096, 5000, 3],
+    [1],
+    [4096, 4096, 4096],
+    [4095, 4097, 1, 1, 1, 8191, 2],
+    [3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37, 41, 43, 47, 53, 59, 61, 67, 71, 73] * 15,
+    [100_000, 7, 250_001, 64],
+]
+
+
+@pytest.mark.parametrize("inplace", [False, True])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_small_layouts(mode, inplace):
+    for n, sizes in enumerate(SMALL_LAYOUTS):
+        seg_off, seg_k, caps = layout(sizes)
+        sig = 10.0 ** (-(np.arange(len(sizes)) % 5))
+        gpu = SegGpu(seg_off, seg_k, caps, inplace)
+        eps = np.zeros(int(seg_off[-1]), np.float32)
+        for step in range(3):
+            g = seg_grad(seg_off, 300 + n, step, sig)
+            gpu.set_residual(eps)
+            eps = check_segmented(mode, gpu, g, eps, what=f"layout {n} mode {mode} step {step}")
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_ties_and_output_ranges_too_small(mode):
+    sizes = [500, 3000, 64, 9000]
+    seg_off, seg_k, caps = layout(sizes, rho_den=10)
+    caps[1] = 5        # Top_k: cap < k -> nothing; Gaussian_k: count > cap -> nothing
+    caps[2] = 0
+    rng = np.random.default_rng(4)
+    g = rng.integers(-3, 4, int(seg_off[-1])).astype(np.float32)   # heavy ties in every segment
+    gpu = SegGpu(seg_off, seg_k, caps)
+    eps = np.zeros_like(g)
+    check_segmented(mode, gpu, g, eps, what=f"ties mode {mode}")
+    res = S.decode_results(gpu.b.result)
+    if mode == 0:
+        assert res[1]["flags"] & S.F_OVERFLOW and res[1]["nnz"] == 0
+    # Gaussian data: the count (about k = 300) cannot fit a range of 5
+    g = synth.normal(int(seg_off[-1]), 6, 0, 1.0)
+    gpu.set_residual(eps)
+    check_segmented(mode, gpu, g, eps, what=f"overflow mode {mode}")
+    res = S.decode_results(gpu.b.result)
+    assert res[1]["flags"] & S.F_OVERFLOW and res[1]["nnz"] == 0
+    assert res[2]["flags"] & S.F_OVERFLOW and res[2]["nnz"] == 0
+    assert res[0]["nnz"] > 0 and res[3]["nnz"] > 0
+
+
+def test_invalid_segments_are_flagged_and_produce_nothing():
+    d = 10_000
+    seg_off = np.array([0, 3000, 2000, 10_000], np.int64)   # segment 1 runs backwards
+    seg_k = np.array([30, 10, 9000], np.int64)              # segment 2: k > length
+    caps = np.array([200, 200, 200], np.int64)
+    gpu = SegGpu(seg_off, seg_k, caps)
+    g = synth.normal(d, 5, 0, 1.0)
+    gpu.b.residual.zero_()
+    for mode in (0, 1):
+        out = gpu.step(mode, g)
+        assert out["res"][0]["flags"] == 0 and out["res"][0]["nnz"] > 0
+        for l in (1, 2):
+            assert out["res"][l]["flags"] == S.F_BADSEGMENT and out["res"][l]["nnz"] == 0
+        assert np.all(out["idx"][200:] == -1)
+        gpu.b.residual.zero_()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_cfg4_segmented_workload(mode):
+    """54 segments summing to d = 25,557,032, per-segment scales over three decades, all
+    segments in one launch, 20 error-feedback iterations."""
+    wl = synth.workload("cfg4_segmented")
+    caps = np.maximum(4 * wl.seg_k, 1024)
+    gpu = SegGpu(wl.seg_off, wl.seg_k, caps)
+    eps = np.zeros(wl.d, np.float32)
+    g = np.empty(wl.d, np.float32)
+    for step in range(wl.steps):
+        wl.grad(step, out=g)
+        eps = check_segmented(mode, gpu, g, eps, what=f"cfg4 mode {mode} step {step}")
+        progress(f"cfg4 mode {mode} step {step} ok")
