@@ -18,6 +18,12 @@ constexpr int kNumThres = 10;                     // thresholds reachable by <= 
 // Thresholds reachable from thres0 by `a` multiplications by 1.5 and `b` halvings, a+b <= 3
 // (Alg. 1 steps 8-11).  Halving is exact, so the value depends only on (a, b).
 __host__ __device__ inline int thres_index(int a, int b) { return (a + b) * (a + b + 1) / 2 + a; }
+// Position of threshold (a, b) when the ten are sorted by their ratio to thres0:
+// 1/8, 1/4, 3/8, 1/2, 3/4, 1, 9/8, 3/2, 9/4, 27/8.
+__host__ __device__ inline int thres_pos(int a, int b) {
+  // indexed by thres_index(a, b); packed 4 bits each: {5,3,7,1,4,8,0,2,6,9}
+  return (int)((0x9620841735ull >> (4 * thres_index(a, b))) & 0xF);
+}
 
 // One per segment, lives in the workspace; written by kernels, read by later kernels.
 struct SegCtrl {
@@ -29,16 +35,18 @@ struct SegCtrl {
   uint32_t pad0;
   // Gaussian_k
   double z;                 // upper-tail normal quantile of k / (tail_div * d)
-  double t64[kNumThres];
+  double t64[kNumThres];    // ascending order of nominal ratio (see thres_pos)
   float t32[kNumThres];
   float t_final;            // fp32 threshold of the mask-producing evaluation
   uint32_t select_none;     // overflow / bad: select nothing
+  uint32_t sorted_ok;       // the ten thresholds are in non-decreasing order (thres0 > 0)
+  uint32_t pad2;
   // Top_k
   uint32_t prefix;          // digits of the k-th key decided so far (high bits)
   uint32_t k_rem;           // survivors still to take among keys matching the prefix
   uint32_t n_eq;            // number of keys equal to the k-th key
   uint32_t rank_ties;       // 1 if only some of the equal keys are kept (needs index order)
-  uint32_t cursor;          // output slots handed out so far
+  uint32_t cursor;          // output slots handed out so far (starts after the ordered part)
   uint32_t pad1;
 };
 
@@ -59,10 +67,12 @@ struct Args {
   sparsify_result* result;
   SegCtrl* ctrl;
   uint32_t* tile_start;   // [L+1], segmented only
-  double* partial;        // [max_tiles][3]: n, mean, M2
-  uint32_t* tile_counts;  // [max_tiles][kNumThres]
+  double* partial;        // [3][max_tiles]: n, mean, M2
+  uint32_t* tile_counts;  // [kNumThres][max_tiles]
   uint32_t* tile_base;    // [max_tiles]
-  uint32_t* hist;         // [L][256]
+  uint32_t* hist;         // [L][hist_copies][256]
+  uint32_t* tie_base;     // [max_tiles]
+  uint32_t hist_copies;   // replicas of each segment's histogram (spreads the atomics)
   uint32_t max_tiles;
   int32_t ddof;
   double tail_div;
@@ -145,15 +155,16 @@ __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
   return v;
 }
 
-// Exclusive prefix sum over the workgroup in thread order; *total gets the block sum.
-// `lds` must hold kWaves + 1 words.  Contains two barriers.
+// Exclusive prefix sum over a workgroup of NW waves in thread order; *total gets the block
+// sum.  `lds` must hold NW words.  Contains two barriers.
+template <int NW = kWaves>
 __device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t* lds, uint32_t* total) {
   const uint32_t inc = wave_inclusive_scan(v);
   if (lane_id() == 63) lds[wave_id()] = inc;
   __syncthreads();
   uint32_t before = 0, all = 0;
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) {
+  for (int w = 0; w < NW; ++w) {
     const uint32_t s = lds[w];
     if (w < wave_id()) before += s;
     all += s;
@@ -161,6 +172,42 @@ __device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t* lds, uint3
   __syncthreads();
   *total = all;
   return before + inc - v;
+}
+
+// Workgroups of the per-segment finalising kernels: one block per segment reads thousands of
+// per-tile partials that other XCDs wrote, so every load pays a full trip to memory; they use
+// 1024 threads and issue their loads in unrolled batches to pay that latency once.
+constexpr int kFinBlock = 1024;
+constexpr int kFinWaves = kFinBlock / 64;
+
+// Ranks in index order (slots, then lanes, then the four components) of the elements of a tile
+// flagged in `sel` (bit e = element e of this thread).  first[j] receives the rank of this
+// thread's first flagged element of slot j; returns the number flagged in the whole tile.
+// One barrier; `lds` must hold kSlots * kWaves words and may be reused after the next barrier.
+__device__ inline uint32_t tile_rank(uint32_t sel, uint32_t* lds, uint32_t (&first)[kSlots]) {
+#pragma unroll
+  for (int j = 0; j < kSlots; ++j) {
+    uint32_t tot = 0, mine = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint64_t m = __ballot((sel >> (4 * j + q)) & 1u);
+      tot += (uint32_t)__builtin_popcountll(m);
+      mine += lanes_below(m);
+    }
+    first[j] = mine;
+    if (lane_id() == 0) lds[j * kWaves + wave_id()] = tot;
+  }
+  __syncthreads();
+  uint32_t run = 0;
+#pragma unroll
+  for (int j = 0; j < kSlots; ++j) {
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      if (w == wave_id()) first[j] += run;
+      run += lds[j * kWaves + w];
+    }
+  }
+  return run;
 }
 
 // Running (count, mean, sum of squared deviations) and its pairwise merge.

@@ -79,17 +79,16 @@ __device__ inline void accum_moments_tile(const Args& a, const Tile& t, uint32_t
     const double m2 = n > 0.0 ? s2 - s1 * (s1 / n) : 0.0;
     w[0] = n;
     w[1] = mean;
-    w[2] = m2 > 0.0 ? m2 : 0.0;
+    w[2] = m2 < 0.0 ? 0.0 : m2;  // rounding only; NaN stays NaN
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     Moments m = {lds[0], lds[1], lds[2]};
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) m = merge(m, Moments{lds[3 * w], lds[3 * w + 1], lds[3 * w + 2]});
-    double* out = a.partial + 3 * (size_t)tile_id;
-    out[0] = m.n;
-    out[1] = m.mean;
-    out[2] = m.m2;
+    a.partial[tile_id] = m.n;
+    a.partial[(size_t)a.max_tiles + tile_id] = m.mean;
+    a.partial[2 * (size_t)a.max_tiles + tile_id] = m.m2;
   }
 }
 
@@ -108,9 +107,24 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
 }
 
 // ---- K2: per segment, combine partials -> mean, std, threshold candidates -------------------
+// Two passes over the per-tile partials, no divisions per partial:
+//   N = sum n_i, mean = sum n_i mean_i / N, M2 = sum (M2_i + n_i (mean_i - mean)^2).
+__device__ inline double fin_block_sum(double v, double* lds) {
+  v = wave_sum(v);
+  __syncthreads();
+  if (lane_id() == 0) lds[wave_id()] = v;
+  __syncthreads();
+  double s = 0.0;
+#pragma unroll
+  for (int w = 0; w < kFinWaves; ++w) s += lds[w];
+  return s;
+}
+
+constexpr int kFinBatch = 8;  // partials per thread per round: 8192 tiles per round
+
 template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_gk_threshold(const Args a) {
-  __shared__ double lds[3 * kWaves];
+__global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
+  __shared__ double lds[kFinWaves];
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
   uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total);
@@ -121,54 +135,73 @@ __global__ __launch_bounds__(kBlock) void k_gk_threshold(const Args a) {
     ntiles = c.ntiles;
     n_seg = c.end - c.start;
   }
-  Moments m = {0.0, 0.0, 0.0};
-  for (uint32_t i = threadIdx.x; i < ntiles; i += kBlock) {
-    const double* p = a.partial + 3 * (size_t)(tile0 + i);
-    m = merge(m, Moments{p[0], p[1], p[2]});
-  }
+  const double* pn = a.partial + tile0;
+  const double* pm = pn + a.max_tiles;
+  const double* pq = pm + a.max_tiles;
+  double wsum = 0.0;
+  for (uint32_t base = 0; base < ntiles; base += kFinBlock * kFinBatch) {
+    double n[kFinBatch], mu[kFinBatch];
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {  // fixed-shape tree: lane i absorbs lane i+off
-    Moments o = {__shfl_down(m.n, off, 64), __shfl_down(m.mean, off, 64),
-                 __shfl_down(m.m2, off, 64)};
-    if ((lane_id() & (2 * off - 1)) == 0) m = merge(m, o);
+    for (int u = 0; u < kFinBatch; ++u) {
+      const uint32_t i = base + u * kFinBlock + threadIdx.x;
+      const bool ok = i < ntiles;
+      n[u] = ok ? pn[i] : 0.0;
+      mu[u] = ok ? pm[i] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < kFinBatch; ++u) wsum = fma(n[u], mu[u], wsum);
   }
-  if (lane_id() == 0) {
-    lds[3 * wave_id()] = m.n;
-    lds[3 * wave_id() + 1] = m.mean;
-    lds[3 * wave_id() + 2] = m.m2;
+  const double mean = fin_block_sum(wsum, lds) / (double)n_seg;
+  double dev = 0.0;
+  for (uint32_t base = 0; base < ntiles; base += kFinBlock * kFinBatch) {
+    double n[kFinBatch], mu[kFinBatch], q[kFinBatch];
+#pragma unroll
+    for (int u = 0; u < kFinBatch; ++u) {
+      const uint32_t i = base + u * kFinBlock + threadIdx.x;
+      const bool ok = i < ntiles;
+      n[u] = ok ? pn[i] : 0.0;
+      mu[u] = ok ? pm[i] : mean;
+      q[u] = ok ? pq[i] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < kFinBatch; ++u) {
+      const double dm = mu[u] - mean;
+      dev += fma(n[u] * dm, dm, q[u]);
+    }
   }
-  __syncthreads();
+  const double m2 = fin_block_sum(dev, lds);
   if (threadIdx.x != 0) return;
-  m = Moments{lds[0], lds[1], lds[2]};
-  for (int w = 1; w < kWaves; ++w) m = merge(m, Moments{lds[3 * w], lds[3 * w + 1], lds[3 * w + 2]});
 
-  const double denom = (double)(n_seg - a.ddof);
-  const double sd = (n_seg - a.ddof < 1) ? 0.0 : sqrt(m.m2 / denom);
+  const double sd = (n_seg - a.ddof < 1) ? 0.0 : sqrt(m2 / (double)(n_seg - a.ddof));
   const double z = c.z;
-  const double thres0 = m.mean + sd * z;
-  // candidate thresholds: `na` multiplications by 1.5 in sequence, then halvings (exact)
+  const double thres0 = mean + sd * z;
+  // candidate thresholds: `na` multiplications by 1.5 in sequence, then halvings (exact),
+  // stored in ascending order of their nominal ratio to thres0
   double up = thres0;
   for (int na = 0; na <= 3; ++na) {
     double v = up;
     for (int nb = 0; na + nb <= 3; ++nb) {
-      const int j = thres_index(na, nb);
-      c.t64[j] = v;
-      c.t32[j] = (float)v;
+      const int p = thres_pos(na, nb);
+      c.t64[p] = v;
+      c.t32[p] = (float)v;
       v = 0.5 * v;
     }
     up = 1.5 * up;
   }
+  c.sorted_ok = thres0 > 0.0 ? 1u : 0u;
   sparsify_result& r = a.result[s];
-  r.mean = m.mean;
+  r.mean = mean;
   r.std = sd;
   r.z = z;
   r.thres0 = thres0;
   uint32_t flags = 0;
-  if (!isfinite(m.mean) || !isfinite(sd) || !isfinite(thres0)) flags |= SPARSIFY_F_NONFINITE;
+  if (!isfinite(mean) || !isfinite(sd) || !isfinite(thres0)) flags |= SPARSIFY_F_NONFINITE;
   r.flags = flags;
 }
 
 // ---- K3: per tile, count |acc| > t for all ten candidate thresholds --------------------------
+// The thresholds sit in ascending order, so once no element of a wave's slot exceeds one of them
+// the larger ones need not be tested (only when the ordering is known to hold).
 template <bool FULL>
 __device__ inline void count_tile(const Args& a, const Tile& t, uint32_t tile_id, uint32_t* lds) {
   float v[kPerThread];
@@ -176,28 +209,59 @@ __device__ inline void count_tile(const Args& a, const Tile& t, uint32_t tile_id
   const SegCtrl& c = a.ctrl[t.seg];
   float thr[kNumThres];
 #pragma unroll
-  for (int j = 0; j < kNumThres; ++j) thr[j] = c.t32[j];
+  for (int p = 0; p < kNumThres; ++p) thr[p] = c.t32[p];
+  const bool can_skip = c.sorted_ok != 0;
   uint32_t cnt[kNumThres];
 #pragma unroll
-  for (int j = 0; j < kNumThres; ++j) cnt[j] = 0;
+  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
 #pragma unroll
-  for (int i = 0; i < kPerThread; ++i) {
-    const float m = fabsf(v[i]);
-    const bool ok = FULL || ((valid >> i) & 1u);
+  for (int j = 0; j < kSlots; ++j) {
+    float m[4];
+    bool ok[4];
 #pragma unroll
-    for (int j = 0; j < kNumThres; ++j)
-      cnt[j] += (uint32_t)__builtin_popcountll(__ballot(ok && (m > thr[j])));
+    for (int q = 0; q < 4; ++q) {
+      m[q] = fabsf(v[4 * j + q]);
+      ok[q] = FULL || ((valid >> (4 * j + q)) & 1u);
+    }
+    uint64_t any = 0;
+#pragma unroll
+    for (int p = 0; p < 5; ++p) {
+      any = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint64_t b = __ballot(ok[q] && (m[q] > thr[p]));
+        cnt[p] += (uint32_t)__builtin_popcountll(b);
+        any |= b;
+      }
+    }
+    if (!can_skip || any != 0) {
+      any = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint64_t b = __ballot(ok[q] && (m[q] > thr[5]));
+        cnt[5] += (uint32_t)__builtin_popcountll(b);
+        any |= b;
+      }
+      if (!can_skip || any != 0) {
+#pragma unroll
+        for (int p = 6; p < kNumThres; ++p) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            cnt[p] += (uint32_t)__builtin_popcountll(__ballot(ok[q] && (m[q] > thr[p])));
+        }
+      }
+    }
   }
   if (lane_id() == 0) {
 #pragma unroll
-    for (int j = 0; j < kNumThres; ++j) lds[wave_id() * kNumThres + j] = cnt[j];
+    for (int p = 0; p < kNumThres; ++p) lds[wave_id() * kNumThres + p] = cnt[p];
   }
   __syncthreads();
   if (threadIdx.x < kNumThres) {
     uint32_t s = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) s += lds[w * kNumThres + threadIdx.x];
-    a.tile_counts[(size_t)tile_id * kNumThres + threadIdx.x] = s;
+    a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile_id] = s;  // [threshold][tile]
   }
 }
 
@@ -212,11 +276,53 @@ __global__ __launch_bounds__(kBlock) void k_gk_count(const Args a) {
 }
 
 // ---- K4: per segment, total the counts, walk Alg. 1 steps 5-13, scan the chosen column -------
+constexpr int kScanPer = 8;                        // consecutive tiles per thread per scan round
+constexpr int kScanChunk = kFinBlock * kScanPer;   // 8192 tiles staged in LDS per round
+constexpr int kTotBatch = 4;
+
+// Exclusive prefix sum of col[0..n) into base[0..n) by one workgroup of kFinBlock threads;
+// returns the total.  `stage` holds kFinBlock*(kScanPer+1) words, `lds_scan` kFinWaves words.
+__device__ inline uint32_t scan_tiles(const uint32_t* col, uint32_t ntiles, uint32_t* base,
+                                      uint32_t* stage, uint32_t* lds_scan) {
+  uint32_t carry = 0;
+  for (uint32_t c0 = 0; c0 < ntiles; c0 += kScanChunk) {
+    const uint32_t n = (ntiles - c0 < (uint32_t)kScanChunk) ? ntiles - c0 : (uint32_t)kScanChunk;
+    uint32_t x[kScanPer];
+#pragma unroll
+    for (int u = 0; u < kScanPer; ++u) {  // coalesced loads, all in flight at once
+      const uint32_t i = u * kFinBlock + threadIdx.x;
+      x[u] = (i < n) ? col[c0 + i] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kScanPer; ++u) {  // +1 word per thread row: no bank conflicts
+      const uint32_t i = u * kFinBlock + threadIdx.x;
+      stage[(i / kScanPer) * (kScanPer + 1) + (i % kScanPer)] = x[u];
+    }
+    __syncthreads();
+    const uint32_t b = threadIdx.x * kScanPer;
+    const uint32_t* mine = stage + threadIdx.x * (kScanPer + 1);
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPer; ++i) sum += mine[i];
+    uint32_t total;
+    uint32_t run = carry + block_exclusive_scan<kFinWaves>(sum, lds_scan, &total);
+#pragma unroll
+    for (int i = 0; i < kScanPer; ++i) {
+      if (b + i < n) base[c0 + b + i] = run;
+      run += mine[i];
+    }
+    carry += total;
+    __syncthreads();
+  }
+  return carry;
+}
+
 template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_gk_decide(const Args a) {
-  __shared__ uint32_t lds_cnt[kWaves * kNumThres];
-  __shared__ uint32_t lds_scan[kWaves + 1];
+__global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
+  __shared__ uint32_t lds_cnt[kFinWaves * kNumThres];
+  __shared__ uint32_t lds_scan[kFinWaves];
   __shared__ uint32_t lds_final;
+  __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];  // +1 word per thread: no bank conflicts
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
   uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total);
@@ -230,37 +336,47 @@ __global__ __launch_bounds__(kBlock) void k_gk_decide(const Args a) {
   }
   uint32_t cnt[kNumThres];
 #pragma unroll
-  for (int j = 0; j < kNumThres; ++j) cnt[j] = 0;
-  for (uint32_t i = threadIdx.x; i < ntiles; i += kBlock) {
-    const uint32_t* p = a.tile_counts + (size_t)(tile0 + i) * kNumThres;
+  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
+  const uint32_t* cols = a.tile_counts + tile0;
+  for (uint32_t base = 0; base < ntiles; base += kFinBlock * kTotBatch) {
+    uint32_t x[kTotBatch][kNumThres];
 #pragma unroll
-    for (int j = 0; j < kNumThres; ++j) cnt[j] += p[j];
+    for (int u = 0; u < kTotBatch; ++u) {
+      const uint32_t i = base + u * kFinBlock + threadIdx.x;
+#pragma unroll
+      for (int p = 0; p < kNumThres; ++p)
+        x[u][p] = (i < ntiles) ? cols[(size_t)p * a.max_tiles + i] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kTotBatch; ++u)
+#pragma unroll
+      for (int p = 0; p < kNumThres; ++p) cnt[p] += x[u][p];
   }
 #pragma unroll
-  for (int j = 0; j < kNumThres; ++j) cnt[j] = wave_sum(cnt[j]);
+  for (int p = 0; p < kNumThres; ++p) cnt[p] = wave_sum(cnt[p]);
   if (lane_id() == 0) {
 #pragma unroll
-    for (int j = 0; j < kNumThres; ++j) lds_cnt[wave_id() * kNumThres + j] = cnt[j];
+    for (int p = 0; p < kNumThres; ++p) lds_cnt[wave_id() * kNumThres + p] = cnt[p];
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t tot[kNumThres];
-    for (int j = 0; j < kNumThres; ++j) {
-      tot[j] = 0;
-      for (int w = 0; w < kWaves; ++w) tot[j] += lds_cnt[w * kNumThres + j];
+    for (int p = 0; p < kNumThres; ++p) {
+      tot[p] = 0;
+      for (int w = 0; w < kFinWaves; ++w) tot[p] += lds_cnt[w * kNumThres + p];
     }
     sparsify_result& r = a.result[s];
-    int na = 0, nb = 0, j = 0;
+    int na = 0, nb = 0, p = 0;
     bool in_band = false;
     uint32_t rounds = 0;
-    for (int round = 0; round <= 3; ++round) {
-      j = thres_index(na, nb);
-      const int64_t est = tot[j];
-      r.count[round] = tot[j];
+    for (int round = 0; round <= 3; ++round) {  // "for i = 0 -> 3": four evaluations at most
+      p = thres_pos(na, nb);
+      const int64_t est = tot[p];
+      r.count[round] = tot[p];
       rounds = round + 1;
-      if (3 * est < 2 * k) {
+      if (3 * est < 2 * k) {          // estimated_k < 2k/3: halve the threshold
         if (round < 3) ++nb;
-      } else if (3 * est > 4 * k) {
+      } else if (3 * est > 4 * k) {   // estimated_k > 4k/3: threshold x 1.5
         if (round < 3) ++na;
       } else {
         in_band = true;
@@ -270,33 +386,22 @@ __global__ __launch_bounds__(kBlock) void k_gk_decide(const Args a) {
     for (uint32_t q = rounds; q < 4; ++q) r.count[q] = 0;
     uint32_t flags = r.flags;  // NONFINITE bit from the threshold kernel
     if (!in_band) flags |= SPARSIFY_F_EXHAUSTED;
-    const bool overflow = (int64_t)tot[j] > cap;
+    const bool overflow = (int64_t)tot[p] > cap;
     if (overflow) flags |= SPARSIFY_F_OVERFLOW;
     r.rounds = rounds;
     r.flags = flags;
-    r.thres = c.t64[j];
-    r.thres_f32 = c.t32[j];
-    r.nnz = overflow ? 0u : tot[j];
+    r.thres = c.t64[p];
+    r.thres_f32 = c.t32[p];
+    r.nnz = overflow ? 0u : tot[p];
     r.topk_key = 0;
     r.topk_ties_taken = 0;
-    c.t_final = c.t32[j];
+    c.t_final = c.t32[p];
     c.select_none = overflow ? 1u : 0u;
-    lds_final = (uint32_t)j;
+    lds_final = (uint32_t)p;
   }
   __syncthreads();
-  const uint32_t jf = lds_final;
-  // exclusive scan of column jf over this segment's tiles -> first output slot of each tile
-  const uint32_t per = (ntiles + kBlock - 1) / kBlock;
-  const uint32_t b = threadIdx.x * per;
-  const uint32_t e = (b + per < ntiles) ? b + per : ntiles;
-  uint32_t sum = 0;
-  for (uint32_t i = b; i < e; ++i) sum += a.tile_counts[(size_t)(tile0 + i) * kNumThres + jf];
-  uint32_t total;
-  uint32_t run = block_exclusive_scan(sum, lds_scan, &total);
-  for (uint32_t i = b; i < e; ++i) {
-    a.tile_base[tile0 + i] = run;
-    run += a.tile_counts[(size_t)(tile0 + i) * kNumThres + jf];
-  }
+  scan_tiles(a.tile_counts + tile0 + (size_t)lds_final * a.max_tiles, ntiles, a.tile_base + tile0,
+             stage, lds_scan);
 }
 
 // ---- K5: compaction in index order + residual (Alg. 1 step 14, Eq. (2)) ----------------------
@@ -314,41 +419,20 @@ __device__ inline void compact_tile(const Args& a, const Tile& t, uint32_t tile_
     const bool ok = FULL || ((valid >> i) & 1u);
     if (ok && !none && (fabsf(v[i]) > thr)) sel |= 1u << i;
   }
-  // rank of each survivor in index order: slots, then lanes, then the 4 components
-  uint32_t below[kSlots];
+  uint32_t first[kSlots];
+  tile_rank(sel, lds, first);
+  const int64_t out0 = (SEG ? c.out_base : 0) + (int64_t)a.tile_base[tile_id];
 #pragma unroll
   for (int j = 0; j < kSlots; ++j) {
-    uint32_t tot = 0, mine = 0;
+    uint32_t r = first[j];
+    const int64_t i0 = slot_index(t, j);
 #pragma unroll
     for (int cpt = 0; cpt < 4; ++cpt) {
-      const uint64_t m = __ballot((sel >> (4 * j + cpt)) & 1u);
-      tot += (uint32_t)__builtin_popcountll(m);
-      mine += lanes_below(m);
-    }
-    below[j] = mine;
-    if (lane_id() == 0) lds[j * kWaves + wave_id()] = tot;
-  }
-  __syncthreads();
-  const int64_t out0 = (SEG ? c.out_base : 0) + (int64_t)a.tile_base[tile_id];
-  uint32_t run = 0;
-#pragma unroll
-  for (int j = 0; j < kSlots; ++j) {
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const uint32_t x = lds[j * kWaves + w];
-      if (w == wave_id()) {
-        uint32_t r = run + below[j];
-        const int64_t i0 = slot_index(t, j);
-#pragma unroll
-        for (int cpt = 0; cpt < 4; ++cpt) {
-          if ((sel >> (4 * j + cpt)) & 1u) {
-            a.out_idx[out0 + r] = (uint32_t)(i0 + cpt);
-            a.out_val[out0 + r] = v[4 * j + cpt];
-            ++r;
-          }
-        }
+      if ((sel >> (4 * j + cpt)) & 1u) {
+        a.out_idx[out0 + r] = (uint32_t)(i0 + cpt);
+        a.out_val[out0 + r] = v[4 * j + cpt];
+        ++r;
       }
-      run += x;
     }
   }
   if (a.inplace) {

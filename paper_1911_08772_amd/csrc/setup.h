@@ -25,7 +25,7 @@ __global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
 
 // Flat Top_k: reset the selection state and the histogram (one block of 256 threads).
 __global__ __launch_bounds__(kBlock) void k_topk_init_flat(const Args a) {
-  a.hist[threadIdx.x] = 0;
+  for (uint32_t r = 0; r < a.hist_copies; ++r) a.hist[r * 256 + threadIdx.x] = 0;
   if (threadIdx.x == 0) {
     SegCtrl& c = a.ctrl[0];
     c.prefix = 0;

@@ -60,8 +60,11 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L) {
   return (uint32_t)(d_total / kTile + 2 * (int64_t)L + 1);
 }
 
+// replicas of each segment's global histogram: spreads same-address atomics of the flat call
+uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
+
 struct Carve {
-  size_t ctrl, tile_start, partial, tile_counts, tile_base, hist, total;
+  size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, hist, total;
 };
 Carve carve(int64_t d_total, int32_t L) {
   const size_t mt = max_tiles_of(d_total, L);
@@ -72,7 +75,8 @@ Carve carve(int64_t d_total, int32_t L) {
   c.partial = off;     off = align_up(off + sizeof(double) * 3 * mt);
   c.tile_counts = off; off = align_up(off + sizeof(uint32_t) * kNumThres * mt);
   c.tile_base = off;   off = align_up(off + sizeof(uint32_t) * mt);
-  c.hist = off;        off = align_up(off + sizeof(uint32_t) * 256 * (size_t)L);
+  c.tie_base = off;    off = align_up(off + sizeof(uint32_t) * mt);
+  c.hist = off;        off = align_up(off + sizeof(uint32_t) * 256 * (size_t)L * hist_copies_of(L));
   c.total = off;
   return c;
 }
@@ -139,7 +143,9 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.partial = reinterpret_cast<double*>(w + cv.partial);
   a.tile_counts = reinterpret_cast<uint32_t*>(w + cv.tile_counts);
   a.tile_base = reinterpret_cast<uint32_t*>(w + cv.tile_base);
+  a.tie_base = reinterpret_cast<uint32_t*>(w + cv.tie_base);
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
+  a.hist_copies = hist_copies_of(L);
   a.max_tiles = max_tiles_of(d_total, L);
   a.ddof = ddof;
   a.tail_div = tail_div;
@@ -155,9 +161,9 @@ template <bool SEG>
 void launch_gaussiank(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   ln.run("accum_moments", k_accum_moments<SEG>, dim3(tiles), blk, a);
-  ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), blk, a);
+  ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), dim3(kFinBlock), a);
   ln.run("gk_count", k_gk_count<SEG>, dim3(tiles), blk, a);
-  ln.run("gk_decide", k_gk_decide<SEG>, dim3(a.L), blk, a);
+  ln.run("gk_decide", k_gk_decide<SEG>, dim3(a.L), dim3(kFinBlock), a);
   ln.run("gk_compact", k_gk_compact<SEG>, dim3(tiles), blk, a);
 }
 
@@ -166,16 +172,17 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   const dim3 pg(persistent_grid(tiles));
   ln.run("topk_accum_hist", k_topk_accum_hist<SEG>, pg, blk, a);
-  ln.run("topk_select0", k_topk_select<SEG>, dim3(a.L), blk, a, 0);
-  ln.run("topk_hist1", k_topk_hist<SEG>, pg, blk, a, 1);
-  ln.run("topk_select1", k_topk_select<SEG>, dim3(a.L), blk, a, 1);
-  ln.run("topk_hist2", k_topk_hist<SEG>, pg, blk, a, 2);
-  ln.run("topk_select2", k_topk_select<SEG>, dim3(a.L), blk, a, 2);
-  ln.run("topk_hist3", k_topk_hist<SEG>, pg, blk, a, 3);
-  ln.run("topk_select3", k_topk_select<SEG>, dim3(a.L), blk, a, 3);
+  const dim3 fin(kFinBlock);
+  ln.run("topk_select0", k_topk_select<SEG>, dim3(a.L), fin, a, 0);
+  ln.run("topk_hist1", k_topk_hist<SEG, false>, pg, blk, a, 1);
+  ln.run("topk_select1", k_topk_select<SEG>, dim3(a.L), fin, a, 1);
+  ln.run("topk_hist2", k_topk_hist<SEG, false>, pg, blk, a, 2);
+  ln.run("topk_select2", k_topk_select<SEG>, dim3(a.L), fin, a, 2);
+  ln.run("topk_hist3", k_topk_hist<SEG, true>, pg, blk, a, 3);
+  ln.run("topk_select3", k_topk_select<SEG>, dim3(a.L), fin, a, 3);
   ln.run("topk_tie_count", k_topk_tie_count<SEG>, dim3(tiles), blk, a);
-  ln.run("topk_tie_scan", k_topk_tie_scan<SEG>, dim3(a.L), blk, a);
-  ln.run("topk_compact", k_topk_compact<SEG>, pg, blk, a);
+  ln.run("topk_tie_scan", k_topk_tie_scan<SEG>, dim3(a.L), fin, a);
+  ln.run("topk_compact", k_topk_compact<SEG>, dim3(tiles), blk, a);
 }
 
 int flat_call(bool gaussian, int64_t d, int64_t k, const float* grad, float* residual, float* acc,
@@ -254,7 +261,7 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   if (mode == 1) {
     launch_gaussiank<true>(ln, a, tiles);
   } else {
-    const size_t n = (size_t)256 * (size_t)num_segments;
+    const size_t n = (size_t)256 * (size_t)num_segments * a.hist_copies;
     ln.run("hist_zero", k_fill_u32, dim3((unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024)),
            dim3(256), a.hist, n, 0u);
     launch_topk<true>(ln, a, tiles);

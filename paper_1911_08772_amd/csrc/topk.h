@@ -1,8 +1,13 @@
 // Exact Top_k (Sec. 1 definition) by radix select over the bit pattern of |acc|: four digit
 // passes (8, 8, 8, 7 bits, most significant first) with per-wave histograms in LDS, a
-// per-segment digit choice, then compaction of {key > T} plus the lowest-index ties.
+// per-segment digit choice after each pass, then compaction of {key > T} plus the lowest-index
+// ties.  Global atomics on one address cost tens of nanoseconds each on this chip, so the
+// global histogram is replicated and the output slots of the bulk of the survivors come from
+// a scan of per-tile counts; only the few survivors that share the k-th key's leading 24 bits
+// take their slots from an atomic cursor.
 #pragma once
 #include "common.h"
+#include "gaussiank.h"
 #include "tile_io.h"
 
 namespace sp {
@@ -11,9 +16,8 @@ constexpr int kDigits = 4;
 __device__ __host__ inline int digit_shift(int pass) { return pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0; }
 __device__ __host__ inline int digit_bits(int pass) { return pass == 3 ? 7 : 8; }
 
-constexpr int kStage = 2048;  // pairs a block buffers in LDS between output reservations
-
-// Adds this block's per-wave LDS histograms into segment s's global histogram and clears them.
+// Adds this block's per-wave LDS histograms into one replica of segment s's global histogram
+// and clears them.
 __device__ inline void flush_hist(const Args& a, int s, uint32_t (*h)[256]) {
   __syncthreads();
   const int bin = threadIdx.x;  // kBlock == 256 bins
@@ -23,7 +27,8 @@ __device__ inline void flush_hist(const Args& a, int s, uint32_t (*h)[256]) {
     v += h[w][bin];
     h[w][bin] = 0;
   }
-  if (v) atomicAdd(&a.hist[(size_t)s * 256 + bin], v);
+  const uint32_t copy = blockIdx.x % a.hist_copies;
+  if (v) atomicAdd(&a.hist[((size_t)s * a.hist_copies + copy) * 256 + bin], v);
   __syncthreads();
 }
 
@@ -63,25 +68,42 @@ __global__ __launch_bounds__(kBlock) void k_topk_accum_hist(const Args a) {
 }
 
 // ---- T3: histogram of digit `pass` over the keys whose higher digits equal the prefix --------
-template <bool FULL>
-__device__ inline void hist_tile(const Args& a, const Tile& t, int pass, uint32_t prefix,
-                                 uint32_t* h) {
+// The last pass also counts, per tile, the keys whose leading 24 bits already exceed the
+// prefix: they are survivors whatever the last digit turns out to be.
+template <bool FULL, bool LAST>
+__device__ inline void hist_tile(const Args& a, const Tile& t, uint32_t tile_id, int pass,
+                                 uint32_t prefix, uint32_t* h, uint32_t* lds_sure) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
   const int hi_shift = digit_shift(pass - 1);
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
+  uint32_t sure = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
     const uint32_t key = mag_key(v[i]);
-    if ((FULL || ((valid >> i) & 1u)) && (key >> hi_shift) == prefix)
-      atomicAdd(&h[(key >> shift) & mask], 1u);
+    const bool ok = FULL || ((valid >> i) & 1u);
+    if (ok && (key >> hi_shift) == prefix) atomicAdd(&h[(key >> shift) & mask], 1u);
+    if (LAST) sure += (ok && (key >> hi_shift) > prefix) ? 1u : 0u;
+  }
+  if (LAST) {
+    sure = wave_sum(sure);
+    __syncthreads();  // lds_sure free again (previous tile's reader is done)
+    if (lane_id() == 0) lds_sure[wave_id()] = sure;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t s = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) s += lds_sure[w];
+      a.tile_counts[tile_id] = s;
+    }
   }
 }
 
-template <bool SEG>
+template <bool SEG, bool LAST>
 __global__ __launch_bounds__(kBlock) void k_topk_hist(const Args a, int pass) {
   __shared__ uint32_t h[kWaves][256];
+  __shared__ uint32_t lds_sure[kWaves];
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   __syncthreads();
@@ -96,29 +118,46 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(const Args a, int pass) {
       cur = t.seg;
       prefix = a.ctrl[cur].prefix;
     }
-    if (t.full) hist_tile<true>(a, t, pass, prefix, h[wave_id()]);
-    else hist_tile<false>(a, t, pass, prefix, h[wave_id()]);
+    if (t.full) hist_tile<true, LAST>(a, t, tid, pass, prefix, h[wave_id()], lds_sure);
+    else hist_tile<false, LAST>(a, t, tid, pass, prefix, h[wave_id()], lds_sure);
   }
   if (cur >= 0) flush_hist(a, cur, h);
 }
 
 // ---- T2: per segment, pick the digit holding the k_rem-th largest key ------------------------
+// One workgroup of kFinBlock threads per segment; the first 256 threads own one bin each, in
+// descending digit order.  After the last pass the same block turns the per-tile counts of
+// sure survivors into their first output slots.
 template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_topk_select(const Args a, int pass) {
-  __shared__ uint32_t lds_scan[kWaves + 1];
+__global__ __launch_bounds__(kFinBlock) void k_topk_select(const Args a, int pass) {
+  __shared__ uint32_t lds_scan[kFinWaves];
+  __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
   if (SEG && (c.bad || c.select_none)) return;
   const uint32_t nbins = 1u << digit_bits(pass);
-  const uint32_t bin = 255u - threadIdx.x;  // thread order = descending digit
-  uint32_t* hp = a.hist + (size_t)s * 256 + bin;
-  const uint32_t v = bin < nbins ? *hp : 0u;
+  const bool owner = threadIdx.x < 256;
+  const uint32_t bin = 255u - (threadIdx.x & 255u);
+  uint32_t v = 0;
+  if (owner) {
+    uint32_t* hp = a.hist + (size_t)s * a.hist_copies * 256 + bin;
+    for (uint32_t r0 = 0; r0 < a.hist_copies; r0 += 16) {
+      uint32_t x[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) x[u] = (r0 + u < a.hist_copies) ? hp[(size_t)(r0 + u) * 256] : 0u;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        v += x[u];
+        if (r0 + u < a.hist_copies) hp[(size_t)(r0 + u) * 256] = 0;  // ready for the next pass
+      }
+    }
+    if (bin >= nbins) v = 0;
+  }
   const uint32_t k_rem = c.k_rem;
   const uint32_t prefix = c.prefix;
   uint32_t total;
-  const uint32_t above = block_exclusive_scan(v, lds_scan, &total);  // keys in higher digits
-  *hp = 0;  // ready for the next pass
-  if (above < k_rem && k_rem <= above + v) {
+  const uint32_t above = block_exclusive_scan<kFinWaves>(v, lds_scan, &total);  // keys in higher digits
+  if (owner && above < k_rem && k_rem <= above + v) {
     const uint32_t np = (prefix << digit_bits(pass)) | bin;
     const uint32_t nk = k_rem - above;
     c.prefix = np;
@@ -130,6 +169,12 @@ __global__ __launch_bounds__(kBlock) void k_topk_select(const Args a, int pass) 
       r.topk_key = np;
       r.topk_ties_taken = nk;
     }
+  }
+  if (pass == kDigits - 1) {
+    const uint32_t tile0 = SEG ? c.tile0 : 0u;
+    const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total);
+    const uint32_t sure = scan_tiles(a.tile_counts + tile0, ntiles, a.tile_base + tile0, stage, lds_scan);
+    if (threadIdx.x == 0) c.cursor = sure;  // the other survivors take slots from here on
   }
 }
 
@@ -149,7 +194,7 @@ __device__ inline void tie_count_tile(const Args& a, const Tile& t, uint32_t til
   if (threadIdx.x == 0) {
     uint32_t s = 0;
     for (int w = 0; w < kWaves; ++w) s += lds[w];
-    a.tile_counts[(size_t)tile_id * kNumThres] = s;
+    a.tile_counts[(size_t)a.max_tiles + tile_id] = s;
   }
 }
 
@@ -165,58 +210,24 @@ __global__ __launch_bounds__(kBlock) void k_topk_tie_count(const Args a) {
 }
 
 template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_topk_tie_scan(const Args a) {
-  __shared__ uint32_t lds_scan[kWaves + 1];
+__global__ __launch_bounds__(kFinBlock) void k_topk_tie_scan(const Args a) {
+  __shared__ uint32_t lds_scan[kFinWaves];
+  __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
   const int s = blockIdx.x;
   const SegCtrl& c = a.ctrl[s];
   if ((SEG && (c.bad || c.select_none)) || !c.rank_ties) return;
   const uint32_t tile0 = SEG ? c.tile0 : 0u;
   const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total);
-  const uint32_t per = (ntiles + kBlock - 1) / kBlock;
-  const uint32_t b = threadIdx.x * per;
-  const uint32_t e = (b + per < ntiles) ? b + per : ntiles;
-  uint32_t sum = 0;
-  for (uint32_t i = b; i < e; ++i) sum += a.tile_counts[(size_t)(tile0 + i) * kNumThres];
-  uint32_t total;
-  uint32_t run = block_exclusive_scan(sum, lds_scan, &total);
-  for (uint32_t i = b; i < e; ++i) {
-    a.tile_base[tile0 + i] = run;
-    run += a.tile_counts[(size_t)(tile0 + i) * kNumThres];
-  }
+  scan_tiles(a.tile_counts + (size_t)a.max_tiles + tile0, ntiles, a.tie_base + tile0, stage, lds_scan);
 }
 
 // ---- T5: compaction of {key > T} and the kept ties, residual write ---------------------------
-struct Stage {
-  uint32_t idx[kStage];
-  float val[kStage];
-  uint32_t scan[kWaves + 1];
-  uint32_t tie[kSlots * kWaves];
-  uint32_t base;
-};
-
-// Hands the staged pairs to segment s's output range: one atomic reservation per flush.
-template <bool SEG>
-__device__ inline void flush_stage(const Args& a, int s, Stage& st, uint32_t staged) {
-  __syncthreads();
-  if (staged == 0) return;
-  SegCtrl& c = a.ctrl[s];
-  if (threadIdx.x == 0) st.base = atomicAdd(&c.cursor, staged);
-  __syncthreads();
-  const uint32_t base = st.base;
-  const int64_t out0 = SEG ? c.out_base : 0;
-  const int64_t cap = SEG ? c.cap : a.flat_cap;
-  for (uint32_t i = threadIdx.x; i < staged; i += kBlock) {
-    if ((int64_t)(base + i) < cap) {
-      a.out_idx[out0 + base + i] = st.idx[i];
-      a.out_val[out0 + base + i] = st.val[i];
-    }
-  }
-  __syncthreads();
-}
-
+// Survivors whose leading 24 bits exceed T's go, in index order, to the slots the scan assigned
+// to their tile.  Survivors that share T's leading 24 bits (normally a handful in the whole
+// vector) take theirs from the segment's cursor, one reservation per tile that has any.
 template <bool SEG, bool FULL>
-__device__ inline uint32_t topk_compact_tile(const Args& a, const Tile& t, uint32_t tile_id,
-                                             Stage& st, uint32_t staged) {
+__device__ inline void topk_compact_tile(const Args& a, const Tile& t, uint32_t tile_id,
+                                         uint32_t* lds, uint32_t* lds_base) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
   SegCtrl& c = a.ctrl[t.seg];
@@ -224,91 +235,85 @@ __device__ inline uint32_t topk_compact_tile(const Args& a, const Tile& t, uint3
   const uint32_t take = c.k_rem;  // ties to keep
   const bool rank_ties = c.rank_ties != 0;
   const bool none = SEG && c.select_none != 0;
-  uint32_t gt = 0, eq = 0;
+  const int64_t out0 = SEG ? c.out_base : 0;
+  const int64_t cap = SEG ? c.cap : a.flat_cap;
+  uint32_t sure = 0, near = 0, eq = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
     if ((FULL || ((valid >> i) & 1u)) && !none) {
       const uint32_t key = mag_key(v[i]);
-      gt |= (key > T ? 1u : 0u) << i;
+      sure |= ((key >> 7) > (T >> 7) ? 1u : 0u) << i;
+      near |= (((key >> 7) == (T >> 7)) && key > T ? 1u : 0u) << i;
       eq |= (key == T ? 1u : 0u) << i;
     }
   }
-  if (rank_ties) {
-    // keep a tie only if fewer than `take` ties precede it in index order
-    uint32_t below[kSlots];
+  uint32_t first[kSlots];
+  tile_rank(sure, lds, first);
+  {
+    const int64_t o = out0 + (int64_t)a.tile_base[tile_id];
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) {
-      uint32_t tot = 0, mine = 0;
+      uint32_t r = first[j];
+      const int64_t i0 = slot_index(t, j);
 #pragma unroll
-      for (int cpt = 0; cpt < 4; ++cpt) {
-        const uint64_t m = __ballot((eq >> (4 * j + cpt)) & 1u);
-        tot += (uint32_t)__builtin_popcountll(m);
-        mine += lanes_below(m);
+      for (int q = 0; q < 4; ++q) {
+        if ((sure >> (4 * j + q)) & 1u) {
+          if ((int64_t)a.tile_base[tile_id] + r < cap) {
+            a.out_idx[o + r] = (uint32_t)(i0 + q);
+            a.out_val[o + r] = v[4 * j + q];
+          }
+          ++r;
+        }
       }
-      below[j] = mine;
-      if (lane_id() == 0) st.tie[j * kWaves + wave_id()] = tot;
     }
-    __syncthreads();
-    uint32_t run = a.tile_base[tile_id];
-    uint32_t kept = 0;
+  }
+  // the rest: same leading bits as T.  Block-uniform early out when the tile has none.
+  if (__syncthreads_or((near | eq) != 0)) {
+    if (rank_ties) {
+      // keep a tie only if fewer than `take` ties precede it in index order
+      const uint32_t n_before = a.tie_base[tile_id];
+      tile_rank(eq, lds, first);
+      uint32_t kept = 0;
 #pragma unroll
-    for (int j = 0; j < kSlots; ++j) {
+      for (int j = 0; j < kSlots; ++j) {
+        uint32_t r = n_before + first[j];
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        if (w == wave_id()) {
-          uint32_t r = run + below[j];
+        for (int q = 0; q < 4; ++q) {
+          if ((eq >> (4 * j + q)) & 1u) {
+            if (r < take) kept |= 1u << (4 * j + q);
+            ++r;
+          }
+        }
+      }
+      eq = kept;
+      __syncthreads();
+    }
+    near |= eq;
+    const uint32_t n_near = tile_rank(near, lds, first);
+    if (n_near != 0) {
+      if (threadIdx.x == 0) *lds_base = atomicAdd(&c.cursor, n_near);
+      __syncthreads();
+      const uint32_t base = *lds_base;
 #pragma unroll
-          for (int cpt = 0; cpt < 4; ++cpt) {
-            if ((eq >> (4 * j + cpt)) & 1u) {
-              if (r < take) kept |= 1u << (4 * j + cpt);
-              ++r;
+      for (int j = 0; j < kSlots; ++j) {
+        uint32_t r = base + first[j];
+        const int64_t i0 = slot_index(t, j);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if ((near >> (4 * j + q)) & 1u) {
+            if ((int64_t)r < cap) {
+              a.out_idx[out0 + r] = (uint32_t)(i0 + q);
+              a.out_val[out0 + r] = v[4 * j + q];
             }
+            ++r;
           }
         }
-        run += st.tie[j * kWaves + w];
       }
     }
-    eq = kept;
-    __syncthreads();
+  } else {
+    near = 0;
   }
-  const uint32_t sel = gt | eq;
-  uint32_t total;
-  uint32_t pos = block_exclusive_scan((uint32_t)__popc(sel), st.scan, &total);
-  if (total != 0) {
-    if (staged + total > (uint32_t)kStage) {
-      flush_stage<SEG>(a, t.seg, st, staged);
-      staged = 0;
-    }
-    if (total > (uint32_t)kStage) {  // dense tile: reserve and write straight to the output
-      if (threadIdx.x == 0) st.base = atomicAdd(&c.cursor, total);
-      __syncthreads();
-      const uint32_t base = st.base;
-      const int64_t out0 = SEG ? c.out_base : 0;
-      const int64_t cap = SEG ? c.cap : a.flat_cap;
-#pragma unroll
-      for (int i = 0; i < kPerThread; ++i) {
-        if ((sel >> i) & 1u) {
-          if ((int64_t)(base + pos) < cap) {
-            a.out_idx[out0 + base + pos] = (uint32_t)(slot_index(t, i >> 2) + (i & 3));
-            a.out_val[out0 + base + pos] = v[i];
-          }
-          ++pos;
-        }
-      }
-      __syncthreads();
-    } else {
-      pos += staged;
-#pragma unroll
-      for (int i = 0; i < kPerThread; ++i) {
-        if ((sel >> i) & 1u) {
-          st.idx[pos] = (uint32_t)(slot_index(t, i >> 2) + (i & 3));
-          st.val[pos] = v[i];
-          ++pos;
-        }
-      }
-      staged += total;
-    }
-  }
+  const uint32_t sel = sure | near;
   if (a.inplace) {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i)
@@ -319,27 +324,17 @@ __device__ inline uint32_t topk_compact_tile(const Args& a, const Tile& t, uint3
       if ((sel >> i) & 1u) v[i] = 0.0f;
     store_tile<FULL>(a.resid, t, v, valid);
   }
-  return staged;
 }
 
 template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_topk_compact(const Args a) {
-  __shared__ Stage st;
-  int cur = -1;
-  uint32_t staged = 0;
-  for (uint32_t tid = blockIdx.x;; tid += gridDim.x) {
-    Tile t;
-    if (!locate_tile<SEG>(a, tid, &t)) break;
-    if (SEG && a.ctrl[t.seg].bad) continue;
-    if (t.seg != cur) {
-      if (cur >= 0) flush_stage<SEG>(a, cur, st, staged);
-      staged = 0;
-      cur = t.seg;
-    }
-    if (t.full) staged = topk_compact_tile<SEG, true>(a, t, tid, st, staged);
-    else staged = topk_compact_tile<SEG, false>(a, t, tid, st, staged);
-  }
-  if (cur >= 0) flush_stage<SEG>(a, cur, st, staged);
+  __shared__ uint32_t lds[kSlots * kWaves];
+  __shared__ uint32_t lds_base;
+  Tile t;
+  if (!locate_tile<SEG>(a, blockIdx.x, &t)) return;
+  if (SEG && a.ctrl[t.seg].bad) return;
+  if (t.full) topk_compact_tile<SEG, true>(a, t, blockIdx.x, lds, &lds_base);
+  else topk_compact_tile<SEG, false>(a, t, blockIdx.x, lds, &lds_base);
 }
 
 }  // namespace sp
