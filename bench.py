@@ -35,6 +35,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3_resnet50")
     ap.add_argument("--inplace", action="store_true", help="acc aliases residual")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile-chunks", type=int, default=0, help="tuning: 4096-element chunks per workgroup")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "
@@ -70,7 +71,7 @@ def main() -> int:
 
     def run(fn, s, trace=None):
         fn(d, k, grads[s], b.residual, b.acc, b.out_idx, b.out_val, cap, b.result, b.workspace,
-           b.workspace_nbytes, trace=trace, stream=stream)
+           b.workspace_nbytes, trace=trace, stream=stream, tile_chunks=args.tile_chunks)
 
     def timed(fn):
         """W warm-up steps then exactly K timed steps; returns (ms per step, nnz per step)."""

@@ -70,7 +70,8 @@ typedef struct {
                       |acc| > thres of Alg. 1 step 6.  1.0: the quantile 1 - k/d as printed in
                       Alg. 1 step 3.  Must be >= 1. */
   int32_t ddof;    /* 1 (default): sample standard deviation; 0: population */
-  int32_t reserved;
+  int32_t tile_chunks; /* 0 (default): automatic.  Otherwise the number of 4096-element chunks one
+                      workgroup processes; a tuning knob, results do not depend on it */
   void* trace;     /* NULL, or a sparsify_trace* to record per-kernel timings of this call */
 } sparsify_opts;
 
@@ -96,7 +97,7 @@ int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual,
 
 /* Exact Top_k compressor (definition in Sec. 1: the k entries largest in absolute value;
  * among equal magnitudes the lower index wins).  Same arguments; cap >= k is required; exactly
- * k pairs are written.  opts: only `trace` is used. */
+ * k pairs are written.  opts: tail_div and ddof are checked but not used. */
 int sparsify_topk(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
                   uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
                   void* workspace, size_t workspace_bytes, const sparsify_opts* opts,

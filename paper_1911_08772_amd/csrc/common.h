@@ -12,7 +12,10 @@ constexpr int kBlock = 256;                       // threads per workgroup (4 wa
 constexpr int kWaves = kBlock / 64;
 constexpr int kSlots = 4;                         // float4 loads per thread per tile
 constexpr int kPerThread = 4 * kSlots;            // 16 elements per thread
-constexpr int kTile = kBlock * kPerThread;        // 4096 elements = 16 KiB per array
+constexpr int kChunk = kBlock * kPerThread;       // 4096 elements = 16 KiB per array
+// A workgroup's unit of work, a "tile", is `tile_chunks` consecutive chunks (chosen per call so
+// that a vector has at most about four thousand tiles: the per-tile partial results that the
+// small per-segment kernels must combine then stay few, whatever d is).
 constexpr int kNumThres = 10;                     // thresholds reachable by <= 3 nudges
 
 // Thresholds reachable from thres0 by `a` multiplications by 1.5 and `b` halvings, a+b <= 3
@@ -40,7 +43,7 @@ struct SegCtrl {
   float t_final;            // fp32 threshold of the mask-producing evaluation
   uint32_t select_none;     // overflow / bad: select nothing
   uint32_t sorted_ok;       // the ten thresholds are in non-decreasing order (thres0 > 0)
-  uint32_t pad2;
+  uint32_t flags;           // result flags raised so far (Gaussian_k)
   // Top_k
   uint32_t prefix;          // digits of the k-th key decided so far (high bits)
   uint32_t k_rem;           // survivors still to take among keys matching the prefix
@@ -74,36 +77,63 @@ struct Args {
   uint32_t* tie_base;     // [max_tiles]
   uint32_t hist_copies;   // replicas of each segment's histogram (spreads the atomics)
   uint32_t max_tiles;
+  uint32_t tile_chunks;   // chunks per tile
   int32_t ddof;
   double tail_div;
 };
 
-// Tile j of a segment covers the absolute range [base + j*kTile, base + (j+1)*kTile) cut to
-// [start, end), with base = start rounded down to a multiple of 4 so that full float4 slots
-// are 16-byte aligned whatever the segment's start.
+// Tile j of a segment covers the absolute range [base + j*E, base + (j+1)*E) cut to
+// [start, end), E = tile_chunks * kChunk, with base = start rounded down to a multiple of 4 so
+// that full float4 slots are 16-byte aligned whatever the segment's start.
 __host__ __device__ inline int64_t seg_base(int64_t start) { return start & ~int64_t(3); }
-__host__ __device__ inline uint32_t seg_ntiles(int64_t start, int64_t end) {
-  return (uint32_t)((end - seg_base(start) + kTile - 1) / kTile);
+__host__ __device__ inline uint32_t seg_ntiles(int64_t start, int64_t end, uint32_t tile_chunks) {
+  const int64_t e = (int64_t)tile_chunks * kChunk;
+  return (uint32_t)((end - seg_base(start) + e - 1) / e);
 }
 
+// One chunk: what the tile_io loads and stores address.
 struct Tile {
   int seg;
-  int64_t tbase;   // absolute index of the tile's first slot (multiple of 4)
-  int64_t lo, hi;  // valid absolute range of this tile
-  bool full;       // every slot of the tile is inside [lo, hi)
+  int64_t tbase;   // absolute index of the chunk's first slot (multiple of 4)
+  int64_t lo, hi;  // valid absolute range of this chunk
+  bool full;       // every slot of the chunk is inside [lo, hi)
 };
+
+// One workgroup's tile: `nchunks` chunks starting at `base`, valid range [lo, hi).
+struct Span {
+  int seg;
+  int64_t base, lo, hi;
+  uint32_t nchunks;
+};
+
+__device__ inline Tile chunk_of(const Span& s, uint32_t u) {
+  Tile t;
+  t.seg = s.seg;
+  t.tbase = s.base + (int64_t)u * kChunk;
+  t.lo = t.tbase > s.lo ? t.tbase : s.lo;
+  t.hi = (t.tbase + kChunk < s.hi) ? t.tbase + kChunk : s.hi;
+  t.full = (t.tbase >= s.lo) && (t.tbase + kChunk <= s.hi);
+  return t;
+}
+
+__device__ inline void make_span(Span* out, int seg, int64_t start, int64_t end, int64_t tb,
+                                 uint32_t tile_chunks) {
+  const int64_t te = tb + (int64_t)tile_chunks * kChunk;
+  out->seg = seg;
+  out->base = tb;
+  out->lo = tb > start ? tb : start;
+  out->hi = te < end ? te : end;
+  out->nchunks = (uint32_t)((out->hi - tb + kChunk - 1) / kChunk);
+}
 
 // Maps a tile id to its segment and range.  Flat calls: one segment starting at 0.
 template <bool SEG>
-__device__ inline bool locate_tile(const Args& a, uint32_t t, Tile* out) {
+__device__ inline bool locate_span(const Args& a, uint32_t t, Span* out) {
+  const int64_t e = (int64_t)a.tile_chunks * kChunk;
   if (!SEG) {
-    const int64_t tb = (int64_t)t * kTile;
+    const int64_t tb = (int64_t)t * e;
     if (tb >= a.d_total) return false;
-    out->seg = 0;
-    out->tbase = tb;
-    out->lo = tb;
-    out->hi = (tb + kTile < a.d_total) ? tb + kTile : a.d_total;
-    out->full = (tb + kTile <= a.d_total);
+    make_span(out, 0, 0, a.d_total, tb, a.tile_chunks);
     return true;
   }
   const uint32_t* ts = a.tile_start;
@@ -114,12 +144,7 @@ __device__ inline bool locate_tile(const Args& a, uint32_t t, Tile* out) {
     if (ts[mid] <= t) lo = mid; else hi = mid;
   }
   const SegCtrl& c = a.ctrl[lo];
-  const int64_t tb = seg_base(c.start) + (int64_t)(t - c.tile0) * kTile;
-  out->seg = lo;
-  out->tbase = tb;
-  out->lo = tb > c.start ? tb : c.start;
-  out->hi = (tb + kTile < c.end) ? tb + kTile : c.end;
-  out->full = (tb >= c.start) && (tb + kTile <= c.end);
+  make_span(out, lo, c.start, c.end, seg_base(c.start) + (int64_t)(t - c.tile0) * e, a.tile_chunks);
   return true;
 }
 

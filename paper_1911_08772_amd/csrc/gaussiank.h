@@ -34,9 +34,16 @@ __device__ inline double norm_isf(double q) {
 }
 
 // ---- K1: acc = grad + residual, per-tile (n, mean, M2) --------------------------------------
+// Per-thread shifted sums sum(x-p), sum((x-p)^2) in fp64 around a wave-uniform pivot p taken
+// from a register (the first valid element the wave meets), so nothing is lost to cancellation
+// whatever the mean is.
+struct MomAcc {
+  double n, s1, s2, pivot;
+  bool have_pivot;
+};
+
 template <bool FULL>
-__device__ inline void accum_moments_tile(const Args& a, const Tile& t, uint32_t tile_id,
-                                          double* lds) {
+__device__ inline void accum_moments_chunk(const Args& a, const Tile& t, MomAcc& m) {
   float g[kPerThread], e[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.grad, t, g);
   load_tile<FULL>(a.resid, t, e);
@@ -44,38 +51,51 @@ __device__ inline void accum_moments_tile(const Args& a, const Tile& t, uint32_t
   for (int i = 0; i < kPerThread; ++i) g[i] = g[i] + e[i];  // Eq. (2): one fp32 add
   store_tile<FULL>(a.acc, t, g, valid);
 
-  // Wave-uniform pivot taken from a register (the first valid element held by the wave), so the
-  // shifted sums sum((x-p)), sum((x-p)^2) lose nothing to cancellation whatever the mean is.
-  float first = g[0];
-  bool has = true;
-  if (!FULL) {
-    has = valid != 0;
-    first = 0.0f;
+  if (!m.have_pivot) {  // wave-uniform
+    float first = g[0];
+    bool has = true;
+    if (!FULL) {
+      has = valid != 0;
+      first = 0.0f;
 #pragma unroll
-    for (int i = kPerThread - 1; i >= 0; --i)
-      if ((valid >> i) & 1u) first = g[i];
+      for (int i = kPerThread - 1; i >= 0; --i)
+        if ((valid >> i) & 1u) first = g[i];
+    }
+    const uint64_t owners = __ballot(has);
+    if (owners != 0) {
+      m.pivot = (double)__shfl(first, __builtin_ctzll(owners), 64);
+      m.have_pivot = true;
+    }
   }
-  const uint64_t owners = __ballot(has);
-  double n = 0.0, s1 = 0.0, s2 = 0.0, pivot = 0.0;
-  if (owners != 0) {
-    const int src = __builtin_ctzll(owners);
-    pivot = (double)__shfl(first, src, 64);
+  if (m.have_pivot) {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       if (FULL || ((valid >> i) & 1u)) {
-        const double c = (double)g[i] - pivot;
-        s1 += c;
-        s2 = fma(c, c, s2);
+        const double c = (double)g[i] - m.pivot;
+        m.s1 += c;
+        m.s2 = fma(c, c, m.s2);
       }
     }
-    n = FULL ? (double)kPerThread : (double)__popc(valid);
+    m.n += FULL ? (double)kPerThread : (double)__popc(valid);
   }
-  n = wave_sum(n);
-  s1 = wave_sum(s1);
-  s2 = wave_sum(s2);
+}
+
+template <bool SEG>
+__global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
+  __shared__ double lds[3 * kWaves];
+  Span sp_;
+  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
+  if (SEG && a.ctrl[sp_.seg].bad) return;
+  MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) accum_moments_chunk<true>(a, t, m);
+    else accum_moments_chunk<false>(a, t, m);
+  }
+  const double n = wave_sum(m.n), s1 = wave_sum(m.s1), s2 = wave_sum(m.s2);
   if (lane_id() == 0) {
     double* w = lds + 3 * wave_id();
-    const double mean = n > 0.0 ? pivot + s1 / n : 0.0;
+    const double mean = n > 0.0 ? m.pivot + s1 / n : 0.0;
     const double m2 = n > 0.0 ? s2 - s1 * (s1 / n) : 0.0;
     w[0] = n;
     w[1] = mean;
@@ -83,26 +103,16 @@ __device__ inline void accum_moments_tile(const Args& a, const Tile& t, uint32_t
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    Moments m = {lds[0], lds[1], lds[2]};
+    Moments r = {lds[0], lds[1], lds[2]};
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) m = merge(m, Moments{lds[3 * w], lds[3 * w + 1], lds[3 * w + 2]});
-    a.partial[tile_id] = m.n;
-    a.partial[(size_t)a.max_tiles + tile_id] = m.mean;
-    a.partial[2 * (size_t)a.max_tiles + tile_id] = m.m2;
-  }
-}
-
-template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
-  __shared__ double lds[3 * kWaves];
-  Tile t;
-  if (!locate_tile<SEG>(a, blockIdx.x, &t)) return;
-  if (SEG && a.ctrl[t.seg].bad) return;
-  if (t.full) accum_moments_tile<true>(a, t, blockIdx.x, lds);
-  else accum_moments_tile<false>(a, t, blockIdx.x, lds);
-  if (!SEG && blockIdx.x == 0 && threadIdx.x == 0) {
-    // The quantile depends on the arguments only; compute it here, hidden under the stream.
-    a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
+    for (int w = 1; w < kWaves; ++w) r = merge(r, Moments{lds[3 * w], lds[3 * w + 1], lds[3 * w + 2]});
+    a.partial[blockIdx.x] = r.n;
+    a.partial[(size_t)a.max_tiles + blockIdx.x] = r.mean;
+    a.partial[2 * (size_t)a.max_tiles + blockIdx.x] = r.m2;
+    if (!SEG && blockIdx.x == 0) {
+      // The quantile depends on the arguments only; compute it here, hidden under the stream.
+      a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
+    }
   }
 }
 
@@ -120,14 +130,14 @@ __device__ inline double fin_block_sum(double v, double* lds) {
   return s;
 }
 
-constexpr int kFinBatch = 8;  // partials per thread per round: 8192 tiles per round
+constexpr int kFinBatch = 4;  // partials per thread per round: 4096 tiles per round
 
 template <bool SEG>
 __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
   __shared__ double lds[kFinWaves];
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
-  uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total);
+  uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
   int64_t n_seg = a.d_total;
   if (SEG) {
     if (c.bad) return;
@@ -138,6 +148,7 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
   const double* pn = a.partial + tile0;
   const double* pm = pn + a.max_tiles;
   const double* pq = pm + a.max_tiles;
+  const double z = c.z;  // issued early: its latency hides under the partial loads
   double wsum = 0.0;
   for (uint32_t base = 0; base < ntiles; base += kFinBlock * kFinBatch) {
     double n[kFinBatch], mu[kFinBatch];
@@ -173,7 +184,6 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
   if (threadIdx.x != 0) return;
 
   const double sd = (n_seg - a.ddof < 1) ? 0.0 : sqrt(m2 / (double)(n_seg - a.ddof));
-  const double z = c.z;
   const double thres0 = mean + sd * z;
   // candidate thresholds: `na` multiplications by 1.5 in sequence, then halvings (exact),
   // stored in ascending order of their nominal ratio to thres0
@@ -189,31 +199,24 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
     up = 1.5 * up;
   }
   c.sorted_ok = thres0 > 0.0 ? 1u : 0u;
+  uint32_t flags = 0;
+  if (!isfinite(mean) || !isfinite(sd) || !isfinite(thres0)) flags |= SPARSIFY_F_NONFINITE;
+  c.flags = flags;
   sparsify_result& r = a.result[s];
   r.mean = mean;
   r.std = sd;
   r.z = z;
   r.thres0 = thres0;
-  uint32_t flags = 0;
-  if (!isfinite(mean) || !isfinite(sd) || !isfinite(thres0)) flags |= SPARSIFY_F_NONFINITE;
-  r.flags = flags;
 }
 
 // ---- K3: per tile, count |acc| > t for all ten candidate thresholds --------------------------
 // The thresholds sit in ascending order, so once no element of a wave's slot exceeds one of them
 // the larger ones need not be tested (only when the ordering is known to hold).
 template <bool FULL>
-__device__ inline void count_tile(const Args& a, const Tile& t, uint32_t tile_id, uint32_t* lds) {
+__device__ inline void count_chunk(const Args& a, const Tile& t, const float (&thr)[kNumThres],
+                                   bool can_skip, uint32_t (&cnt)[kNumThres]) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
-  const SegCtrl& c = a.ctrl[t.seg];
-  float thr[kNumThres];
-#pragma unroll
-  for (int p = 0; p < kNumThres; ++p) thr[p] = c.t32[p];
-  const bool can_skip = c.sorted_ok != 0;
-  uint32_t cnt[kNumThres];
-#pragma unroll
-  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
 #pragma unroll
   for (int j = 0; j < kSlots; ++j) {
     float m[4];
@@ -252,6 +255,30 @@ __device__ inline void count_tile(const Args& a, const Tile& t, uint32_t tile_id
       }
     }
   }
+}
+
+// The tiles are visited from the last to the first: the end of acc is what the accumulate
+// kernel wrote most recently, so it is the part most likely still to sit in the last-level cache.
+template <bool SEG>
+__global__ __launch_bounds__(kBlock) void k_gk_count(const Args a) {
+  __shared__ uint32_t lds[kWaves * kNumThres];
+  Span sp_;
+  const uint32_t tile = gridDim.x - 1u - blockIdx.x;
+  if (!locate_span<SEG>(a, tile, &sp_)) return;
+  const SegCtrl& c = a.ctrl[sp_.seg];
+  if (SEG && c.bad) return;
+  float thr[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) thr[p] = c.t32[p];
+  const bool can_skip = c.sorted_ok != 0;
+  uint32_t cnt[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
+    else count_chunk<false>(a, t, thr, can_skip, cnt);
+  }
   if (lane_id() == 0) {
 #pragma unroll
     for (int p = 0; p < kNumThres; ++p) lds[wave_id() * kNumThres + p] = cnt[p];
@@ -261,24 +288,14 @@ __device__ inline void count_tile(const Args& a, const Tile& t, uint32_t tile_id
     uint32_t s = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) s += lds[w * kNumThres + threadIdx.x];
-    a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile_id] = s;  // [threshold][tile]
+    a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile] = s;  // [threshold][tile]
   }
 }
 
-template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_gk_count(const Args a) {
-  __shared__ uint32_t lds[kWaves * kNumThres];
-  Tile t;
-  if (!locate_tile<SEG>(a, blockIdx.x, &t)) return;
-  if (SEG && a.ctrl[t.seg].bad) return;
-  if (t.full) count_tile<true>(a, t, blockIdx.x, lds);
-  else count_tile<false>(a, t, blockIdx.x, lds);
-}
-
 // ---- K4: per segment, total the counts, walk Alg. 1 steps 5-13, scan the chosen column -------
-constexpr int kScanPer = 8;                        // consecutive tiles per thread per scan round
-constexpr int kScanChunk = kFinBlock * kScanPer;   // 8192 tiles staged in LDS per round
-constexpr int kTotBatch = 4;
+constexpr int kScanPer = 4;                        // consecutive tiles per thread per scan round
+constexpr int kScanChunk = kFinBlock * kScanPer;   // 4096 tiles staged in LDS per round
+constexpr int kTotBatch = 2;
 
 // Exclusive prefix sum of col[0..n) into base[0..n) by one workgroup of kFinBlock threads;
 // returns the total.  `stage` holds kFinBlock*(kScanPer+1) words, `lds_scan` kFinWaves words.
@@ -322,10 +339,10 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
   __shared__ uint32_t lds_cnt[kFinWaves * kNumThres];
   __shared__ uint32_t lds_scan[kFinWaves];
   __shared__ uint32_t lds_final;
-  __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];  // +1 word per thread: no bank conflicts
+  __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
-  uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total);
+  uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
   int64_t k = a.flat_k, cap = a.flat_cap;
   if (SEG) {
     if (c.bad) return;
@@ -333,6 +350,14 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
     ntiles = c.ntiles;
     k = c.k;
     cap = c.cap;
+  }
+  // thread 0 needs these after the totals; ask for them now so their latency overlaps
+  double t64[kNumThres];
+  uint32_t flags = 0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int p = 0; p < kNumThres; ++p) t64[p] = c.t64[p];
+    flags = c.flags;  // NONFINITE bit from the threshold kernel
   }
   uint32_t cnt[kNumThres];
 #pragma unroll
@@ -361,6 +386,7 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t tot[kNumThres];
+#pragma unroll
     for (int p = 0; p < kNumThres; ++p) {
       tot[p] = 0;
       for (int w = 0; w < kFinWaves; ++w) tot[p] += lds_cnt[w * kNumThres + p];
@@ -369,10 +395,11 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
     int na = 0, nb = 0, p = 0;
     bool in_band = false;
     uint32_t rounds = 0;
+    uint32_t counts[4] = {0, 0, 0, 0};
     for (int round = 0; round <= 3; ++round) {  // "for i = 0 -> 3": four evaluations at most
       p = thres_pos(na, nb);
       const int64_t est = tot[p];
-      r.count[round] = tot[p];
+      counts[round] = tot[p];
       rounds = round + 1;
       if (3 * est < 2 * k) {          // estimated_k < 2k/3: halve the threshold
         if (round < 3) ++nb;
@@ -383,36 +410,36 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
         break;
       }
     }
-    for (uint32_t q = rounds; q < 4; ++q) r.count[q] = 0;
-    uint32_t flags = r.flags;  // NONFINITE bit from the threshold kernel
     if (!in_band) flags |= SPARSIFY_F_EXHAUSTED;
     const bool overflow = (int64_t)tot[p] > cap;
     if (overflow) flags |= SPARSIFY_F_OVERFLOW;
-    r.rounds = rounds;
-    r.flags = flags;
-    r.thres = c.t64[p];
-    r.thres_f32 = c.t32[p];
+    const double tf = t64[p];
     r.nnz = overflow ? 0u : tot[p];
+    r.rounds = rounds;
+    r.count[0] = counts[0];
+    r.count[1] = counts[1];
+    r.count[2] = counts[2];
+    r.count[3] = counts[3];
+    r.flags = flags;
+    r.thres = tf;
+    r.thres_f32 = (float)tf;
     r.topk_key = 0;
     r.topk_ties_taken = 0;
-    c.t_final = c.t32[p];
+    c.t_final = (float)tf;
     c.select_none = overflow ? 1u : 0u;
     lds_final = (uint32_t)p;
   }
   __syncthreads();
-  scan_tiles(a.tile_counts + tile0 + (size_t)lds_final * a.max_tiles, ntiles, a.tile_base + tile0,
-             stage, lds_scan);
+  scan_tiles(cols + (size_t)lds_final * a.max_tiles, ntiles, a.tile_base + tile0, stage, lds_scan);
 }
 
 // ---- K5: compaction in index order + residual (Alg. 1 step 14, Eq. (2)) ----------------------
-template <bool SEG, bool FULL>
-__device__ inline void compact_tile(const Args& a, const Tile& t, uint32_t tile_id,
-                                    uint32_t* lds) {
+// `run` is the number of survivors of this tile's earlier chunks (block-uniform).
+template <bool FULL>
+__device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr, bool none,
+                                         int64_t out0, uint32_t run, uint32_t* lds) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
-  const SegCtrl& c = a.ctrl[t.seg];
-  const float thr = c.t_final;
-  const bool none = c.select_none != 0;
   uint32_t sel = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
@@ -420,11 +447,10 @@ __device__ inline void compact_tile(const Args& a, const Tile& t, uint32_t tile_
     if (ok && !none && (fabsf(v[i]) > thr)) sel |= 1u << i;
   }
   uint32_t first[kSlots];
-  tile_rank(sel, lds, first);
-  const int64_t out0 = (SEG ? c.out_base : 0) + (int64_t)a.tile_base[tile_id];
+  const uint32_t total = tile_rank(sel, lds, first);
 #pragma unroll
   for (int j = 0; j < kSlots; ++j) {
-    uint32_t r = first[j];
+    uint32_t r = run + first[j];
     const int64_t i0 = slot_index(t, j);
 #pragma unroll
     for (int cpt = 0; cpt < 4; ++cpt) {
@@ -449,16 +475,26 @@ __device__ inline void compact_tile(const Args& a, const Tile& t, uint32_t tile_
       if ((sel >> i) & 1u) v[i] = 0.0f;
     store_tile<FULL>(a.resid, t, v, valid);
   }
+  __syncthreads();  // lds is reused by the next chunk
+  return run + total;
 }
 
 template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_gk_compact(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
-  Tile t;
-  if (!locate_tile<SEG>(a, blockIdx.x, &t)) return;
-  if (SEG && a.ctrl[t.seg].bad) return;
-  if (t.full) compact_tile<SEG, true>(a, t, blockIdx.x, lds);
-  else compact_tile<SEG, false>(a, t, blockIdx.x, lds);
+  Span sp_;
+  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
+  const SegCtrl& c = a.ctrl[sp_.seg];
+  if (SEG && c.bad) return;
+  const float thr = c.t_final;
+  const bool none = c.select_none != 0;
+  const int64_t out0 = (SEG ? c.out_base : 0) + (int64_t)a.tile_base[blockIdx.x];
+  uint32_t run = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) run = compact_chunk<true>(a, t, thr, none, out0, run, lds);
+    else run = compact_chunk<false>(a, t, thr, none, out0, run, lds);
+  }
 }
 
 }  // namespace sp

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
               o0 >= 0 && o1 >= o0 && o1 <= a.out_cap);
       if (s == 0 && start != 0) bad = true;
       if (s == a.L - 1 && end != a.d_total) bad = true;
-      if (!bad) nt = seg_ntiles(start, end);
+      if (!bad) nt = seg_ntiles(start, end, a.tile_chunks);
     }
     uint32_t total;
     const uint32_t excl = block_exclusive_scan(nt, lds_scan, &total);

@@ -55,9 +55,20 @@ struct Launcher {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-uint32_t max_tiles_of(int64_t d_total, int32_t L) {
-  // each segment adds at most two tiles over d/kTile (ragged head and tail)
-  return (uint32_t)(d_total / kTile + 2 * (int64_t)L + 1);
+// Chunks per tile: the smallest power of two that keeps a vector of d elements within about
+// four thousand tiles (one workgroup each), so that the per-tile partials stay few.
+constexpr int64_t kTargetTiles = 4096;
+uint32_t tile_chunks_of(int64_t d_total) {
+  const int64_t chunks = (d_total + kChunk - 1) / kChunk;
+  uint32_t c = 1;
+  while ((chunks + c - 1) / c > kTargetTiles) c *= 2;
+  return c;
+}
+
+// The workspace is sized for the finest tiling (one chunk per tile), so any tiling fits.
+uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
+  // each segment adds at most two tiles over d/tile (ragged head and tail)
+  return (uint32_t)(d_total / ((int64_t)kChunk * tile_chunks) + 2 * (int64_t)L + 1);
 }
 
 // replicas of each segment's global histogram: spreads same-address atomics of the flat call
@@ -67,7 +78,7 @@ struct Carve {
   size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, hist, total;
 };
 Carve carve(int64_t d_total, int32_t L) {
-  const size_t mt = max_tiles_of(d_total, L);
+  const size_t mt = max_tiles_of(d_total, L, 1);
   Carve c;
   size_t off = 0;
   c.ctrl = off;        off = align_up(off + sizeof(SegCtrl) * (size_t)L);
@@ -146,15 +157,15 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.tie_base = reinterpret_cast<uint32_t*>(w + cv.tie_base);
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
   a.hist_copies = hist_copies_of(L);
-  a.max_tiles = max_tiles_of(d_total, L);
+  a.tile_chunks = tile_chunks_of(d_total);
+  if (opts && opts->tile_chunks != 0) {
+    if (opts->tile_chunks < 0 || opts->tile_chunks > (1 << 20)) return SPARSIFY_E_INVALID;
+    a.tile_chunks = (uint32_t)opts->tile_chunks;
+  }
+  a.max_tiles = max_tiles_of(d_total, L, 1);
   a.ddof = ddof;
   a.tail_div = tail_div;
   return SPARSIFY_OK;
-}
-
-uint32_t persistent_grid(uint32_t tiles) {
-  const uint32_t want = 2048;  // 256 CUs x 8 workgroups of 256 threads
-  return tiles < want ? (tiles ? tiles : 1u) : want;
 }
 
 template <bool SEG>
@@ -170,7 +181,7 @@ void launch_gaussiank(Launcher& ln, const Args& a, uint32_t tiles) {
 template <bool SEG>
 void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
-  const dim3 pg(persistent_grid(tiles));
+  const dim3 pg(tiles);
   ln.run("topk_accum_hist", k_topk_accum_hist<SEG>, pg, blk, a);
   const dim3 fin(kFinBlock);
   ln.run("topk_select0", k_topk_select<SEG>, dim3(a.L), fin, a, 0);
@@ -192,14 +203,14 @@ int flat_call(bool gaussian, int64_t d, int64_t k, const float* grad, float* res
   if (!gaussian && cap < k) return SPARSIFY_E_INVALID;
   Args a;
   const int rc = prepare(a, 1, d, grad, residual, acc, out_idx, out_val, cap, result, workspace,
-                         workspace_bytes, gaussian ? opts : nullptr);
+                         workspace_bytes, opts);
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
   Launcher ln{static_cast<hipStream_t>(stream),
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
   ln.begin();
-  const uint32_t tiles = seg_ntiles(0, d);
+  const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
   if (gaussian) {
     launch_gaussiank<false>(ln, a, tiles);
   } else {

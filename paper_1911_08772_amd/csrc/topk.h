@@ -52,27 +52,23 @@ __global__ __launch_bounds__(kBlock) void k_topk_accum_hist(const Args a) {
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   __syncthreads();
-  int cur = -1;
-  for (uint32_t tid = blockIdx.x;; tid += gridDim.x) {
-    Tile t;
-    if (!locate_tile<SEG>(a, tid, &t)) break;
-    if (SEG && a.ctrl[t.seg].bad) continue;
-    if (t.seg != cur) {
-      if (cur >= 0) flush_hist(a, cur, h);
-      cur = t.seg;
-    }
+  Span sp_;
+  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
+  if (SEG && a.ctrl[sp_.seg].bad) return;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
     if (t.full) accum_hist_tile<true>(a, t, h[wave_id()]);
     else accum_hist_tile<false>(a, t, h[wave_id()]);
   }
-  if (cur >= 0) flush_hist(a, cur, h);
+  flush_hist(a, sp_.seg, h);
 }
 
 // ---- T3: histogram of digit `pass` over the keys whose higher digits equal the prefix --------
 // The last pass also counts, per tile, the keys whose leading 24 bits already exceed the
 // prefix: they are survivors whatever the last digit turns out to be.
 template <bool FULL, bool LAST>
-__device__ inline void hist_tile(const Args& a, const Tile& t, uint32_t tile_id, int pass,
-                                 uint32_t prefix, uint32_t* h, uint32_t* lds_sure) {
+__device__ inline uint32_t hist_tile(const Args& a, const Tile& t, int pass, uint32_t prefix,
+                                     uint32_t* h) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
   const int hi_shift = digit_shift(pass - 1);
@@ -86,18 +82,7 @@ __device__ inline void hist_tile(const Args& a, const Tile& t, uint32_t tile_id,
     if (ok && (key >> hi_shift) == prefix) atomicAdd(&h[(key >> shift) & mask], 1u);
     if (LAST) sure += (ok && (key >> hi_shift) > prefix) ? 1u : 0u;
   }
-  if (LAST) {
-    sure = wave_sum(sure);
-    __syncthreads();  // lds_sure free again (previous tile's reader is done)
-    if (lane_id() == 0) lds_sure[wave_id()] = sure;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t s = 0;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) s += lds_sure[w];
-      a.tile_counts[tile_id] = s;
-    }
-  }
+  return sure;
 }
 
 template <bool SEG, bool LAST>
@@ -107,21 +92,31 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(const Args a, int pass) {
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   __syncthreads();
-  int cur = -1;
-  uint32_t prefix = 0;
-  for (uint32_t tid = blockIdx.x;; tid += gridDim.x) {
-    Tile t;
-    if (!locate_tile<SEG>(a, tid, &t)) break;
-    if (SEG && (a.ctrl[t.seg].bad || a.ctrl[t.seg].select_none)) continue;
-    if (t.seg != cur) {
-      if (cur >= 0) flush_hist(a, cur, h);
-      cur = t.seg;
-      prefix = a.ctrl[cur].prefix;
-    }
-    if (t.full) hist_tile<true, LAST>(a, t, tid, pass, prefix, h[wave_id()], lds_sure);
-    else hist_tile<false, LAST>(a, t, tid, pass, prefix, h[wave_id()], lds_sure);
+  Span sp_;
+  // odd passes walk the tiles backwards: each pass starts where the previous one ended, on the
+  // part of acc most likely still to sit in the last-level cache
+  const uint32_t tile = (pass & 1) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  if (!locate_span<SEG>(a, tile, &sp_)) return;
+  const SegCtrl& c = a.ctrl[sp_.seg];
+  if (SEG && (c.bad || c.select_none)) return;
+  const uint32_t prefix = c.prefix;
+  uint32_t sure = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) sure += hist_tile<true, LAST>(a, t, pass, prefix, h[wave_id()]);
+    else sure += hist_tile<false, LAST>(a, t, pass, prefix, h[wave_id()]);
   }
-  if (cur >= 0) flush_hist(a, cur, h);
+  if (LAST) {
+    sure = wave_sum(sure);
+    if (lane_id() == 0) lds_sure[wave_id()] = sure;
+  }
+  flush_hist(a, sp_.seg, h);  // starts with a barrier
+  if (LAST && threadIdx.x == 0) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) s += lds_sure[w];
+    a.tile_counts[tile] = s;
+  }
 }
 
 // ---- T2: per segment, pick the digit holding the k_rem-th largest key ------------------------
@@ -172,7 +167,7 @@ __global__ __launch_bounds__(kFinBlock) void k_topk_select(const Args a, int pas
   }
   if (pass == kDigits - 1) {
     const uint32_t tile0 = SEG ? c.tile0 : 0u;
-    const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total);
+    const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total, a.tile_chunks);
     const uint32_t sure = scan_tiles(a.tile_counts + tile0, ntiles, a.tile_base + tile0, stage, lds_scan);
     if (threadIdx.x == 0) c.cursor = sure;  // the other survivors take slots from here on
   }
@@ -180,33 +175,36 @@ __global__ __launch_bounds__(kFinBlock) void k_topk_select(const Args a, int pas
 
 // ---- ties: when only some of the keys equal to T are kept, rank them by index ----------------
 template <bool FULL>
-__device__ inline void tie_count_tile(const Args& a, const Tile& t, uint32_t tile_id, uint32_t T,
-                                      uint32_t* lds) {
+__device__ inline uint32_t tie_count_chunk(const Args& a, const Tile& t, uint32_t T) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
   uint32_t n = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i)
     n += ((FULL || ((valid >> i) & 1u)) && mag_key(v[i]) == T) ? 1u : 0u;
+  return n;
+}
+
+template <bool SEG>
+__global__ __launch_bounds__(kBlock) void k_topk_tie_count(const Args a) {
+  __shared__ uint32_t lds[kWaves];
+  Span sp_;
+  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
+  const SegCtrl& c = a.ctrl[sp_.seg];
+  if ((SEG && (c.bad || c.select_none)) || !c.rank_ties) return;
+  uint32_t n = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    n += t.full ? tie_count_chunk<true>(a, t, c.prefix) : tie_count_chunk<false>(a, t, c.prefix);
+  }
   n = wave_sum(n);
   if (lane_id() == 0) lds[wave_id()] = n;
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t s = 0;
     for (int w = 0; w < kWaves; ++w) s += lds[w];
-    a.tile_counts[(size_t)a.max_tiles + tile_id] = s;
+    a.tile_counts[(size_t)a.max_tiles + blockIdx.x] = s;
   }
-}
-
-template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_topk_tie_count(const Args a) {
-  __shared__ uint32_t lds[kWaves];
-  Tile t;
-  if (!locate_tile<SEG>(a, blockIdx.x, &t)) return;
-  const SegCtrl& c = a.ctrl[t.seg];
-  if ((SEG && (c.bad || c.select_none)) || !c.rank_ties) return;
-  if (t.full) tie_count_tile<true>(a, t, blockIdx.x, c.prefix, lds);
-  else tie_count_tile<false>(a, t, blockIdx.x, c.prefix, lds);
 }
 
 template <bool SEG>
@@ -217,30 +215,33 @@ __global__ __launch_bounds__(kFinBlock) void k_topk_tie_scan(const Args a) {
   const SegCtrl& c = a.ctrl[s];
   if ((SEG && (c.bad || c.select_none)) || !c.rank_ties) return;
   const uint32_t tile0 = SEG ? c.tile0 : 0u;
-  const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total);
+  const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total, a.tile_chunks);
   scan_tiles(a.tile_counts + (size_t)a.max_tiles + tile0, ntiles, a.tie_base + tile0, stage, lds_scan);
 }
 
 // ---- T5: compaction of {key > T} and the kept ties, residual write ---------------------------
 // Survivors whose leading 24 bits exceed T's go, in index order, to the slots the scan assigned
 // to their tile.  Survivors that share T's leading 24 bits (normally a handful in the whole
-// vector) take theirs from the segment's cursor, one reservation per tile that has any.
-template <bool SEG, bool FULL>
-__device__ inline void topk_compact_tile(const Args& a, const Tile& t, uint32_t tile_id,
-                                         uint32_t* lds, uint32_t* lds_base) {
+// vector) take theirs from the segment's cursor, one reservation per chunk that has any.
+struct TopkSel {
+  uint32_t T, take;       // the k-th key; ties to keep
+  bool rank_ties, none;
+  int64_t out0, cap;
+  uint32_t sure_run;      // sure survivors of this tile's earlier chunks
+  uint32_t tie_run;       // ties met so far in index order (this tile's base + earlier chunks)
+  uint32_t tile_sure0;    // first output slot of this tile's sure survivors
+};
+
+template <bool FULL>
+__device__ inline void topk_compact_chunk(const Args& a, const Tile& t, SegCtrl& c, TopkSel& k,
+                                          uint32_t* lds, uint32_t* lds_base) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
-  SegCtrl& c = a.ctrl[t.seg];
-  const uint32_t T = c.prefix;
-  const uint32_t take = c.k_rem;  // ties to keep
-  const bool rank_ties = c.rank_ties != 0;
-  const bool none = SEG && c.select_none != 0;
-  const int64_t out0 = SEG ? c.out_base : 0;
-  const int64_t cap = SEG ? c.cap : a.flat_cap;
+  const uint32_t T = k.T;
   uint32_t sure = 0, near = 0, eq = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
-    if ((FULL || ((valid >> i) & 1u)) && !none) {
+    if ((FULL || ((valid >> i) & 1u)) && !k.none) {
       const uint32_t key = mag_key(v[i]);
       sure |= ((key >> 7) > (T >> 7) ? 1u : 0u) << i;
       near |= (((key >> 7) == (T >> 7)) && key > T ? 1u : 0u) << i;
@@ -248,44 +249,42 @@ __device__ inline void topk_compact_tile(const Args& a, const Tile& t, uint32_t 
     }
   }
   uint32_t first[kSlots];
-  tile_rank(sure, lds, first);
-  {
-    const int64_t o = out0 + (int64_t)a.tile_base[tile_id];
+  const uint32_t n_sure = tile_rank(sure, lds, first);
 #pragma unroll
-    for (int j = 0; j < kSlots; ++j) {
-      uint32_t r = first[j];
-      const int64_t i0 = slot_index(t, j);
+  for (int j = 0; j < kSlots; ++j) {
+    uint32_t r = k.tile_sure0 + k.sure_run + first[j];
+    const int64_t i0 = slot_index(t, j);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if ((sure >> (4 * j + q)) & 1u) {
-          if ((int64_t)a.tile_base[tile_id] + r < cap) {
-            a.out_idx[o + r] = (uint32_t)(i0 + q);
-            a.out_val[o + r] = v[4 * j + q];
-          }
-          ++r;
+    for (int q = 0; q < 4; ++q) {
+      if ((sure >> (4 * j + q)) & 1u) {
+        if ((int64_t)r < k.cap) {
+          a.out_idx[k.out0 + r] = (uint32_t)(i0 + q);
+          a.out_val[k.out0 + r] = v[4 * j + q];
         }
+        ++r;
       }
     }
   }
-  // the rest: same leading bits as T.  Block-uniform early out when the tile has none.
+  k.sure_run += n_sure;
+  // the rest: same leading bits as T.  Block-uniform early out when the chunk has none.
   if (__syncthreads_or((near | eq) != 0)) {
-    if (rank_ties) {
+    if (k.rank_ties) {
       // keep a tie only if fewer than `take` ties precede it in index order
-      const uint32_t n_before = a.tie_base[tile_id];
-      tile_rank(eq, lds, first);
+      const uint32_t n_eq = tile_rank(eq, lds, first);
       uint32_t kept = 0;
 #pragma unroll
       for (int j = 0; j < kSlots; ++j) {
-        uint32_t r = n_before + first[j];
+        uint32_t r = k.tie_run + first[j];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if ((eq >> (4 * j + q)) & 1u) {
-            if (r < take) kept |= 1u << (4 * j + q);
+            if (r < k.take) kept |= 1u << (4 * j + q);
             ++r;
           }
         }
       }
       eq = kept;
+      k.tie_run += n_eq;
       __syncthreads();
     }
     near |= eq;
@@ -301,9 +300,9 @@ __device__ inline void topk_compact_tile(const Args& a, const Tile& t, uint32_t 
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if ((near >> (4 * j + q)) & 1u) {
-            if ((int64_t)r < cap) {
-              a.out_idx[out0 + r] = (uint32_t)(i0 + q);
-              a.out_val[out0 + r] = v[4 * j + q];
+            if ((int64_t)r < k.cap) {
+              a.out_idx[k.out0 + r] = (uint32_t)(i0 + q);
+              a.out_val[k.out0 + r] = v[4 * j + q];
             }
             ++r;
           }
@@ -324,17 +323,32 @@ __device__ inline void topk_compact_tile(const Args& a, const Tile& t, uint32_t 
       if ((sel >> i) & 1u) v[i] = 0.0f;
     store_tile<FULL>(a.resid, t, v, valid);
   }
+  __syncthreads();  // lds and lds_base are reused by the next chunk
 }
 
 template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_topk_compact(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ uint32_t lds_base;
-  Tile t;
-  if (!locate_tile<SEG>(a, blockIdx.x, &t)) return;
-  if (SEG && a.ctrl[t.seg].bad) return;
-  if (t.full) topk_compact_tile<SEG, true>(a, t, blockIdx.x, lds, &lds_base);
-  else topk_compact_tile<SEG, false>(a, t, blockIdx.x, lds, &lds_base);
+  Span sp_;
+  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
+  SegCtrl& c = a.ctrl[sp_.seg];
+  if (SEG && c.bad) return;
+  TopkSel k;
+  k.T = c.prefix;
+  k.take = c.k_rem;
+  k.rank_ties = c.rank_ties != 0;
+  k.none = SEG && c.select_none != 0;
+  k.out0 = SEG ? c.out_base : 0;
+  k.cap = SEG ? c.cap : a.flat_cap;
+  k.sure_run = 0;
+  k.tie_run = k.rank_ties ? a.tie_base[blockIdx.x] : 0u;
+  k.tile_sure0 = a.tile_base[blockIdx.x];
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) topk_compact_chunk<true>(a, t, c, k, lds, &lds_base);
+    else topk_compact_chunk<false>(a, t, c, k, lds, &lds_base);
+  }
 }
 
 }  // namespace sp

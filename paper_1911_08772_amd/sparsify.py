@@ -24,7 +24,7 @@ RESULT_BYTES = RESULT_DTYPE.itemsize  # 80
 
 
 class Opts(C.Structure):
-    _fields_ = [("tail_div", C.c_double), ("ddof", C.c_int32), ("reserved", C.c_int32),
+    _fields_ = [("tail_div", C.c_double), ("ddof", C.c_int32), ("tile_chunks", C.c_int32),
                 ("trace", C.c_void_p)]
 
 
@@ -77,8 +77,9 @@ def _stream(stream) -> int:
     return stream.cuda_stream
 
 
-def _opts(tail_div: float, ddof: int, trace) -> Opts:
-    return Opts(float(tail_div), int(ddof), 0, trace.handle if trace is not None else None)
+def _opts(tail_div: float, ddof: int, trace, tile_chunks: int = 0) -> Opts:
+    return Opts(float(tail_div), int(ddof), int(tile_chunks),
+                trace.handle if trace is not None else None)
 
 
 def version() -> str:
@@ -116,8 +117,8 @@ class Trace:
 
 def sparsify_gaussiank(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                        workspace_nbytes, tail_div=2.0, ddof=1, trace=None, stream=None,
-                       check=True) -> int:
-    o = _opts(tail_div, ddof, trace)
+                       check=True, tile_chunks=0) -> int:
+    o = _opts(tail_div, ddof, trace, tile_chunks)
     rc = lib.sparsify_gaussiank(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                                 _ptr(out_val), cap, _ptr(result), _ptr(workspace),
                                 workspace_nbytes, C.byref(o), _stream(stream))
@@ -127,8 +128,8 @@ def sparsify_gaussiank(d, k, grad, residual, acc, out_idx, out_val, cap, result,
 
 
 def sparsify_topk(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
-                  workspace_nbytes, trace=None, stream=None, check=True) -> int:
-    o = _opts(2.0, 1, trace)
+                  workspace_nbytes, trace=None, stream=None, check=True, tile_chunks=0) -> int:
+    o = _opts(2.0, 1, trace, tile_chunks)
     rc = lib.sparsify_topk(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                            _ptr(out_val), cap, _ptr(result), _ptr(workspace), workspace_nbytes,
                            C.byref(o), _stream(stream))
@@ -139,8 +140,9 @@ def sparsify_topk(d, k, grad, residual, acc, out_idx, out_val, cap, result, work
 
 def sparsify_segmented(num_segments, d_total, seg_off, seg_k, mode, grad, residual, acc, out_idx,
                        out_val, out_off, out_cap, results, workspace, workspace_nbytes,
-                       tail_div=2.0, ddof=1, trace=None, stream=None, check=True) -> int:
-    o = _opts(tail_div, ddof, trace)
+                       tail_div=2.0, ddof=1, trace=None, stream=None, check=True,
+                       tile_chunks=0) -> int:
+    o = _opts(tail_div, ddof, trace, tile_chunks)
     rc = lib.sparsify_segmented(num_segments, d_total, _ptr(seg_off), _ptr(seg_k), mode,
                                 _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                                 _ptr(out_val), _ptr(out_off), out_cap, _ptr(results),
