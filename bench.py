@@ -24,7 +24,7 @@ KERNEL_BYTES_PER_ELEM = {"accum_moments": 12, "gk_count": 4, "gk_compact": 8,
                          "topk_accum_hist": 12, "topk_hist1": 4, "topk_hist2": 4,
                          "topk_hist3": 4, "topk_compact": 8, "topk_tie_count": 0}
 GK_BYTES_PER_ELEM = 24   # r g, r eps, w acc | r acc (one count pass) | r acc, w eps'
-TOPK_BYTES_PER_ELEM = 36  # r g, r eps, w acc | 3 further digit passes | r acc, w eps'
+TOPK_BYTES_PER_ELEM = 32  # r g, r eps, w acc (+digit 1) | 3 further digit passes | r acc, w eps'
 
 
 def main() -> int:
@@ -36,6 +36,8 @@ def main() -> int:
     ap.add_argument("--inplace", action="store_true", help="acc aliases residual")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile-chunks", type=int, default=0, help="tuning: 4096-element chunks per workgroup")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain copy kernel of 4d bytes each way (counter scaling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "
@@ -106,6 +108,12 @@ def main() -> int:
             rounds.append(int(r["rounds"]))
         return {n: v / K for n, v in sums.items()}, nnz, rounds
 
+    if args.calibration_copy:
+        n4 = d - d % 4
+        for _ in range(3):
+            S.sparsify_calibration_copy(b.acc, grads[0], n4, stream=stream)
+        torch.cuda.synchronize()
+
     gk_ms, gk_wall, gk_ev = timed(S.sparsify_gaussiank)
     gk_stage, gk_nnz, gk_rounds = traced(S.sparsify_gaussiank)
     tk_ms, tk_wall, tk_ev = timed(S.sparsify_topk)
@@ -120,13 +128,7 @@ def main() -> int:
     dom = max((n for n in gk_stage if KERNEL_BYTES_PER_ELEM.get(n, 0) > 0), key=lambda n: gk_stage[n])
     dom_bytes = KERNEL_BYTES_PER_ELEM[dom] * d
     dom_gbps = dom_bytes / (gk_stage[dom] * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
-        except Exception:
-            traffic = None
+    traffic = read_traffic(args.workload, dom)
 
     out = {
         "metric": "Gaussian-k sparsify GB/s (algorithmic bytes) at d=25.6M, rho=0.001; exact Top-k beside it",
@@ -157,6 +159,19 @@ def main() -> int:
         out["cpu_baseline"] = cpu_baseline(wl, cap)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def read_traffic(workload: str, kernel: str):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this
+    workload (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel), or None."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith(f"traffic kernel={kernel} "):
+                return float(line.split("bytes_per_launch=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(wl, cap):

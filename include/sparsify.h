@@ -135,6 +135,11 @@ const char* sparsify_trace_stage_name(const sparsify_trace* t, int32_t i);
  * SPARSIFY_E_INVALID if i is out of range or the events are not complete */
 int sparsify_trace_stage_ms(sparsify_trace* t, int32_t i, float* ms);
 
+/* Measurement aid: copies n floats (n a positive multiple of 4; both DEVICE pointers 16-byte
+ * aligned, not overlapping) with one plain kernel that reads 4n bytes and writes 4n bytes.
+ * Hardware byte counters of the compressor's kernels are scaled by what they read for this one. */
+int sparsify_calibration_copy(float* dst, const float* src, int64_t n, void* stream);
+
 /* Library version string (static storage). */
 const char* sparsify_version(void);
 

@@ -45,7 +45,7 @@ struct MomAcc {
 template <bool FULL>
 __device__ inline void accum_moments_chunk(const Args& a, const Tile& t, MomAcc& m) {
   float g[kPerThread], e[kPerThread];
-  const uint32_t valid = load_tile<FULL>(a.grad, t, g);
+  const uint32_t valid = load_tile<FULL, true>(a.grad, t, g);
   load_tile<FULL>(a.resid, t, e);
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) g[i] = g[i] + e[i];  // Eq. (2): one fp32 add

@@ -23,6 +23,16 @@ __global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
     p[i] = v;
 }
 
+// Plain copy of n floats (n a multiple of 4, both pointers 16-byte aligned): a kernel of known
+// traffic, 4n bytes read and 4n written, against which hardware byte counters are scaled.
+__global__ __launch_bounds__(kBlock) void k_calibration_copy(float* dst, const float* src, size_t n4) {
+  const float4* s4 = reinterpret_cast<const float4*>(src);
+  float4* d4 = reinterpret_cast<float4*>(dst);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+       i += (size_t)gridDim.x * blockDim.x)
+    d4[i] = s4[i];
+}
+
 // Flat Top_k: reset the selection state and the histogram (one block of 256 threads).
 __global__ __launch_bounds__(kBlock) void k_topk_init_flat(const Args a) {
   for (uint32_t r = 0; r < a.hist_copies; ++r) a.hist[r * 256 + threadIdx.x] = 0;

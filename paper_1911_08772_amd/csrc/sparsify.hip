@@ -281,6 +281,17 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   return ln.err == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;
 }
 
+int sparsify_calibration_copy(float* dst, const float* src, int64_t n, void* stream) {
+  if (!dst || !src || n < 4 || (n & 3) != 0 || misaligned(dst, 16) || misaligned(src, 16))
+    return SPARSIFY_E_INVALID;
+  if (overlap(range_of(dst, 4 * (size_t)n), range_of(src, 4 * (size_t)n))) return SPARSIFY_E_INVALID;
+  const size_t n4 = (size_t)n / 4;
+  const size_t want = (n4 + kBlock - 1) / kBlock;
+  k_calibration_copy<<<dim3((unsigned)(want < 65536 ? want : 65536)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream)>>>(dst, src, n4);
+  return hipGetLastError() == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;
+}
+
 sparsify_trace* sparsify_trace_create(void) {
   sparsify_trace* t = new (std::nothrow) sparsify_trace();
   if (!t) return nullptr;

@@ -11,14 +11,19 @@ __device__ inline int64_t slot_index(const Tile& t, int slot) {
   return t.tbase + (int64_t)(slot * kBlock + (int)threadIdx.x) * 4;
 }
 
-// returns the validity mask (bit e set if element e of this thread is inside the tile's range)
-template <bool FULL>
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// returns the validity mask (bit e set if element e of this thread is inside the tile's range).
+// STREAM marks data that will not be read again soon (non-temporal: it should not displace
+// what later passes re-read from the caches).
+template <bool FULL, bool STREAM = false>
 __device__ inline uint32_t load_tile(const float* __restrict__ p, const Tile& t,
                                      float (&v)[kPerThread]) {
   if (FULL) {
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) {
-      const float4 q = *reinterpret_cast<const float4*>(p + slot_index(t, j));
+      const f32x4* src = reinterpret_cast<const f32x4*>(p + slot_index(t, j));
+      const f32x4 q = STREAM ? __builtin_nontemporal_load(src) : *src;
       v[4 * j + 0] = q.x;
       v[4 * j + 1] = q.y;
       v[4 * j + 2] = q.z;

@@ -39,6 +39,7 @@ lib.sparsify_gaussiank.argtypes = _flat
 lib.sparsify_topk.argtypes = _flat
 lib.sparsify_segmented.argtypes = [C.c_int32, C.c_int64, _p, _p, C.c_int32, _p, _p, _p, _p, _p,
                                    _p, C.c_int64, _p, _p, C.c_size_t, C.POINTER(Opts), _p]
+lib.sparsify_calibration_copy.argtypes = [_p, _p, C.c_int64, _p]
 lib.sparsify_trace_create.restype = _p
 lib.sparsify_trace_destroy.argtypes = [_p]
 lib.sparsify_trace_destroy.restype = None
@@ -48,7 +49,7 @@ lib.sparsify_trace_stage_name.restype = C.c_char_p
 lib.sparsify_trace_stage_ms.argtypes = [_p, C.c_int32, C.POINTER(C.c_float)]
 
 EXPORTS = ["sparsify_version", "sparsify_workspace_bytes", "sparsify_gaussiank", "sparsify_topk",
-           "sparsify_segmented", "sparsify_trace_create", "sparsify_trace_destroy",
+           "sparsify_segmented", "sparsify_calibration_copy", "sparsify_trace_create", "sparsify_trace_destroy",
            "sparsify_trace_num_stages", "sparsify_trace_stage_name", "sparsify_trace_stage_ms"]
 
 
@@ -149,6 +150,13 @@ def sparsify_segmented(num_segments, d_total, seg_off, seg_k, mode, grad, residu
                                 _ptr(workspace), workspace_nbytes, C.byref(o), _stream(stream))
     if check and rc != OK:
         raise SparsifyError(rc, "sparsify_segmented")
+    return rc
+
+
+def sparsify_calibration_copy(dst, src, n, stream=None, check=True) -> int:
+    rc = lib.sparsify_calibration_copy(_ptr(dst), _ptr(src), n, _stream(stream))
+    if check and rc != OK:
+        raise SparsifyError(rc, "sparsify_calibration_copy")
     return rc
 
 
