@@ -62,7 +62,7 @@ def main() -> int:
 
     # fresh gradients, generated on the host and parked in HBM before any timing
     host = np.empty(d, np.float32)
-    grads = torch.empty((n_grads, d), dtype=torch.float32, device=dev)
+    grads = [torch.empty(d, dtype=torch.float32, device=dev) for _ in range(n_grads)]
     for s in range(n_grads):
         wl.grad(s, out=host)
         grads[s].copy_(torch.from_numpy(host))

@@ -78,6 +78,7 @@ struct Args {
   uint32_t hist_copies;   // replicas of each segment's histogram (spreads the atomics)
   uint32_t max_tiles;
   uint32_t tile_chunks;   // chunks per tile
+  uint32_t moment_parts;  // flat calls: number of moment partials (accumulate workgroups)
   int32_t ddof;
   double tail_div;
 };

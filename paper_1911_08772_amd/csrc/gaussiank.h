@@ -80,9 +80,47 @@ __device__ inline void accum_moments_chunk(const Args& a, const Tile& t, MomAcc&
   }
 }
 
+// Combines the four waves' shifted sums around the first wave's pivot (no merge divisions) and
+// stores the workgroup's (n, mean, M2) as partial `slot`.
+__device__ inline void store_moment_partial(const Args& a, const MomAcc& m, uint32_t slot,
+                                            double* lds) {
+  const double n = wave_sum(m.n), s1 = wave_sum(m.s1), s2 = wave_sum(m.s2);
+  if (lane_id() == 0) {
+    double* w = lds + 4 * wave_id();
+    w[0] = n;
+    w[1] = s1;
+    w[2] = s2;
+    w[3] = m.pivot;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double N = 0.0, S1 = 0.0, S2 = 0.0, P = 0.0;
+    bool have = false;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const double nw = lds[4 * w], s1w = lds[4 * w + 1], s2w = lds[4 * w + 2], pw = lds[4 * w + 3];
+      if (nw > 0.0) {
+        if (!have) {
+          P = pw;
+          have = true;
+        }
+        const double dp = pw - P;  // sum (x-P) = s1 + n dp ; sum (x-P)^2 = s2 + 2 dp s1 + n dp^2
+        N += nw;
+        S1 += fma(nw, dp, s1w);
+        S2 += s2w + dp * fma(nw, dp, 2.0 * s1w);
+      }
+    }
+    const double mean = N > 0.0 ? P + S1 / N : 0.0;
+    const double m2 = N > 0.0 ? S2 - S1 * (S1 / N) : 0.0;
+    a.partial[slot] = N;
+    a.partial[(size_t)a.max_tiles + slot] = mean;
+    a.partial[2 * (size_t)a.max_tiles + slot] = m2 < 0.0 ? 0.0 : m2;  // rounding only; NaN stays
+  }
+}
+
 template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
-  __shared__ double lds[3 * kWaves];
+  __shared__ double lds[4 * kWaves];
   Span sp_;
   if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
   if (SEG && a.ctrl[sp_.seg].bad) return;
@@ -92,28 +130,32 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
     if (t.full) accum_moments_chunk<true>(a, t, m);
     else accum_moments_chunk<false>(a, t, m);
   }
-  const double n = wave_sum(m.n), s1 = wave_sum(m.s1), s2 = wave_sum(m.s2);
-  if (lane_id() == 0) {
-    double* w = lds + 3 * wave_id();
-    const double mean = n > 0.0 ? m.pivot + s1 / n : 0.0;
-    const double m2 = n > 0.0 ? s2 - s1 * (s1 / n) : 0.0;
-    w[0] = n;
-    w[1] = mean;
-    w[2] = m2 < 0.0 ? 0.0 : m2;  // rounding only; NaN stays NaN
+  store_moment_partial(a, m, blockIdx.x, lds);
+  if (!SEG && blockIdx.x == 0 && threadIdx.x == 0) {
+    // The quantile depends on the arguments only; compute it here, hidden under the stream.
+    a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    Moments r = {lds[0], lds[1], lds[2]};
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) r = merge(r, Moments{lds[3 * w], lds[3 * w + 1], lds[3 * w + 2]});
-    a.partial[blockIdx.x] = r.n;
-    a.partial[(size_t)a.max_tiles + blockIdx.x] = r.mean;
-    a.partial[2 * (size_t)a.max_tiles + blockIdx.x] = r.m2;
-    if (!SEG && blockIdx.x == 0) {
-      // The quantile depends on the arguments only; compute it here, hidden under the stream.
-      a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
-    }
+}
+
+// Flat calls: a resident grid walks the chunks with a grid stride and leaves one partial per
+// workgroup (the moments need no particular partition of the vector).
+__global__ __launch_bounds__(kBlock) void k_accum_moments_flat(const Args a) {
+  __shared__ double lds[4 * kWaves];
+  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
+  for (uint32_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+    Tile t;
+    t.seg = 0;
+    t.tbase = (int64_t)ch * kChunk;
+    t.lo = t.tbase;
+    t.hi = (t.tbase + kChunk < a.d_total) ? t.tbase + kChunk : a.d_total;
+    t.full = t.tbase + kChunk <= a.d_total;
+    if (t.full) accum_moments_chunk<true>(a, t, m);
+    else accum_moments_chunk<false>(a, t, m);
   }
+  store_moment_partial(a, m, blockIdx.x, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0)
+    a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
 }
 
 // ---- K2: per segment, combine partials -> mean, std, threshold candidates -------------------
@@ -137,7 +179,7 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
   __shared__ double lds[kFinWaves];
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
-  uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  uint32_t tile0 = 0, ntiles = a.moment_parts;  // flat: one partial per accumulate workgroup
   int64_t n_seg = a.d_total;
   if (SEG) {
     if (c.bad) return;

@@ -168,10 +168,34 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   return SPARSIFY_OK;
 }
 
+// Workgroups of `kernel` that fit on the device at once (cached per kernel; falls back to a
+// conservative figure if the runtime cannot tell).
+template <class K>
+uint32_t resident_blocks(K kernel, int block) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block, 0) != hipSuccess ||
+      cus < 1 || per_cu < 1)
+    return 1024;
+  return (uint32_t)cus * (uint32_t)per_cu;
+}
+
 template <bool SEG>
-void launch_gaussiank(Launcher& ln, const Args& a, uint32_t tiles) {
+void launch_gaussiank(Launcher& ln, Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
-  ln.run("accum_moments", k_accum_moments<SEG>, dim3(tiles), blk, a);
+  if (SEG) {
+    ln.run("accum_moments", k_accum_moments<SEG>, dim3(tiles), blk, a);
+  } else {
+    static const uint32_t resident = resident_blocks(k_accum_moments_flat, kBlock);
+    uint32_t want = resident;
+    const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+    if (want > nchunks) want = nchunks;
+    if (want > a.max_tiles) want = a.max_tiles;
+    if (want < 1) want = 1;
+    a.moment_parts = want;
+    ln.run("accum_moments", k_accum_moments_flat, dim3(want), blk, a);
+  }
   ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), dim3(kFinBlock), a);
   ln.run("gk_count", k_gk_count<SEG>, dim3(tiles), blk, a);
   ln.run("gk_decide", k_gk_decide<SEG>, dim3(a.L), dim3(kFinBlock), a);
