@@ -13,7 +13,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kSlots = 4;                         // float4 loads per thread per tile
 constexpr int kPerThread = 4 * kSlots;            // 16 elements per thread
 constexpr int kChunk = kBlock * kPerThread;       // 4096 elements = 16 KiB per array
-// A workgroup's unit of work, a "tile", is `tile_chunks` consecutive chunks (chosen per call so
+// A workgroup's unit of work, a "tile", is `tile_chunks` (odd) consecutive chunks (chosen per call so
 // that a vector has at most about four thousand tiles: the per-tile partial results that the
 // small per-segment kernels must combine then stay few, whatever d is).
 constexpr int kNumThres = 10;                     // thresholds reachable by <= 3 nudges
@@ -73,6 +73,7 @@ struct Args {
   double* partial;        // [3][max_tiles]: n, mean, M2
   uint32_t* tile_counts;  // [kNumThres][max_tiles]
   uint32_t* tile_base;    // [max_tiles]
+  uint32_t* group_counts; // [64][kNumThres]: totals of groups of 64 tiles (fused flat path)
   uint32_t* hist;         // [L][hist_copies][256]
   uint32_t* tie_base;     // [max_tiles]
   uint32_t hist_copies;   // replicas of each segment's histogram (spreads the atomics)

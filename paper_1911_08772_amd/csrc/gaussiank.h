@@ -158,6 +158,50 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_flat(const Args a) {
     a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
 }
 
+// The ten thresholds reachable from thres0 (Alg. 1 steps 8-11): `na` multiplications by 1.5 in
+// sequence, then halvings (exact), stored in ascending order of their nominal ratio to thres0.
+__device__ inline void candidate_thresholds(double thres0, double (&t64)[kNumThres]) {
+  double up = thres0;
+#pragma unroll
+  for (int na = 0; na <= 3; ++na) {
+    double v = up;
+#pragma unroll
+    for (int nb = 0; nb <= 3 - na; ++nb) {
+      t64[thres_pos(na, nb)] = v;
+      v = 0.5 * v;
+    }
+    up = 1.5 * up;
+  }
+}
+
+// Alg. 1 steps 5-13 on the ten totals: at most four evaluations ("for i = 0 -> 3"); the mask
+// is the one of the last evaluated threshold.  Returns its position.
+struct Walk {
+  int pos;
+  uint32_t rounds;
+  uint32_t counts[4];
+  bool in_band;
+};
+__device__ inline Walk walk_thresholds(const uint32_t (&tot)[kNumThres], int64_t k) {
+  Walk w = {0, 0, {0, 0, 0, 0}, false};
+  int na = 0, nb = 0;
+  for (int round = 0; round <= 3; ++round) {
+    w.pos = thres_pos(na, nb);
+    const int64_t est = tot[w.pos];
+    w.counts[round] = tot[w.pos];
+    w.rounds = round + 1;
+    if (3 * est < 2 * k) {          // estimated_k < 2k/3: halve the threshold
+      if (round < 3) ++nb;
+    } else if (3 * est > 4 * k) {   // estimated_k > 4k/3: threshold x 1.5
+      if (round < 3) ++na;
+    } else {
+      w.in_band = true;
+      break;
+    }
+  }
+  return w;
+}
+
 // ---- K2: per segment, combine partials -> mean, std, threshold candidates -------------------
 // Two passes over the per-tile partials, no divisions per partial:
 //   N = sum n_i, mean = sum n_i mean_i / N, M2 = sum (M2_i + n_i (mean_i - mean)^2).
@@ -227,18 +271,12 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
 
   const double sd = (n_seg - a.ddof < 1) ? 0.0 : sqrt(m2 / (double)(n_seg - a.ddof));
   const double thres0 = mean + sd * z;
-  // candidate thresholds: `na` multiplications by 1.5 in sequence, then halvings (exact),
-  // stored in ascending order of their nominal ratio to thres0
-  double up = thres0;
-  for (int na = 0; na <= 3; ++na) {
-    double v = up;
-    for (int nb = 0; na + nb <= 3; ++nb) {
-      const int p = thres_pos(na, nb);
-      c.t64[p] = v;
-      c.t32[p] = (float)v;
-      v = 0.5 * v;
-    }
-    up = 1.5 * up;
+  double t64[kNumThres];
+  candidate_thresholds(thres0, t64);
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) {
+    c.t64[p] = t64[p];
+    c.t32[p] = (float)t64[p];
   }
   c.sorted_ok = thres0 > 0.0 ? 1u : 0u;
   uint32_t flags = 0;
@@ -255,10 +293,9 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
 // The thresholds sit in ascending order, so once no element of a wave's slot exceeds one of them
 // the larger ones need not be tested (only when the ordering is known to hold).
 template <bool FULL>
-__device__ inline void count_chunk(const Args& a, const Tile& t, const float (&thr)[kNumThres],
-                                   bool can_skip, uint32_t (&cnt)[kNumThres]) {
-  float v[kPerThread];
-  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+__device__ inline void count_values(const float (&v)[kPerThread], uint32_t valid,
+                                    const float (&thr)[kNumThres], bool can_skip,
+                                    uint32_t (&cnt)[kNumThres]) {
 #pragma unroll
   for (int j = 0; j < kSlots; ++j) {
     float m[4];
@@ -297,6 +334,14 @@ __device__ inline void count_chunk(const Args& a, const Tile& t, const float (&t
       }
     }
   }
+}
+
+template <bool FULL>
+__device__ inline void count_chunk(const Args& a, const Tile& t, const float (&thr)[kNumThres],
+                                   bool can_skip, uint32_t (&cnt)[kNumThres]) {
+  float v[kPerThread];
+  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+  count_values<FULL>(v, valid, thr, can_skip, cnt);
 }
 
 // The tiles are visited from the last to the first: the end of acc is what the accumulate
@@ -434,24 +479,11 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
       for (int w = 0; w < kFinWaves; ++w) tot[p] += lds_cnt[w * kNumThres + p];
     }
     sparsify_result& r = a.result[s];
-    int na = 0, nb = 0, p = 0;
-    bool in_band = false;
-    uint32_t rounds = 0;
-    uint32_t counts[4] = {0, 0, 0, 0};
-    for (int round = 0; round <= 3; ++round) {  // "for i = 0 -> 3": four evaluations at most
-      p = thres_pos(na, nb);
-      const int64_t est = tot[p];
-      counts[round] = tot[p];
-      rounds = round + 1;
-      if (3 * est < 2 * k) {          // estimated_k < 2k/3: halve the threshold
-        if (round < 3) ++nb;
-      } else if (3 * est > 4 * k) {   // estimated_k > 4k/3: threshold x 1.5
-        if (round < 3) ++na;
-      } else {
-        in_band = true;
-        break;
-      }
-    }
+    const Walk w = walk_thresholds(tot, k);
+    const int p = w.pos;
+    const bool in_band = w.in_band;
+    const uint32_t rounds = w.rounds;
+    const uint32_t* counts = w.counts;
     if (!in_band) flags |= SPARSIFY_F_EXHAUSTED;
     const bool overflow = (int64_t)tot[p] > cap;
     if (overflow) flags |= SPARSIFY_F_OVERFLOW;
@@ -478,10 +510,9 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
 // ---- K5: compaction in index order + residual (Alg. 1 step 14, Eq. (2)) ----------------------
 // `run` is the number of survivors of this tile's earlier chunks (block-uniform).
 template <bool FULL>
-__device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr, bool none,
-                                         int64_t out0, uint32_t run, uint32_t* lds) {
-  float v[kPerThread];
-  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+__device__ inline uint32_t compact_values(const Args& a, const Tile& t, float (&v)[kPerThread],
+                                          uint32_t valid, float thr, bool none, int64_t out0,
+                                          uint32_t run, uint32_t* lds) {
   uint32_t sel = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
@@ -519,6 +550,14 @@ __device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr
   }
   __syncthreads();  // lds is reused by the next chunk
   return run + total;
+}
+
+template <bool FULL>
+__device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr, bool none,
+                                         int64_t out0, uint32_t run, uint32_t* lds) {
+  float v[kPerThread];
+  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+  return compact_values<FULL>(a, t, v, valid, thr, none, out0, run, lds);
 }
 
 template <bool SEG>

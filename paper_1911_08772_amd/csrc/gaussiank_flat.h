@@ -1,0 +1,219 @@
+// Gaussian_k, flat vectors: three launches instead of five.  A launch costs 3-4 us on the
+// stream even when the kernel does nothing, and a single workgroup that combines per-tile
+// partials is latency-bound; here every workgroup of the count kernel derives the thresholds
+// from the (few) moment partials itself, and every workgroup of the compact kernel walks
+// Algorithm 1 and finds its own output base from per-group totals.  All workgroups run the same
+// arithmetic on the same inputs in the same order, so they agree bit for bit.
+//
+// Used when the vector has at most kFusedMaxTiles tiles (always, unless tile_chunks is forced).
+#pragma once
+#include "common.h"
+#include "gaussiank.h"
+#include "tile_io.h"
+
+namespace sp {
+
+constexpr int kGroupTiles = 64;                                   // tiles per group
+constexpr int kFusedMaxTiles = 4096;
+constexpr int kMaxGroups = kFusedMaxTiles / kGroupTiles;          // 64
+constexpr int kMaxMomentParts = 1024;                             // accumulate workgroups at most
+
+// K1: the accumulate kernel of gaussiank.h (k_accum_moments_flat); its workgroup 0 also clears
+// the group totals the count kernel adds into.
+__global__ __launch_bounds__(kBlock) void k_accum_moments_fused(const Args a) {
+  __shared__ double lds[4 * kWaves];
+  if (blockIdx.x == 0) {
+    for (uint32_t i = threadIdx.x; i < (uint32_t)(kMaxGroups * kNumThres); i += kBlock)
+      a.group_counts[i] = 0;
+  }
+  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
+  for (uint32_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+    Tile t;
+    t.seg = 0;
+    t.tbase = (int64_t)ch * kChunk;
+    t.lo = t.tbase;
+    t.hi = (t.tbase + kChunk < a.d_total) ? t.tbase + kChunk : a.d_total;
+    t.full = t.tbase + kChunk <= a.d_total;
+    if (t.full) accum_moments_chunk<true>(a, t, m);
+    else accum_moments_chunk<false>(a, t, m);
+  }
+  store_moment_partial(a, m, blockIdx.x, lds);
+  if (blockIdx.x == 0 && threadIdx.x == 0)
+    a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
+}
+
+// K3: thresholds from the moment partials (every workgroup), then the ten counts of its tile.
+// One pass over the partials around the provisional centre P = mean of partial 0:
+//   A = sum n_i (mean_i - P), B = sum M2_i + n_i (mean_i - P)^2, mean = P + A/N, M2 = B - A^2/N.
+__global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
+  __shared__ double lds_m[2 * kWaves];
+  __shared__ uint32_t lds[kWaves * kNumThres];
+  const uint32_t tile = gridDim.x - 1u - blockIdx.x;  // backwards: see k_gk_count
+  Span sp_;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[0];
+  const uint32_t parts = a.moment_parts;
+  const double* pn = a.partial;
+  const double* pm = pn + a.max_tiles;
+  const double* pq = pm + a.max_tiles;
+  const double z = c.z;
+  const double P = pm[0];
+  double A = 0.0, B = 0.0;
+  for (uint32_t b0 = 0; b0 < parts; b0 += 4 * kBlock) {  // four partials per thread per round
+    double n[4], mu[4], q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = b0 + u * kBlock + threadIdx.x;
+      const bool ok = i < parts;
+      n[u] = ok ? pn[i] : 0.0;
+      mu[u] = ok ? pm[i] : P;
+      q[u] = ok ? pq[i] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const double dm = mu[u] - P;
+      A = fma(n[u], dm, A);
+      B += fma(n[u] * dm, dm, q[u]);
+    }
+  }
+  A = wave_sum(A);
+  B = wave_sum(B);
+  if (lane_id() == 0) {
+    lds_m[2 * wave_id()] = A;
+    lds_m[2 * wave_id() + 1] = B;
+  }
+  __syncthreads();
+  A = 0.0;
+  B = 0.0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    A += lds_m[2 * w];
+    B += lds_m[2 * w + 1];
+  }
+  const double N = (double)a.d_total;
+  const double mean = P + A / N;
+  double m2 = B - A * (A / N);
+  m2 = m2 < 0.0 ? 0.0 : m2;
+  const double sd = (a.d_total - a.ddof < 1) ? 0.0 : sqrt(m2 / (double)(a.d_total - a.ddof));
+  const double thres0 = mean + sd * z;
+  double t64[kNumThres];
+  candidate_thresholds(thres0, t64);
+  float thr[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) thr[p] = (float)t64[p];
+  const bool can_skip = thres0 > 0.0;
+  if (tile == 0 && threadIdx.x == 0) {  // one workgroup publishes what every workgroup computed
+#pragma unroll
+    for (int p = 0; p < kNumThres; ++p) {
+      c.t64[p] = t64[p];
+      c.t32[p] = thr[p];
+    }
+    uint32_t flags = 0;
+    if (!isfinite(mean) || !isfinite(sd) || !isfinite(thres0)) flags |= SPARSIFY_F_NONFINITE;
+    c.flags = flags;
+    sparsify_result& r = a.result[0];
+    r.mean = mean;
+    r.std = sd;
+    r.z = z;
+    r.thres0 = thres0;
+  }
+
+  uint32_t cnt[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
+    else count_chunk<false>(a, t, thr, can_skip, cnt);
+  }
+  if (lane_id() == 0) {
+#pragma unroll
+    for (int p = 0; p < kNumThres; ++p) lds[wave_id() * kNumThres + p] = cnt[p];
+  }
+  __syncthreads();
+  if (threadIdx.x < kNumThres) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) s += lds[w * kNumThres + threadIdx.x];
+    a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile] = s;  // [threshold][tile]
+    if (s) atomicAdd(&a.group_counts[(tile / kGroupTiles) * kNumThres + threadIdx.x], s);
+  }
+}
+
+// K5: every workgroup totals the group counts, walks Alg. 1 steps 5-13, finds the first output
+// slot of its tile (groups before its own + tiles before it inside its group), then compacts.
+__global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
+  __shared__ uint32_t lds_g[kMaxGroups * kNumThres];    // group totals [group][threshold]
+  __shared__ uint32_t lds_t[kGroupTiles * kNumThres];   // counts of my group's tiles [threshold][tile]
+  __shared__ uint32_t lds_tot[kNumThres];
+  __shared__ uint32_t lds_base;
+  __shared__ uint32_t lds[kSlots * kWaves];
+  const uint32_t tile = blockIdx.x;
+  Span sp_;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[0];
+  const uint32_t ntiles = gridDim.x;
+  const uint32_t ngroups = (ntiles + kGroupTiles - 1) / kGroupTiles;
+  const uint32_t g = tile / kGroupTiles, g0 = g * kGroupTiles, within = tile - g0;
+
+  for (uint32_t i = threadIdx.x; i < ngroups * kNumThres; i += kBlock) lds_g[i] = a.group_counts[i];
+  for (uint32_t i = threadIdx.x; i < (uint32_t)(kGroupTiles * kNumThres); i += kBlock) {
+    const uint32_t p = i / kGroupTiles, j = i % kGroupTiles;
+    lds_t[i] = (j < within) ? a.tile_counts[(size_t)p * a.max_tiles + g0 + j] : 0u;
+  }
+  double t64[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) t64[p] = c.t64[p];
+  const uint32_t flags0 = c.flags;
+  __syncthreads();
+  if (threadIdx.x < kNumThres) {
+    uint32_t s = 0;
+    for (uint32_t j = 0; j < ngroups; ++j) s += lds_g[j * kNumThres + threadIdx.x];
+    lds_tot[threadIdx.x] = s;
+  }
+  __syncthreads();
+  uint32_t tot[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) tot[p] = lds_tot[p];
+  const Walk w = walk_thresholds(tot, a.flat_k);
+  const bool overflow = (int64_t)tot[w.pos] > a.flat_cap;
+  if (wave_id() == 0) {
+    uint32_t x = 0;
+    if ((uint32_t)lane_id() < g) x += lds_g[lane_id() * kNumThres + w.pos];      // kMaxGroups == 64 lanes
+    x += lds_t[w.pos * kGroupTiles + lane_id()];                                  // kGroupTiles == 64 lanes
+    x = wave_sum(x);
+    if (lane_id() == 0) lds_base = x;
+  }
+  __syncthreads();
+  const double tf = t64[w.pos];
+  const float thr = (float)tf;
+  if (tile == 0 && threadIdx.x == 0) {
+    uint32_t flags = flags0;
+    if (!w.in_band) flags |= SPARSIFY_F_EXHAUSTED;
+    if (overflow) flags |= SPARSIFY_F_OVERFLOW;
+    sparsify_result& r = a.result[0];
+    r.nnz = overflow ? 0u : tot[w.pos];
+    r.rounds = w.rounds;
+    r.count[0] = w.counts[0];
+    r.count[1] = w.counts[1];
+    r.count[2] = w.counts[2];
+    r.count[3] = w.counts[3];
+    r.flags = flags;
+    r.thres = tf;
+    r.thres_f32 = thr;
+    r.topk_key = 0;
+    r.topk_ties_taken = 0;
+  }
+  const int64_t out0 = (int64_t)lds_base;
+  uint32_t run = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) run = compact_chunk<true>(a, t, thr, overflow, out0, run, lds);
+    else run = compact_chunk<false>(a, t, thr, overflow, out0, run, lds);
+  }
+}
+
+static_assert(kMaxGroups == 64 && kGroupTiles == 64, "one lane per group and per tile of a group");
+
+}  // namespace sp

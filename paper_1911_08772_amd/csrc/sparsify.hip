@@ -8,6 +8,7 @@
 
 #include "common.h"
 #include "gaussiank.h"
+#include "gaussiank_flat.h"
 #include "setup.h"
 #include "sparsify.h"
 #include "topk.h"
@@ -55,13 +56,16 @@ struct Launcher {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-// Chunks per tile: the smallest power of two that keeps a vector of d elements within about
-// four thousand tiles (one workgroup each), so that the per-tile partials stay few.
+// Chunks per tile: the smallest odd number that keeps a vector of d elements within about four
+// thousand tiles (one workgroup each), so that the per-tile partials stay few.  Odd on purpose:
+// with a power-of-two tile size the workgroups, which advance in step, sit a power of two
+// bytes apart and crowd the same memory channels (measured: 4 chunks per tile 5 % slower than
+// 3 or 5).
 constexpr int64_t kTargetTiles = 4096;
 uint32_t tile_chunks_of(int64_t d_total) {
   const int64_t chunks = (d_total + kChunk - 1) / kChunk;
   uint32_t c = 1;
-  while ((chunks + c - 1) / c > kTargetTiles) c *= 2;
+  while ((chunks + c - 1) / c > kTargetTiles) c += 2;
   return c;
 }
 
@@ -75,7 +79,7 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
 uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
 
 struct Carve {
-  size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, hist, total;
+  size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, group_counts, hist, total;
 };
 Carve carve(int64_t d_total, int32_t L) {
   const size_t mt = max_tiles_of(d_total, L, 1);
@@ -87,6 +91,7 @@ Carve carve(int64_t d_total, int32_t L) {
   c.tile_counts = off; off = align_up(off + sizeof(uint32_t) * kNumThres * mt);
   c.tile_base = off;   off = align_up(off + sizeof(uint32_t) * mt);
   c.tie_base = off;    off = align_up(off + sizeof(uint32_t) * mt);
+  c.group_counts = off; off = align_up(off + sizeof(uint32_t) * kMaxGroups * kNumThres);
   c.hist = off;        off = align_up(off + sizeof(uint32_t) * 256 * (size_t)L * hist_copies_of(L));
   c.total = off;
   return c;
@@ -155,6 +160,7 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.tile_counts = reinterpret_cast<uint32_t*>(w + cv.tile_counts);
   a.tile_base = reinterpret_cast<uint32_t*>(w + cv.tile_base);
   a.tie_base = reinterpret_cast<uint32_t*>(w + cv.tie_base);
+  a.group_counts = reinterpret_cast<uint32_t*>(w + cv.group_counts);
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
   a.hist_copies = hist_copies_of(L);
   a.tile_chunks = tile_chunks_of(d_total);
@@ -184,17 +190,23 @@ uint32_t resident_blocks(K kernel, int block) {
 template <bool SEG>
 void launch_gaussiank(Launcher& ln, Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
-  if (SEG) {
-    ln.run("accum_moments", k_accum_moments<SEG>, dim3(tiles), blk, a);
-  } else {
-    static const uint32_t resident = resident_blocks(k_accum_moments_flat, kBlock);
-    uint32_t want = resident;
+  if (!SEG) {
+    static const uint32_t resident = resident_blocks(k_accum_moments_fused, kBlock);
     const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+    uint32_t want = resident < (uint32_t)kMaxMomentParts ? resident : (uint32_t)kMaxMomentParts;
     if (want > nchunks) want = nchunks;
     if (want > a.max_tiles) want = a.max_tiles;
     if (want < 1) want = 1;
     a.moment_parts = want;
+    if (tiles <= (uint32_t)kFusedMaxTiles) {  // three launches: see gaussiank_flat.h
+      ln.run("accum_moments", k_accum_moments_fused, dim3(want), blk, a);
+      ln.run("gk_count", k_gk_count_fused, dim3(tiles), blk, a);
+      ln.run("gk_compact", k_gk_compact_fused, dim3(tiles), blk, a);
+      return;
+    }
     ln.run("accum_moments", k_accum_moments_flat, dim3(want), blk, a);
+  } else {
+    ln.run("accum_moments", k_accum_moments<SEG>, dim3(tiles), blk, a);
   }
   ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), dim3(kFinBlock), a);
   ln.run("gk_count", k_gk_count<SEG>, dim3(tiles), blk, a);

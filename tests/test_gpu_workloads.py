@@ -14,7 +14,7 @@ from paper_1911_08772_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def chain(wl_name, selector, steps=None, inplace=False):
+def chain(wl_name, selector, steps=None, inplace=False, **kw):
     """Error-feedback chain on both sides, each keeping its own residual; every step compares the
     result record, the pair set and the complete residual (acc at the first and last step)."""
     wl = synth.workload(wl_name)
@@ -41,7 +41,7 @@ def chain(wl_name, selector, steps=None, inplace=False):
 
         th = threading.Thread(target=run_oracle)
         th.start()
-        got = gpu.step(selector, g, wl.k, fetch_dense=False)
+        got = gpu.step(selector, g, wl.k, fetch_dense=False, **kw)
         eps_g = gpu.b.residual.cpu().numpy()
         th.join()
         idx_o, val_o, _, ro = box["o"]
@@ -71,6 +71,13 @@ def test_cfg2_vgg16_sized_mixture(selector):
 @pytest.mark.parametrize("selector", ["gaussiank", "topk"])
 def test_cfg3_resnet50_sized(selector, wl):
     chain(wl, selector)
+
+
+def test_cfg3_one_chunk_per_tile():
+    """6240 tiles: beyond what the three-launch flat Gaussian_k path handles, so this runs the
+    five-launch path on a flat vector."""
+    chain("cfg3_resnet50", "gaussiank", steps=3, tile_chunks=1)
+    chain("cfg3_resnet50", "topk", steps=3, tile_chunks=1)
 
 
 def test_cfg3_inplace_mode():
