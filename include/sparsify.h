@@ -62,6 +62,9 @@ typedef struct {
   double thres;       /* fp64 threshold of the evaluation that produced the mask */
   uint32_t topk_key;        /* Top_k: bit pattern of the k-th largest |acc| */
   uint32_t topk_ties_taken; /* Top_k: selected entries whose magnitude equals that one */
+  double acc_sqnorm;        /* ||acc||^2 and ||acc - Comp_k(acc)||^2 = ||residual'||^2 in fp64: the */
+  double residual_sqnorm;   /* two sides of the contraction property (Eq. (3)-(5), Theorem 1).
+                               Filled only when sparsify_opts.error_norms is set, else 0. */
 } sparsify_result;
 
 /* HOST struct; pass NULL for the defaults. */
@@ -73,6 +76,9 @@ typedef struct {
   int32_t tile_chunks; /* 0 (default): automatic.  Otherwise the number of 4096-element chunks one
                       workgroup processes; a tuning knob, results do not depend on it */
   void* trace;     /* NULL, or a sparsify_trace* to record per-kernel timings of this call */
+  int32_t error_norms; /* 0 (default).  1: also reduce ||acc||^2 and ||residual'||^2 (fp64) into the
+                      result record; the sums ride on the compaction pass, one small launch more */
+  int32_t reserved;
 } sparsify_opts;
 
 /* Bytes of `workspace` needed for a vector of d_total elements in num_segments segments

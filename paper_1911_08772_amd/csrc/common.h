@@ -56,6 +56,7 @@ struct SegCtrl {
 struct Args {
   int32_t L;          // segments (1 for the flat calls)
   int32_t inplace;    // acc == residual
+  int32_t norms;      // also reduce ||acc||^2 and ||residual'||^2
   int64_t d_total;
   int64_t flat_k, flat_cap;
   const int64_t* seg_off;
@@ -74,6 +75,7 @@ struct Args {
   uint32_t* tile_counts;  // [kNumThres][max_tiles]
   uint32_t* tile_base;    // [max_tiles]
   uint32_t* group_counts; // [64][kNumThres]: totals of groups of 64 tiles (fused flat path)
+  double* norm_partial;   // [2][max_tiles]: per-tile sum of acc^2 and of residual'^2
   uint32_t* hist;         // [L][hist_copies][256]
   uint32_t* tie_base;     // [max_tiles]
   uint32_t hist_copies;   // replicas of each segment's histogram (spreads the atomics)
@@ -235,6 +237,43 @@ __device__ inline uint32_t tile_rank(uint32_t sel, uint32_t* lds, uint32_t (&fir
     }
   }
   return run;
+}
+
+// Squared norms that ride on the compaction pass: sum of x^2 over the valid elements of a tile,
+// and over those not selected (the residual).
+struct NormAcc {
+  double all, rest;
+};
+__device__ inline void norm_accumulate(NormAcc& n, const float (&v)[kPerThread], uint32_t valid,
+                                       uint32_t sel) {
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    if ((valid >> i) & 1u) {
+      const double x = (double)v[i];
+      n.all = fma(x, x, n.all);
+      if (!((sel >> i) & 1u)) n.rest = fma(x, x, n.rest);
+    }
+  }
+}
+// One barrier; `lds` holds 2 * kWaves doubles.
+__device__ inline void store_norm_partial(const Args& a, const NormAcc& n, uint32_t tile,
+                                          double* lds) {
+  const double x = wave_sum(n.all), y = wave_sum(n.rest);
+  if (lane_id() == 0) {
+    lds[2 * wave_id()] = x;
+    lds[2 * wave_id() + 1] = y;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double sx = 0.0, sy = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      sx += lds[2 * w];
+      sy += lds[2 * w + 1];
+    }
+    a.norm_partial[tile] = sx;
+    a.norm_partial[(size_t)a.max_tiles + tile] = sy;
+  }
 }
 
 // Running (count, mean, sum of squared deviations) and its pairwise merge.

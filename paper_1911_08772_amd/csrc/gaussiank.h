@@ -499,6 +499,8 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
     r.thres_f32 = (float)tf;
     r.topk_key = 0;
     r.topk_ties_taken = 0;
+    r.acc_sqnorm = 0.0;
+    r.residual_sqnorm = 0.0;
     c.t_final = (float)tf;
     c.select_none = overflow ? 1u : 0u;
     lds_final = (uint32_t)p;
@@ -509,16 +511,17 @@ __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
 
 // ---- K5: compaction in index order + residual (Alg. 1 step 14, Eq. (2)) ----------------------
 // `run` is the number of survivors of this tile's earlier chunks (block-uniform).
-template <bool FULL>
+template <bool FULL, bool NORMS>
 __device__ inline uint32_t compact_values(const Args& a, const Tile& t, float (&v)[kPerThread],
                                           uint32_t valid, float thr, bool none, int64_t out0,
-                                          uint32_t run, uint32_t* lds) {
+                                          uint32_t run, uint32_t* lds, NormAcc& norms) {
   uint32_t sel = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
     const bool ok = FULL || ((valid >> i) & 1u);
     if (ok && !none && (fabsf(v[i]) > thr)) sel |= 1u << i;
   }
+  if (NORMS) norm_accumulate(norms, v, valid, sel);
   uint32_t first[kSlots];
   const uint32_t total = tile_rank(sel, lds, first);
 #pragma unroll
@@ -552,17 +555,19 @@ __device__ inline uint32_t compact_values(const Args& a, const Tile& t, float (&
   return run + total;
 }
 
-template <bool FULL>
+template <bool FULL, bool NORMS>
 __device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr, bool none,
-                                         int64_t out0, uint32_t run, uint32_t* lds) {
+                                         int64_t out0, uint32_t run, uint32_t* lds,
+                                         NormAcc& norms) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
-  return compact_values<FULL>(a, t, v, valid, thr, none, out0, run, lds);
+  return compact_values<FULL, NORMS>(a, t, v, valid, thr, none, out0, run, lds, norms);
 }
 
-template <bool SEG>
+template <bool SEG, bool NORMS>
 __global__ __launch_bounds__(kBlock) void k_gk_compact(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
+  __shared__ double lds_n[2 * kWaves];
   Span sp_;
   if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
   const SegCtrl& c = a.ctrl[sp_.seg];
@@ -571,10 +576,43 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact(const Args a) {
   const bool none = c.select_none != 0;
   const int64_t out0 = (SEG ? c.out_base : 0) + (int64_t)a.tile_base[blockIdx.x];
   uint32_t run = 0;
+  NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    if (t.full) run = compact_chunk<true>(a, t, thr, none, out0, run, lds);
-    else run = compact_chunk<false>(a, t, thr, none, out0, run, lds);
+    if (t.full) run = compact_chunk<true, NORMS>(a, t, thr, none, out0, run, lds, norms);
+    else run = compact_chunk<false, NORMS>(a, t, thr, none, out0, run, lds, norms);
+  }
+  if (NORMS) store_norm_partial(a, norms, blockIdx.x, lds_n);
+}
+
+// ---- optional: ||acc||^2 and ||residual'||^2 from the per-tile sums of the compact kernel ----
+template <bool SEG>
+__global__ __launch_bounds__(kFinBlock) void k_norms_finalize(const Args a) {
+  __shared__ double lds[kFinWaves];
+  const int s = blockIdx.x;
+  const SegCtrl& c = a.ctrl[s];
+  if (SEG && c.bad) return;
+  const uint32_t tile0 = SEG ? c.tile0 : 0u;
+  const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total, a.tile_chunks);
+  double out[2];
+  for (int which = 0; which < 2; ++which) {
+    const double* p = a.norm_partial + (size_t)which * a.max_tiles + tile0;
+    double acc = 0.0;
+    for (uint32_t base = 0; base < ntiles; base += kFinBlock * kFinBatch) {
+      double x[kFinBatch];
+#pragma unroll
+      for (int u = 0; u < kFinBatch; ++u) {
+        const uint32_t i = base + u * kFinBlock + threadIdx.x;
+        x[u] = (i < ntiles) ? p[i] : 0.0;
+      }
+#pragma unroll
+      for (int u = 0; u < kFinBatch; ++u) acc += x[u];
+    }
+    out[which] = fin_block_sum(acc, lds);
+  }
+  if (threadIdx.x == 0) {
+    a.result[s].acc_sqnorm = out[0];
+    a.result[s].residual_sqnorm = out[1];
   }
 }
 

@@ -143,12 +143,14 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
 
 // K5: every workgroup totals the group counts, walks Alg. 1 steps 5-13, finds the first output
 // slot of its tile (groups before its own + tiles before it inside its group), then compacts.
+template <bool NORMS>
 __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   __shared__ uint32_t lds_g[kMaxGroups * kNumThres];    // group totals [group][threshold]
   __shared__ uint32_t lds_t[kGroupTiles * kNumThres];   // counts of my group's tiles [threshold][tile]
   __shared__ uint32_t lds_tot[kNumThres];
   __shared__ uint32_t lds_base;
   __shared__ uint32_t lds[kSlots * kWaves];
+  __shared__ double lds_n[2 * kWaves];
   const uint32_t tile = blockIdx.x;
   Span sp_;
   if (!locate_span<false>(a, tile, &sp_)) return;
@@ -204,14 +206,18 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
     r.thres_f32 = thr;
     r.topk_key = 0;
     r.topk_ties_taken = 0;
+    r.acc_sqnorm = 0.0;  // filled by k_norms_finalize when asked for
+    r.residual_sqnorm = 0.0;
   }
   const int64_t out0 = (int64_t)lds_base;
   uint32_t run = 0;
+  NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    if (t.full) run = compact_chunk<true>(a, t, thr, overflow, out0, run, lds);
-    else run = compact_chunk<false>(a, t, thr, overflow, out0, run, lds);
+    if (t.full) run = compact_chunk<true, NORMS>(a, t, thr, overflow, out0, run, lds, norms);
+    else run = compact_chunk<false, NORMS>(a, t, thr, overflow, out0, run, lds, norms);
   }
+  if (NORMS) store_norm_partial(a, norms, tile, lds_n);
 }
 
 static_assert(kMaxGroups == 64 && kGroupTiles == 64, "one lane per group and per tile of a group");

@@ -15,6 +15,8 @@ __device__ inline void clear_result(sparsify_result& r) {
   r.mean = r.std = r.z = r.thres0 = r.thres = 0.0;
   r.topk_key = 0;
   r.topk_ties_taken = 0;
+  r.acc_sqnorm = 0.0;
+  r.residual_sqnorm = 0.0;
 }
 
 __global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {

@@ -79,7 +79,8 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
 uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
 
 struct Carve {
-  size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, group_counts, hist, total;
+  size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, group_counts, norm_partial, hist,
+      total;
 };
 Carve carve(int64_t d_total, int32_t L) {
   const size_t mt = max_tiles_of(d_total, L, 1);
@@ -92,6 +93,7 @@ Carve carve(int64_t d_total, int32_t L) {
   c.tile_base = off;   off = align_up(off + sizeof(uint32_t) * mt);
   c.tie_base = off;    off = align_up(off + sizeof(uint32_t) * mt);
   c.group_counts = off; off = align_up(off + sizeof(uint32_t) * kMaxGroups * kNumThres);
+  c.norm_partial = off; off = align_up(off + sizeof(double) * 2 * mt);
   c.hist = off;        off = align_up(off + sizeof(uint32_t) * 256 * (size_t)L * hist_copies_of(L));
   c.total = off;
   return c;
@@ -161,6 +163,8 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.tile_base = reinterpret_cast<uint32_t*>(w + cv.tile_base);
   a.tie_base = reinterpret_cast<uint32_t*>(w + cv.tie_base);
   a.group_counts = reinterpret_cast<uint32_t*>(w + cv.group_counts);
+  a.norm_partial = reinterpret_cast<double*>(w + cv.norm_partial);
+  a.norms = (opts && opts->error_norms) ? 1 : 0;
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
   a.hist_copies = hist_copies_of(L);
   a.tile_chunks = tile_chunks_of(d_total);
@@ -201,7 +205,12 @@ void launch_gaussiank(Launcher& ln, Args& a, uint32_t tiles) {
     if (tiles <= (uint32_t)kFusedMaxTiles) {  // three launches: see gaussiank_flat.h
       ln.run("accum_moments", k_accum_moments_fused, dim3(want), blk, a);
       ln.run("gk_count", k_gk_count_fused, dim3(tiles), blk, a);
-      ln.run("gk_compact", k_gk_compact_fused, dim3(tiles), blk, a);
+      if (a.norms) {
+        ln.run("gk_compact", k_gk_compact_fused<true>, dim3(tiles), blk, a);
+        ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+      } else {
+        ln.run("gk_compact", k_gk_compact_fused<false>, dim3(tiles), blk, a);
+      }
       return;
     }
     ln.run("accum_moments", k_accum_moments_flat, dim3(want), blk, a);
@@ -211,7 +220,12 @@ void launch_gaussiank(Launcher& ln, Args& a, uint32_t tiles) {
   ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), dim3(kFinBlock), a);
   ln.run("gk_count", k_gk_count<SEG>, dim3(tiles), blk, a);
   ln.run("gk_decide", k_gk_decide<SEG>, dim3(a.L), dim3(kFinBlock), a);
-  ln.run("gk_compact", k_gk_compact<SEG>, dim3(tiles), blk, a);
+  if (a.norms) {
+    ln.run("gk_compact", k_gk_compact<SEG, true>, dim3(tiles), blk, a);
+    ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+  } else {
+    ln.run("gk_compact", k_gk_compact<SEG, false>, dim3(tiles), blk, a);
+  }
 }
 
 template <bool SEG>
@@ -229,7 +243,12 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   ln.run("topk_select3", k_topk_select<SEG>, dim3(a.L), fin, a, 3);
   ln.run("topk_tie_count", k_topk_tie_count<SEG>, dim3(tiles), blk, a);
   ln.run("topk_tie_scan", k_topk_tie_scan<SEG>, dim3(a.L), fin, a);
-  ln.run("topk_compact", k_topk_compact<SEG>, dim3(tiles), blk, a);
+  if (a.norms) {
+    ln.run("topk_compact", k_topk_compact<SEG, true>, dim3(tiles), blk, a);
+    ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+  } else {
+    ln.run("topk_compact", k_topk_compact<SEG, false>, dim3(tiles), blk, a);
+  }
 }
 
 int flat_call(bool gaussian, int64_t d, int64_t k, const float* grad, float* residual, float* acc,

@@ -232,9 +232,9 @@ struct TopkSel {
   uint32_t tile_sure0;    // first output slot of this tile's sure survivors
 };
 
-template <bool FULL>
+template <bool FULL, bool NORMS>
 __device__ inline void topk_compact_chunk(const Args& a, const Tile& t, SegCtrl& c, TopkSel& k,
-                                          uint32_t* lds, uint32_t* lds_base) {
+                                          uint32_t* lds, uint32_t* lds_base, NormAcc& norms) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
   const uint32_t T = k.T;
@@ -313,6 +313,7 @@ __device__ inline void topk_compact_chunk(const Args& a, const Tile& t, SegCtrl&
     near = 0;
   }
   const uint32_t sel = sure | near;
+  if (NORMS) norm_accumulate(norms, v, valid, sel);
   if (a.inplace) {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i)
@@ -326,9 +327,10 @@ __device__ inline void topk_compact_chunk(const Args& a, const Tile& t, SegCtrl&
   __syncthreads();  // lds and lds_base are reused by the next chunk
 }
 
-template <bool SEG>
+template <bool SEG, bool NORMS>
 __global__ __launch_bounds__(kBlock) void k_topk_compact(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
+  __shared__ double lds_n[2 * kWaves];
   __shared__ uint32_t lds_base;
   Span sp_;
   if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
@@ -344,11 +346,13 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact(const Args a) {
   k.sure_run = 0;
   k.tie_run = k.rank_ties ? a.tie_base[blockIdx.x] : 0u;
   k.tile_sure0 = a.tile_base[blockIdx.x];
+  NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    if (t.full) topk_compact_chunk<true>(a, t, c, k, lds, &lds_base);
-    else topk_compact_chunk<false>(a, t, c, k, lds, &lds_base);
+    if (t.full) topk_compact_chunk<true, NORMS>(a, t, c, k, lds, &lds_base, norms);
+    else topk_compact_chunk<false, NORMS>(a, t, c, k, lds, &lds_base, norms);
   }
+  if (NORMS) store_norm_partial(a, norms, blockIdx.x, lds_n);
 }
 
 }  // namespace sp

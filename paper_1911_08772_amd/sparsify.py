@@ -19,13 +19,14 @@ F_OVERFLOW, F_NONFINITE, F_EXHAUSTED, F_BADSEGMENT = 1, 2, 4, 8
 RESULT_DTYPE = np.dtype([("nnz", "<u4"), ("rounds", "<u4"), ("count", "<u4", (4,)),
                          ("flags", "<u4"), ("thres_f32", "<f4"), ("mean", "<f8"), ("std", "<f8"),
                          ("z", "<f8"), ("thres0", "<f8"), ("thres", "<f8"), ("topk_key", "<u4"),
-                         ("topk_ties_taken", "<u4")])
-RESULT_BYTES = RESULT_DTYPE.itemsize  # 80
+                         ("topk_ties_taken", "<u4"), ("acc_sqnorm", "<f8"),
+                         ("residual_sqnorm", "<f8")])
+RESULT_BYTES = RESULT_DTYPE.itemsize  # 96
 
 
 class Opts(C.Structure):
     _fields_ = [("tail_div", C.c_double), ("ddof", C.c_int32), ("tile_chunks", C.c_int32),
-                ("trace", C.c_void_p)]
+                ("trace", C.c_void_p), ("error_norms", C.c_int32), ("reserved", C.c_int32)]
 
 
 _p = C.c_void_p
@@ -78,9 +79,9 @@ def _stream(stream) -> int:
     return stream.cuda_stream
 
 
-def _opts(tail_div: float, ddof: int, trace, tile_chunks: int = 0) -> Opts:
+def _opts(tail_div: float, ddof: int, trace, tile_chunks: int = 0, error_norms: bool = False) -> Opts:
     return Opts(float(tail_div), int(ddof), int(tile_chunks),
-                trace.handle if trace is not None else None)
+                trace.handle if trace is not None else None, 1 if error_norms else 0, 0)
 
 
 def version() -> str:
@@ -118,8 +119,8 @@ class Trace:
 
 def sparsify_gaussiank(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                        workspace_nbytes, tail_div=2.0, ddof=1, trace=None, stream=None,
-                       check=True, tile_chunks=0) -> int:
-    o = _opts(tail_div, ddof, trace, tile_chunks)
+                       check=True, tile_chunks=0, error_norms=False) -> int:
+    o = _opts(tail_div, ddof, trace, tile_chunks, error_norms)
     rc = lib.sparsify_gaussiank(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                                 _ptr(out_val), cap, _ptr(result), _ptr(workspace),
                                 workspace_nbytes, C.byref(o), _stream(stream))
@@ -129,8 +130,9 @@ def sparsify_gaussiank(d, k, grad, residual, acc, out_idx, out_val, cap, result,
 
 
 def sparsify_topk(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
-                  workspace_nbytes, trace=None, stream=None, check=True, tile_chunks=0) -> int:
-    o = _opts(2.0, 1, trace, tile_chunks)
+                  workspace_nbytes, trace=None, stream=None, check=True, tile_chunks=0,
+                  error_norms=False) -> int:
+    o = _opts(2.0, 1, trace, tile_chunks, error_norms)
     rc = lib.sparsify_topk(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                            _ptr(out_val), cap, _ptr(result), _ptr(workspace), workspace_nbytes,
                            C.byref(o), _stream(stream))
@@ -142,8 +144,8 @@ def sparsify_topk(d, k, grad, residual, acc, out_idx, out_val, cap, result, work
 def sparsify_segmented(num_segments, d_total, seg_off, seg_k, mode, grad, residual, acc, out_idx,
                        out_val, out_off, out_cap, results, workspace, workspace_nbytes,
                        tail_div=2.0, ddof=1, trace=None, stream=None, check=True,
-                       tile_chunks=0) -> int:
-    o = _opts(tail_div, ddof, trace, tile_chunks)
+                       tile_chunks=0, error_norms=False) -> int:
+    o = _opts(tail_div, ddof, trace, tile_chunks, error_norms)
     rc = lib.sparsify_segmented(num_segments, d_total, _ptr(seg_off), _ptr(seg_k), mode,
                                 _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                                 _ptr(out_val), _ptr(out_off), out_cap, _ptr(results),

@@ -28,8 +28,10 @@ def test_library_exports_every_declared_function():
 
 
 def test_result_record_layout_matches_header():
-    assert S.RESULT_BYTES == 80
+    assert S.RESULT_BYTES == 96
     assert S.RESULT_DTYPE.fields["mean"][1] == 32 and S.RESULT_DTYPE.fields["topk_key"][1] == 72
+    assert S.RESULT_DTYPE.fields["acc_sqnorm"][1] == 80
+    assert C.sizeof(S.Opts) == 32
 
 
 def test_workspace_bytes():
