@@ -112,7 +112,7 @@ class Trace:
         return out
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and lib is not None:  # lib is gone at interpreter exit
             lib.sparsify_trace_destroy(self.handle)
             self.handle = None
 
