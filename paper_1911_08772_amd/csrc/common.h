@@ -140,15 +140,25 @@ __device__ inline bool locate_span(const Args& a, uint32_t t, Span* out) {
     make_span(out, 0, 0, a.d_total, tb, a.tile_chunks);
     return true;
   }
+  // Largest s with tile_start[s] <= t, found by the whole wave at once: 64 evenly spaced
+  // entries per round (one load latency per round instead of one per bisection step).
   const uint32_t* ts = a.tile_start;
-  if (t >= ts[a.L]) return false;
-  int lo = 0, hi = a.L;  // largest s with ts[s] <= t
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (ts[mid] <= t) lo = mid; else hi = mid;
+  const uint32_t total = ts[a.L];
+  const uint32_t lane = threadIdx.x & 63u;
+  uint32_t lo = 0, n = (uint32_t)a.L;
+  while (n > 1) {
+    const uint32_t stride = (n + 63u) / 64u;
+    const uint32_t off = lane * stride;
+    const uint32_t v = off < n ? ts[lo + off] : 0xFFFFFFFFu;
+    const uint32_t below = (uint32_t)__builtin_popcountll(__ballot(v <= t));  // >= 1: ts[lo] <= t
+    const uint32_t first = (below - 1u) * stride;
+    lo += first;
+    n = (n - first < stride) ? n - first : stride;
   }
+  if (t >= total) return false;
   const SegCtrl& c = a.ctrl[lo];
-  make_span(out, lo, c.start, c.end, seg_base(c.start) + (int64_t)(t - c.tile0) * e, a.tile_chunks);
+  make_span(out, (int)lo, c.start, c.end, seg_base(c.start) + (int64_t)(t - c.tile0) * e,
+            a.tile_chunks);
   return true;
 }
 

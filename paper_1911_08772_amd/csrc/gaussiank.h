@@ -131,9 +131,17 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
     else accum_moments_chunk<false>(a, t, m);
   }
   store_moment_partial(a, m, blockIdx.x, lds);
-  if (!SEG && blockIdx.x == 0 && threadIdx.x == 0) {
-    // The quantile depends on the arguments only; compute it here, hidden under the stream.
-    a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
+  // The quantile depends on the arguments only; the workgroup of a segment's first tile
+  // computes it here, hidden under the stream.
+  if (threadIdx.x == 0) {
+    if (!SEG) {
+      if (blockIdx.x == 0)
+        a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
+    } else {
+      SegCtrl& c = a.ctrl[sp_.seg];
+      if (blockIdx.x == c.tile0)
+        c.z = norm_isf((double)c.k / (a.tail_div * (double)(c.end - c.start)));
+    }
   }
 }
 

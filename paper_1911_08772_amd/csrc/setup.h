@@ -109,8 +109,6 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
         } else {
           r.nnz = (uint32_t)k;
         }
-      } else {
-        c.z = norm_isf((double)k / (a.tail_div * (double)(end - start)));
       }
     }
     const uint64_t next = (uint64_t)carry + total;

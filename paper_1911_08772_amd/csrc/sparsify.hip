@@ -322,7 +322,8 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   Launcher ln{static_cast<hipStream_t>(stream),
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
   ln.begin();
-  const uint32_t tiles = a.max_tiles;  // upper bound; surplus blocks exit at once
+  // upper bound of the tile count for this tiling; surplus workgroups exit at once
+  const uint32_t tiles = max_tiles_of(d_total, num_segments, a.tile_chunks);
   ln.run("seg_setup", k_seg_setup, dim3(1), dim3(kBlock), a, (int)mode);
   if (mode == 1) {
     launch_gaussiank<true>(ln, a, tiles);
