@@ -22,7 +22,7 @@ HBM_PEAK_GBPS = 8000.0
 # algorithmic bytes per element of each streaming kernel (fp32 reads/writes the method needs)
 KERNEL_BYTES_PER_ELEM = {"accum_moments": 12, "gk_count": 4, "gk_compact": 8,
                          "topk_accum_hist": 12, "topk_hist1": 4, "topk_hist2": 4,
-                         "topk_hist3": 4, "topk_compact": 8, "topk_tie_count": 0}
+                         "topk_hist3": 4, "topk_compact": 8, "topk_tie_count": 0, "topk_ties": 0}
 GK_BYTES_PER_ELEM = 24   # r g, r eps, w acc | r acc (one count pass) | r acc, w eps'
 TOPK_BYTES_PER_ELEM = 32  # r g, r eps, w acc (+digit 1) | 3 further digit passes | r acc, w eps'
 

@@ -50,6 +50,10 @@ struct SegCtrl {
   uint32_t n_eq;            // number of keys equal to the k-th key
   uint32_t rank_ties;       // 1 if only some of the equal keys are kept (needs index order)
   uint32_t cursor;          // output slots handed out so far (starts after the ordered part)
+  uint32_t sel_prefix[3];   // fused flat path: prefix and rank left after the digit of pass 0..2
+  uint32_t sel_krem[3];     //   (one slot per pass: a kernel reads one slot and writes the next)
+  uint32_t topk_key;        // fused flat path: the k-th key and the ties to keep
+  uint32_t topk_take;
   uint32_t pad1;
 };
 

@@ -12,6 +12,7 @@
 #include "setup.h"
 #include "sparsify.h"
 #include "topk.h"
+#include "topk_flat.h"
 
 using namespace sp;
 
@@ -94,7 +95,9 @@ Carve carve(int64_t d_total, int32_t L) {
   c.tie_base = off;    off = align_up(off + sizeof(uint32_t) * mt);
   c.group_counts = off; off = align_up(off + sizeof(uint32_t) * kMaxGroups * kNumThres);
   c.norm_partial = off; off = align_up(off + sizeof(double) * 2 * mt);
-  c.hist = off;        off = align_up(off + sizeof(uint32_t) * 256 * (size_t)L * hist_copies_of(L));
+  size_t hist_words = (size_t)256 * (size_t)L * hist_copies_of(L);
+  if (hist_words < (size_t)kTopkHistWords) hist_words = kTopkHistWords;  // four per-pass buffers (flat)
+  c.hist = off;        off = align_up(off + sizeof(uint32_t) * hist_words);
   c.total = off;
   return c;
 }
@@ -232,6 +235,22 @@ template <bool SEG>
 void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   const dim3 pg(tiles);
+  if (!SEG && tiles <= (uint32_t)kFusedMaxTiles) {  // seven launches: see topk_flat.h
+    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a);
+    ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
+    ln.run("topk_hist1", k_topk_hist_fused<false>, pg, blk, a, 1);
+    ln.run("topk_hist2", k_topk_hist_fused<false>, pg, blk, a, 2);
+    ln.run("topk_hist3", k_topk_hist_fused<true>, pg, blk, a, 3);
+    ln.run("topk_ties", k_topk_ties_fused, pg, blk, a);
+    if (a.norms) {
+      ln.run("topk_compact", k_topk_compact_fused<true>, pg, blk, a);
+      ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+    } else {
+      ln.run("topk_compact", k_topk_compact_fused<false>, pg, blk, a);
+    }
+    return;
+  }
+  if (!SEG) ln.run("topk_init", k_topk_init_flat, dim3(1), blk, a);
   ln.run("topk_accum_hist", k_topk_accum_hist<SEG>, pg, blk, a);
   const dim3 fin(kFinBlock);
   ln.run("topk_select0", k_topk_select<SEG>, dim3(a.L), fin, a, 0);
@@ -269,7 +288,6 @@ int flat_call(bool gaussian, int64_t d, int64_t k, const float* grad, float* res
   if (gaussian) {
     launch_gaussiank<false>(ln, a, tiles);
   } else {
-    ln.run("topk_init", k_topk_init_flat, dim3(1), dim3(kBlock), a);
     launch_topk<false>(ln, a, tiles);
   }
   if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);

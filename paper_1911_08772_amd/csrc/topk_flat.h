@@ -1,0 +1,223 @@
+// Exact Top_k, flat vectors: seven launches instead of twelve.  The per-segment "select"
+// kernels of topk.h are latency-bound single workgroups that each cost a launch; here every
+// workgroup of the next pass chooses the digit itself from the replicated histogram of the
+// previous pass (same arithmetic, same inputs: all agree), each pass has its own histogram
+// buffer (cleared once by the init kernel), and every compact workgroup finds its output base
+// from per-group totals of the sure survivors.
+//
+// Used when the vector has at most kFusedMaxTiles tiles (always, unless tile_chunks is forced).
+#pragma once
+#include "common.h"
+#include "gaussiank_flat.h"
+#include "topk.h"
+
+namespace sp {
+
+constexpr int kTopkCopies = 32;  // replicas of each pass's global histogram
+constexpr int kTopkHistWords = kDigits * kTopkCopies * 256;
+
+__device__ inline uint32_t* pass_hist(const Args& a, int pass) {
+  return a.hist + (size_t)pass * kTopkCopies * 256;
+}
+
+// Clears the four histograms and the group totals, resets the selection state.
+__global__ __launch_bounds__(kBlock) void k_topk_init_fused(const Args a) {
+  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < (uint32_t)kTopkHistWords;
+       i += gridDim.x * kBlock)
+    a.hist[i] = 0;
+  if (blockIdx.x == 0) {
+    for (uint32_t i = threadIdx.x; i < (uint32_t)(kMaxGroups * kNumThres); i += kBlock)
+      a.group_counts[i] = 0;
+    if (threadIdx.x == 0) {
+      SegCtrl& c = a.ctrl[0];
+      c.prefix = 0;
+      c.k_rem = (uint32_t)a.flat_k;
+      c.n_eq = 0;
+      c.rank_ties = 0;
+      c.cursor = 0;
+      c.select_none = 0;
+      c.bad = 0;
+      sparsify_result& r = a.result[0];
+      clear_result(r);
+      r.nnz = (uint32_t)a.flat_k;
+    }
+  }
+}
+
+// The digit of pass `pass` that holds the k_rem-th largest of the keys matching `prefix`, from
+// the replicated histogram `hist`; run by all 256 threads of a workgroup (thread order =
+// descending digit).  `lds` holds kWaves + 3 words.  Three barriers.
+struct Digit {
+  uint32_t prefix, k_rem, count;  // extended prefix, rank left inside the digit, keys in it
+};
+__device__ inline Digit choose_digit(const uint32_t* hist, int pass, uint32_t prefix,
+                                     uint32_t k_rem, uint32_t* lds) {
+  const uint32_t nbins = 1u << digit_bits(pass);
+  const uint32_t bin = 255u - threadIdx.x;
+  uint32_t x[kTopkCopies];
+#pragma unroll
+  for (int r = 0; r < kTopkCopies; ++r) x[r] = hist[r * 256 + bin];  // all in flight at once
+  uint32_t v = 0;
+#pragma unroll
+  for (int r = 0; r < kTopkCopies; ++r) v += x[r];
+  if (bin >= nbins) v = 0;
+  uint32_t total;
+  const uint32_t above = block_exclusive_scan<kWaves>(v, lds, &total);  // keys in higher digits
+  if (above < k_rem && k_rem <= above + v) {
+    lds[kWaves] = (prefix << digit_bits(pass)) | bin;
+    lds[kWaves + 1] = k_rem - above;
+    lds[kWaves + 2] = v;
+  }
+  __syncthreads();
+  const Digit d = {lds[kWaves], lds[kWaves + 1], lds[kWaves + 2]};
+  return d;
+}
+
+// Passes 1..3.  Prologue: the digit of the previous pass.  The last pass also counts, per tile,
+// the keys whose leading 24 bits already exceed the prefix (survivors whatever the last digit
+// is) and adds them into the per-group totals.
+template <bool LAST>
+__global__ __launch_bounds__(kBlock) void k_topk_hist_fused(const Args a, int pass) {
+  __shared__ uint32_t h[kWaves][256];
+  __shared__ uint32_t lds_sel[kWaves + 3];
+  __shared__ uint32_t lds_sure[kWaves];
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
+  // odd passes walk the tiles backwards (see k_topk_hist)
+  const uint32_t tile = (pass & 1) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  Span sp_;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[0];
+  const uint32_t prefix_in = pass == 1 ? 0u : c.sel_prefix[pass - 2];
+  const uint32_t k_in = pass == 1 ? (uint32_t)a.flat_k : c.sel_krem[pass - 2];
+  const Digit dg = choose_digit(pass_hist(a, pass - 1), pass - 1, prefix_in, k_in, lds_sel);
+  if (tile == 0 && threadIdx.x == 0) {  // published for the next kernel's prologue (own slot:
+    c.sel_prefix[pass - 1] = dg.prefix;  // other workgroups of this kernel still read the last)
+    c.sel_krem[pass - 1] = dg.k_rem;
+  }
+  uint32_t sure = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) sure += hist_tile<true, LAST>(a, t, pass, dg.prefix, h[wave_id()]);
+    else sure += hist_tile<false, LAST>(a, t, pass, dg.prefix, h[wave_id()]);
+  }
+  if (LAST) {
+    sure = wave_sum(sure);
+    if (lane_id() == 0) lds_sure[wave_id()] = sure;
+  }
+  __syncthreads();
+  {
+    const int bin = threadIdx.x;
+    uint32_t v = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) v += h[w][bin];
+    if (v) atomicAdd(&pass_hist(a, pass)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+  }
+  if (LAST && threadIdx.x == 0) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) s += lds_sure[w];
+    a.tile_counts[tile] = s;
+    if (s) atomicAdd(&a.group_counts[(tile / kGroupTiles) * kNumThres], s);
+  }
+}
+
+// After the last pass: every workgroup chooses the last digit (so T, the ties to keep and
+// whether they must be ranked are known); workgroup 0 publishes them with the start of the
+// cursor; if ties must be ranked, each workgroup counts the keys equal to T in its tile.
+__global__ __launch_bounds__(kBlock) void k_topk_ties_fused(const Args a) {
+  __shared__ uint32_t lds_sel[kWaves + 3];
+  __shared__ uint32_t lds[kWaves];
+  const uint32_t tile = blockIdx.x;
+  Span sp_;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[0];
+  const Digit dg = choose_digit(pass_hist(a, 3), 3, c.sel_prefix[2], c.sel_krem[2], lds_sel);
+  const bool rank_ties = dg.count > dg.k_rem;
+  if (tile == 0) {
+    uint32_t g = 0;  // total of the sure survivors: one group total per lane
+    if (wave_id() == 0) {
+      const uint32_t ngroups = (gridDim.x + kGroupTiles - 1) / kGroupTiles;
+      g = (uint32_t)lane_id() < ngroups ? a.group_counts[lane_id() * kNumThres] : 0u;
+      g = wave_sum(g);
+    }
+    if (threadIdx.x == 0) {
+      c.topk_key = dg.prefix;
+      c.topk_take = dg.k_rem;
+      c.n_eq = dg.count;
+      c.rank_ties = rank_ties ? 1u : 0u;
+      c.cursor = g;  // the survivors that share T's leading 24 bits take slots from here on
+      sparsify_result& r = a.result[0];
+      r.topk_key = dg.prefix;
+      r.topk_ties_taken = dg.k_rem;
+    }
+  }
+  if (!rank_ties) return;
+  uint32_t n = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    n += t.full ? tie_count_chunk<true>(a, t, dg.prefix) : tie_count_chunk<false>(a, t, dg.prefix);
+  }
+  n = wave_sum(n);
+  if (lane_id() == 0) lds[wave_id()] = n;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+    for (int w = 0; w < kWaves; ++w) s += lds[w];
+    a.tile_counts[(size_t)a.max_tiles + tile] = s;
+  }
+}
+
+// Compaction.  Prologue: first slot of the tile's sure survivors (groups before its own + tiles
+// before it inside its group) and, when ties are ranked, the number of ties before the tile.
+template <bool NORMS>
+__global__ __launch_bounds__(kBlock) void k_topk_compact_fused(const Args a) {
+  __shared__ uint32_t lds[kSlots * kWaves];
+  __shared__ uint32_t lds_base;
+  __shared__ uint32_t lds_pre[kWaves];
+  __shared__ double lds_n[2 * kWaves];
+  const uint32_t tile = blockIdx.x;
+  Span sp_;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[0];
+  TopkSel k;
+  k.T = c.topk_key;
+  k.take = c.topk_take;
+  k.rank_ties = c.rank_ties != 0;
+  k.none = false;
+  k.out0 = 0;
+  k.cap = a.flat_cap;
+  k.sure_run = 0;
+  const uint32_t g = tile / kGroupTiles, g0 = g * kGroupTiles, within = tile - g0;
+  uint32_t x = 0;
+  if (wave_id() == 0) {
+    if ((uint32_t)lane_id() < g) x += a.group_counts[lane_id() * kNumThres];
+    if ((uint32_t)lane_id() < within) x += a.tile_counts[g0 + lane_id()];
+    x = wave_sum(x);
+  }
+  uint32_t ties_before = 0;
+  if (k.rank_ties) {  // rare: sum the tie counts of all earlier tiles
+    const uint32_t* tc = a.tile_counts + a.max_tiles;
+    for (uint32_t i = threadIdx.x; i < tile; i += kBlock) ties_before += tc[i];
+    ties_before = wave_sum(ties_before);
+  }
+  if (lane_id() == 0) {
+    lds_pre[wave_id()] = ties_before;
+    if (wave_id() == 0) lds_base = x;
+  }
+  __syncthreads();
+  k.tile_sure0 = lds_base;
+  k.tie_run = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) k.tie_run += lds_pre[w];
+  __syncthreads();
+  NormAcc norms = {0.0, 0.0};
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) topk_compact_chunk<true, NORMS>(a, t, c, k, lds, &lds_base, norms);
+    else topk_compact_chunk<false, NORMS>(a, t, c, k, lds, &lds_base, norms);
+  }
+  if (NORMS) store_norm_partial(a, norms, tile, lds_n);
+}
+
+}  // namespace sp
