@@ -21,10 +21,14 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 # algorithmic bytes per element of each streaming kernel (fp32 reads/writes the method needs)
 KERNEL_BYTES_PER_ELEM = {"accum_moments": 12, "gk_count": 4, "gk_compact": 8,
-                         "topk_accum_hist": 12, "topk_hist1": 4, "topk_hist2": 4,
-                         "topk_hist3": 4, "topk_compact": 8, "topk_tie_count": 0, "topk_ties": 0}
+                         "topk_accum_hist": 12, "topk_filter": 4, "topk_compact": 8,
+                         "topk_hist1": 4, "topk_hist2": 4, "topk_hist3": 4}
 GK_BYTES_PER_ELEM = 24   # r g, r eps, w acc | r acc (one count pass) | r acc, w eps'
-TOPK_BYTES_PER_ELEM = 32  # r g, r eps, w acc (+digit 1) | 3 further digit passes | r acc, w eps'
+# r g, r eps, w acc (+digit 1) | r acc (filter: candidates written out) | r acc, w eps'; the
+# candidate lists the three later digit passes read are data dependent and not counted
+TOPK_BYTES_PER_ELEM = 24
+GK_INPLACE_BYTES_PER_ELEM = 20   # the compaction pass only reads acc (and zeroes the survivors)
+TOPK_INPLACE_BYTES_PER_ELEM = 28  # no room for candidates: 12 + 3 full digit passes + r acc
 
 
 def main() -> int:
@@ -172,8 +176,10 @@ def main() -> int:
                                       "note": "cfg4 layout (54 segments) on the same gradients"}
             del bs
 
-    gk_gbps = gbps(GK_BYTES_PER_ELEM, float(np.mean(gk_nnz)), gk_ms)
-    tk_gbps = gbps(TOPK_BYTES_PER_ELEM, float(k), tk_ms)
+    gk_bpe = GK_INPLACE_BYTES_PER_ELEM if args.inplace else GK_BYTES_PER_ELEM
+    tk_bpe = TOPK_INPLACE_BYTES_PER_ELEM if args.inplace else TOPK_BYTES_PER_ELEM
+    gk_gbps = gbps(gk_bpe, float(np.mean(gk_nnz)), gk_ms)
+    tk_gbps = gbps(tk_bpe, float(k), tk_ms)
 
     dom = max((n for n in gk_stage if KERNEL_BYTES_PER_ELEM.get(n, 0) > 0), key=lambda n: gk_stage[n])
     dom_bytes = KERNEL_BYTES_PER_ELEM[dom] * d
@@ -190,13 +196,13 @@ def main() -> int:
         "elements_per_s": round(d / (gk_ms * 1e-3), 1),
         "pct_hbm_peak": round(100.0 * gk_gbps / HBM_PEAK_GBPS, 2),
         "gaussiank": {"ms_per_step": round(gk_ms, 5), "wall_ms": round(gk_wall, 5),
-                      "event_ms": round(gk_ev, 5), "bytes_per_elem": GK_BYTES_PER_ELEM,
+                      "event_ms": round(gk_ev, 5), "bytes_per_elem": gk_bpe,
                       "nnz_mean": float(np.mean(gk_nnz)), "rounds_mean": float(np.mean(gk_rounds)),
                       "kernel_ms": {n: round(v, 5) for n, v in gk_stage.items()}},
         "topk": {"ms_per_step": round(tk_ms, 5), "GBps": round(tk_gbps, 2),
                  "elements_per_s": round(d / (tk_ms * 1e-3), 1),
                  "pct_hbm_peak": round(100.0 * tk_gbps / HBM_PEAK_GBPS, 2),
-                 "bytes_per_elem": TOPK_BYTES_PER_ELEM,
+                 "bytes_per_elem": tk_bpe,
                  "kernel_ms": {n: round(v, 5) for n, v in tk_stage.items()}},
         "gaussiank_speedup_over_topk": round(tk_ms / gk_ms, 3),
         "also": extras,

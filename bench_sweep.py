@@ -51,7 +51,7 @@ def main() -> int:
         b = S.Buffers.allocate(d, cap, 1, False, dev)
         stream = torch.cuda.current_stream()
         out = {"d": d, "k": k}
-        for name, fn, bpe in (("gaussiank", S.sparsify_gaussiank, 24), ("topk", S.sparsify_topk, 32)):
+        for name, fn, bpe in (("gaussiank", S.sparsify_gaussiank, 24), ("topk", S.sparsify_topk, 24)):
             b.residual.zero_()
             times = []
             for s in range(args.warmup + args.steps):

@@ -16,6 +16,8 @@
  *   and keeps no state between calls.  `grad` is only read.  `residual` holds eps on entry
  *   and eps' on exit.  `acc` receives grad+residual; `acc == residual` is allowed (in-place
  *   mode: the buffer then ends as eps').  Any other overlap between buffers is an error.
+ *   Between its first and its last kernel a call may use `residual` (when it is not `acc`)
+ *   as scratch: its contents are defined again only when the call's work has completed.
  * Sizes.  1 <= k <= d < 2^31.  Indices are uint32 positions in the flat buffer.
  * Output order.  Gaussian_k pairs come out in ascending index order; Top_k pairs in
  *   unspecified order (treat them as a set).  Entries beyond `nnz` are not written.

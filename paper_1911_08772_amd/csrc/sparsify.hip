@@ -12,6 +12,7 @@
 #include "setup.h"
 #include "sparsify.h"
 #include "topk.h"
+#include "topk_filter.h"
 #include "topk_flat.h"
 
 using namespace sp;
@@ -235,6 +236,22 @@ template <bool SEG>
 void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   const dim3 pg(tiles);
+  if (!SEG && tiles <= (uint32_t)kFusedMaxTiles && !a.inplace) {  // see topk_filter.h
+    const dim3 cg((tiles + kWaves - 1) / kWaves);  // one wave per tile's candidate list
+    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a);
+    ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
+    ln.run("topk_filter", k_topk_filter, pg, blk, a);
+    ln.run("topk_cand2", k_topk_cand_hist, cg, blk, a, 2);
+    ln.run("topk_cand3", k_topk_cand_hist, cg, blk, a, 3);
+    ln.run("topk_final", k_topk_cand_final, cg, blk, a);
+    if (a.norms) {
+      ln.run("topk_compact", k_topk_compact_ordered<true>, pg, blk, a);
+      ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+    } else {
+      ln.run("topk_compact", k_topk_compact_ordered<false>, pg, blk, a);
+    }
+    return;
+  }
   if (!SEG && tiles <= (uint32_t)kFusedMaxTiles) {  // seven launches: see topk_flat.h
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a);
     ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);

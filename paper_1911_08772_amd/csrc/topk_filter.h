@@ -1,0 +1,308 @@
+// Exact Top_k, flat vectors with a separate accumulator: radix select with candidate filtering.
+// Once the exponent byte of the k-th key is known, only the keys that share it (a few per cent
+// of a bell-shaped vector) can still be the k-th key.  The one remaining pass over the whole of
+// acc writes those keys out, tile by tile, and the three later digit passes read them instead
+// of acc: 12 + 4 + 8 bytes per element instead of 12 + 3 * 4 + 8.
+//
+// The candidate keys of a tile go to the residual buffer, at the tile's own offset: the old
+// residual has been consumed by the accumulate kernel and the new one is not written before
+// the compaction kernel, so in between the buffer is free and a tile's stretch of it can hold
+// every key of the tile if it must.  (With acc == residual there is no such room; that case
+// keeps the unfiltered passes of topk_flat.h.)
+//
+// Every survivor's output slot is fixed by counts: per tile, the keys above the k-th key T and
+// the keys equal to it are counted from the candidates, the compaction kernel turns group and
+// tile totals into its first slot, and ties are kept lowest index first.  The pairs come out in
+// ascending index order; no output cursor is needed.
+#pragma once
+#include "common.h"
+#include "gaussiank_flat.h"
+#include "topk.h"
+#include "topk_flat.h"
+
+namespace sp {
+
+// rows of tile_counts used by this path
+constexpr int kRowTake = 0;   // survivors of the tile, ranked ties not included
+constexpr int kRowTies = 1;   // keys equal to T (only when ties are ranked)
+constexpr int kRowCand = 2;   // candidate keys the filter pass wrote for the tile
+constexpr int kRowAbove = 3;  // keys whose exponent byte exceeds the chosen one
+// columns of group_counts used by this path
+constexpr int kColTake = 0;
+constexpr int kColTies = 1;
+
+__device__ inline uint32_t* tile_row(const Args& a, int row) {
+  return a.tile_counts + (size_t)row * a.max_tiles;
+}
+__device__ inline uint32_t* tile_candidates(const Args& a, uint32_t tile) {
+  return reinterpret_cast<uint32_t*>(a.resid) + (int64_t)tile * a.tile_chunks * kChunk;
+}
+
+// ---- the one pass over acc after the accumulate kernel ----------------------------------------
+// Prologue: the exponent byte E of the k-th key.  Then, per tile: the keys with exponent E are
+// appended (in no particular order) to the tile's candidate list and enter the histogram of the
+// second digit; the keys with a larger exponent are counted.
+template <bool FULL>
+__device__ inline uint32_t filter_chunk(const Args& a, const Tile& t, uint32_t E, uint32_t* cand,
+                                        uint32_t* h, uint32_t* lds_cursor) {
+  float v[kPerThread];
+  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+  uint32_t above = 0, cmask = 0;
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    const uint32_t key = mag_key(v[i]);
+    const bool ok = FULL || ((valid >> i) & 1u);
+    above += (ok && (key >> 23) > E) ? 1u : 0u;
+    cmask |= ((ok && (key >> 23) == E) ? 1u : 0u) << i;
+  }
+  const uint32_t n = (uint32_t)__builtin_popcount(cmask);
+  const uint32_t inc = wave_inclusive_scan(n);
+  const uint32_t wave_total = __shfl(inc, 63, 64);
+  if (wave_total != 0) {  // wave-uniform
+    uint32_t base = 0;
+    if (lane_id() == 63) base = atomicAdd(lds_cursor, wave_total);  // LDS: one per wave and chunk
+    base = __shfl(base, 63, 64);
+    uint32_t pos = base + inc - n;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      if ((cmask >> i) & 1u) {
+        const uint32_t key = mag_key(v[i]);
+        cand[pos++] = key;
+        atomicAdd(&h[(key >> 15) & 255u], 1u);
+      }
+    }
+  }
+  return above;
+}
+
+__global__ __launch_bounds__(kBlock) void k_topk_filter(const Args a) {
+  __shared__ uint32_t h[kWaves][256];
+  __shared__ uint32_t lds_sel[kWaves + 3];
+  __shared__ uint32_t lds_above[kWaves];
+  __shared__ uint32_t lds_cursor;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
+  if (threadIdx.x == 0) lds_cursor = 0;
+  const uint32_t tile = gridDim.x - 1u - blockIdx.x;  // starts where the accumulate kernel ended
+  Span sp_;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[0];
+  const Digit dg = choose_digit(pass_hist(a, 0), 0, 0u, (uint32_t)a.flat_k, lds_sel);  // barriers
+  if (tile == 0 && threadIdx.x == 0) {
+    c.sel_prefix[0] = dg.prefix;
+    c.sel_krem[0] = dg.k_rem;
+  }
+  uint32_t* cand = tile_candidates(a, tile);
+  uint32_t above = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) above += filter_chunk<true>(a, t, dg.prefix, cand, h[wave_id()], &lds_cursor);
+    else above += filter_chunk<false>(a, t, dg.prefix, cand, h[wave_id()], &lds_cursor);
+  }
+  above = wave_sum(above);
+  if (lane_id() == 0) lds_above[wave_id()] = above;
+  __syncthreads();
+  {
+    const int bin = threadIdx.x;
+    uint32_t v = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) v += h[w][bin];
+    if (v) atomicAdd(&pass_hist(a, 1)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+  }
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) s += lds_above[w];
+    tile_row(a, kRowAbove)[tile] = s;
+    tile_row(a, kRowCand)[tile] = lds_cursor;
+  }
+}
+
+// ---- digit passes 2 and 3 over the candidates -------------------------------------------------
+// One wave per tile's candidate list (a few hundred keys as a rule), four lists per workgroup.
+// `fn(key)` is called for every candidate of the wave's tile.
+constexpr int kCandBatch = 4;
+template <typename F>
+__device__ inline void for_each_candidate(const Args& a, uint32_t tile, uint32_t ntiles, F fn) {
+  if (tile >= ntiles) return;
+  const uint32_t n = tile_row(a, kRowCand)[tile];
+  const uint32_t* cand = tile_candidates(a, tile);
+  for (uint32_t i0 = 0; i0 < n; i0 += 64 * kCandBatch) {
+    uint32_t key[kCandBatch];
+#pragma unroll
+    for (int u = 0; u < kCandBatch; ++u) {
+      const uint32_t i = i0 + u * 64 + lane_id();
+      key[u] = i < n ? cand[i] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kCandBatch; ++u)
+      if (i0 + u * 64 + lane_id() < n) fn(key[u]);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const Args a, int pass) {
+  __shared__ uint32_t h[kWaves][256];
+  __shared__ uint32_t lds_sel[kWaves + 3];
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
+  SegCtrl& c = a.ctrl[0];
+  const Digit dg = choose_digit(pass_hist(a, pass - 1), pass - 1, c.sel_prefix[pass - 2],
+                                c.sel_krem[pass - 2], lds_sel);  // barriers
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    c.sel_prefix[pass - 1] = dg.prefix;
+    c.sel_krem[pass - 1] = dg.k_rem;
+  }
+  const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  const int hi_shift = digit_shift(pass - 1);
+  const int shift = digit_shift(pass);
+  const uint32_t mask = (1u << digit_bits(pass)) - 1u;
+  uint32_t* hw = h[wave_id()];
+  for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key) {
+    if ((key >> hi_shift) == dg.prefix) atomicAdd(&hw[(key >> shift) & mask], 1u);
+  });
+  __syncthreads();
+  const int bin = threadIdx.x;
+  uint32_t v = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) v += h[w][bin];
+  if (v) atomicAdd(&pass_hist(a, pass)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+}
+
+// After the last digit: T, the ties to keep, whether they must be ranked; per tile, the number of
+// survivors (keys above T; keys equal to T as well when all of them are kept) and, when ties are
+// ranked, the number of keys equal to T.
+__global__ __launch_bounds__(kBlock) void k_topk_cand_final(const Args a) {
+  __shared__ uint32_t lds_sel[kWaves + 3];
+  SegCtrl& c = a.ctrl[0];
+  const Digit dg = choose_digit(pass_hist(a, 3), 3, c.sel_prefix[2], c.sel_krem[2], lds_sel);
+  const uint32_t T = dg.prefix;
+  const bool rank_ties = dg.count > dg.k_rem;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    c.topk_key = T;
+    c.topk_take = dg.k_rem;
+    c.n_eq = dg.count;
+    c.rank_ties = rank_ties ? 1u : 0u;
+    sparsify_result& r = a.result[0];
+    r.topk_key = T;
+    r.topk_ties_taken = dg.k_rem;
+  }
+  const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  const uint32_t tile = blockIdx.x * kWaves + wave_id();
+  uint32_t gt = 0, eq = 0;
+  for_each_candidate(a, tile, ntiles, [&](uint32_t key) {
+    gt += key > T ? 1u : 0u;
+    eq += key == T ? 1u : 0u;
+  });
+  gt = wave_sum(gt);
+  eq = wave_sum(eq);
+  if (tile < ntiles && lane_id() == 0) {
+    const uint32_t taken = tile_row(a, kRowAbove)[tile] + gt + (rank_ties ? 0u : eq);
+    tile_row(a, kRowTake)[tile] = taken;
+    uint32_t* grp = a.group_counts + (tile / kGroupTiles) * kNumThres;
+    if (taken) atomicAdd(&grp[kColTake], taken);
+    if (rank_ties) {
+      tile_row(a, kRowTies)[tile] = eq;
+      if (eq) atomicAdd(&grp[kColTies], eq);
+    }
+  }
+}
+
+// ---- compaction in index order, residual write -------------------------------------------------
+template <bool FULL, bool NORMS>
+__device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, uint32_t T, uint32_t take,
+                                             bool rank_ties, uint32_t& out_run, uint32_t& tie_run,
+                                             uint32_t* lds, NormAcc& norms) {
+  float v[kPerThread];
+  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+  uint32_t sel = 0, eq = 0;
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    if (FULL || ((valid >> i) & 1u)) {
+      const uint32_t key = mag_key(v[i]);
+      sel |= ((key > T || (!rank_ties && key == T)) ? 1u : 0u) << i;
+      eq |= ((rank_ties && key == T) ? 1u : 0u) << i;
+    }
+  }
+  uint32_t first[kSlots];
+  if (rank_ties && __syncthreads_or(eq != 0)) {
+    // keep a tie only if fewer than `take` ties precede it in index order
+    const uint32_t n_eq = tile_rank(eq, lds, first);
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+      uint32_t r = tie_run + first[j];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if ((eq >> (4 * j + q)) & 1u) {
+          if (r < take) sel |= 1u << (4 * j + q);
+          ++r;
+        }
+      }
+    }
+    tie_run += n_eq;
+    __syncthreads();  // lds is reused below
+  }
+  const uint32_t n_sel = tile_rank(sel, lds, first);
+#pragma unroll
+  for (int j = 0; j < kSlots; ++j) {
+    uint32_t r = out_run + first[j];
+    const int64_t i0 = slot_index(t, j);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if ((sel >> (4 * j + q)) & 1u) {
+        if ((int64_t)r < a.flat_cap) {
+          a.out_idx[r] = (uint32_t)(i0 + q);
+          a.out_val[r] = v[4 * j + q];
+        }
+        ++r;
+      }
+    }
+  }
+  out_run += n_sel;
+  if (NORMS) norm_accumulate(norms, v, valid, sel);
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i)
+    if ((sel >> i) & 1u) v[i] = 0.0f;
+  store_tile<FULL>(a.resid, t, v, valid);
+  __syncthreads();  // lds is reused by the next chunk
+}
+
+template <bool NORMS>
+__global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
+  __shared__ uint32_t lds[kSlots * kWaves];
+  __shared__ uint32_t lds_base[2];
+  __shared__ double lds_n[2 * kWaves];
+  const uint32_t tile = blockIdx.x;
+  Span sp_;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  const SegCtrl& c = a.ctrl[0];
+  const uint32_t T = c.topk_key, take = c.topk_take;
+  const bool rank_ties = c.rank_ties != 0;
+  const uint32_t g = tile / kGroupTiles, g0 = g * kGroupTiles, within = tile - g0;
+  if (wave_id() == 0) {  // survivors and ties before this tile: whole groups, then tiles of its own
+    uint32_t x = 0, y = 0;
+    if ((uint32_t)lane_id() < g) x += a.group_counts[lane_id() * kNumThres + kColTake];
+    if ((uint32_t)lane_id() < within) x += tile_row(a, kRowTake)[g0 + lane_id()];
+    if (rank_ties) {
+      if ((uint32_t)lane_id() < g) y += a.group_counts[lane_id() * kNumThres + kColTies];
+      if ((uint32_t)lane_id() < within) y += tile_row(a, kRowTies)[g0 + lane_id()];
+    }
+    x = wave_sum(x);
+    y = wave_sum(y);
+    if (lane_id() == 0) {
+      lds_base[0] = x;
+      lds_base[1] = y;
+    }
+  }
+  __syncthreads();
+  uint32_t tie_run = lds_base[1];
+  uint32_t out_run = lds_base[0] + (tie_run < take ? tie_run : take);
+  NormAcc norms = {0.0, 0.0};
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) ordered_compact_chunk<true, NORMS>(a, t, T, take, rank_ties, out_run, tie_run, lds, norms);
+    else ordered_compact_chunk<false, NORMS>(a, t, T, take, rank_ties, out_run, tie_run, lds, norms);
+  }
+  if (NORMS) store_norm_partial(a, norms, tile, lds_n);
+}
+
+}  // namespace sp

@@ -65,6 +65,29 @@ def test_topk_ties_and_special_values(d):
             check_flat("topk", gpu, acc, zero, k, what=f"topk {name} d={d} k={k}")
 
 
+@pytest.mark.parametrize("inplace", [False, True])
+def test_topk_ranked_ties_across_tile_groups(inplace):
+    """Hundreds of tiles (several groups of 64), keys drawn from a handful of values: the k-th key
+    is shared by thousands of entries and only the lowest-index ones are kept."""
+    d = 1_000_003
+    rng = np.random.default_rng(2024)
+    zero = np.zeros(d, np.float32)
+    vecs = {"small_ints": rng.integers(-3, 4, d).astype(np.float32),
+            "two_exponents": (rng.integers(1, 5, d) * np.float32(0.5)).astype(np.float32),
+            "constant": np.full(d, -2.5, np.float32)}
+    late = np.zeros(d, np.float32)           # every tie of the k-th key sits in the last tiles
+    late[d - 5000:] = 1.0
+    late[:100] = 2.0
+    vecs["ties_at_the_end"] = late
+    gpu = FlatGpu(d, cap=d, inplace=inplace)
+    for name, acc in vecs.items():
+        for k in (1, 1000, d // 7, d // 2, d - 1):
+            for tc in (1, 0):
+                gpu.set_residual(zero)
+                check_flat("topk", gpu, acc, zero, k, what=f"topk {name} k={k} tc={tc} inplace={inplace}",
+                           tile_chunks=tc)
+
+
 @pytest.mark.parametrize("d", [777, 20_011])
 def test_gaussiank_special_values(d):
     rng = np.random.default_rng(d + 1)
