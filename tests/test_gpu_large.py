@@ -27,8 +27,10 @@ def test_134m_elements_against_oracle(selector):
         progress(f"134M {selector} step {step} ok")
 
 
-def test_537m_elements_properties():
-    d = 1 << 29
+@pytest.mark.parametrize("d", [1 << 29, (1 << 31) - 1], ids=["537m", "largest_d"])
+def test_properties_at_sizes_beyond_the_oracle(d):
+    """2^29 (the top of the paper's range) and 2^31 - 1 (the largest d the interface accepts:
+    ragged tail, indices up to 2^31 - 2, 64-bit offsets everywhere)."""
     k = synth.k_of(d, 1000)
     cap = 4 * k
     g = synth.normal(d, 402, 0, 1e-3)
@@ -46,9 +48,10 @@ def test_537m_elements_properties():
     exp = g.copy()
     exp[want] = 0.0
     assert same_bits(got["eps"], exp)
+    del exp
     assert abs(float(res["mean"]) - float(np.mean(g, dtype=np.float64))) < 1e-12
     assert abs(float(res["std"]) / float(np.std(g.astype(np.float64), ddof=1)) - 1) < 1e-9
-    progress("537M gaussiank ok")
+    progress(f"d={d} gaussiank ok")
     # Top_k: exactly k, every kept magnitude >= every dropped one, ties only at the k-th key
     gpu.b.residual.zero_()
     got = gpu.step("topk", g, k)
@@ -68,4 +71,4 @@ def test_537m_elements_properties():
     exp = g.copy()
     exp[idx] = 0.0
     assert same_bits(got["eps"], exp)
-    progress("537M topk ok")
+    progress(f"d={d} topk ok")
