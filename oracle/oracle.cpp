@@ -167,6 +167,73 @@ int oracle_gaussiank(int64_t d, int64_t k, const float* acc, int64_t cap, double
   return 0;
 }
 
+// Counter-based choice of the sample position inside stratum j: a 64-bit finaliser of the
+// (seed, j) pair (xor-shift-multiply rounds with the constants of the SplitMix64 generator,
+// Steele, Lea & Flood 2014), whose high 32 bits are scaled to [0, len) by a multiply-shift.
+static uint64_t stratum_hash(uint64_t seed, uint64_t j) {
+  uint64_t x = seed + (j + 1) * 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+int oracle_dgck(int64_t d, int64_t k, const float* acc, int32_t sample_stride, uint64_t seed,
+                uint32_t* idx, float* val, float* eps_out, oracle_result* res,
+                uint32_t* sample_pos) {
+  if (d < 1 || d >= (int64_t(1) << 31) || k < 1 || k > d || sample_stride < 1) return 1;
+  clear_result(res);
+  const int64_t S = sample_stride;
+  const int64_t m = (d + S - 1) / S;
+  // the sample: one position per stratum
+  std::vector<uint32_t> skey((size_t)m);
+  for (int64_t j = 0; j < m; ++j) {
+    const int64_t lo = j * S;
+    const uint64_t len = (uint64_t)std::min<int64_t>(S, d - lo);
+    const uint64_t hi32 = stratum_hash(seed, (uint64_t)j) >> 32;
+    const int64_t p = lo + (int64_t)((hi32 * len) >> 32);
+    if (sample_pos) sample_pos[j] = (uint32_t)p;
+    skey[(size_t)j] = mag_key(acc[p]);
+  }
+  // first selection: the k_s-th largest magnitude of the sample is the threshold
+  const int64_t ks = (k * m + d - 1) / d;
+  std::nth_element(skey.begin(), skey.begin() + (ks - 1), skey.end(), std::greater<uint32_t>());
+  const uint32_t Ts = skey[(size_t)(ks - 1)];
+  // keep what reaches the threshold
+  std::vector<uint32_t> kept;
+  for (int64_t i = 0; i < d; ++i)
+    if (mag_key(acc[i]) >= Ts) kept.push_back((uint32_t)i);
+  const int64_t n = (int64_t)kept.size();
+  res->rounds = 1;
+  res->count[0] = (uint32_t)n;
+  res->count[1] = (uint32_t)m;
+  res->count[2] = (uint32_t)ks;
+  std::memcpy(&res->thres_f32, &Ts, 4);
+  res->thres = (double)res->thres_f32;
+  res->topk_key = Ts;
+  if (n > k) {
+    // second selection, on the kept entries only: larger magnitude first, lower index first
+    std::stable_sort(kept.begin(), kept.end(), [&](uint32_t a, uint32_t b) {
+      return mag_key(acc[a]) > mag_key(acc[b]);  // kept is in index order: stable = lower index
+    });
+    const uint32_t T = mag_key(acc[kept[(size_t)(k - 1)]]);
+    kept.resize((size_t)k);
+    uint32_t ties = 0;
+    for (uint32_t i : kept) ties += mag_key(acc[i]) == T ? 1u : 0u;
+    std::sort(kept.begin(), kept.end());
+    res->rounds = 2;
+    res->topk_key = T;
+    res->topk_ties_taken = ties;
+  }
+  for (int64_t i = 0; i < d; ++i) eps_out[i] = acc[i];
+  for (size_t j = 0; j < kept.size(); ++j) {
+    idx[j] = kept[j];
+    val[j] = acc[kept[j]];
+    eps_out[kept[j]] = 0.0f;
+  }
+  res->nnz = (uint32_t)kept.size();
+  return 0;
+}
+
 int oracle_randk_dense(int64_t d, int64_t k, const float* acc, const uint32_t* chosen,
                        float* dense_out) {
   if (d < 1 || k < 1 || k > d) return 1;

@@ -13,7 +13,9 @@
  * Gaussian closed form of the Top_k error ratio and the (1-k/d)^2 bound of
  * Theorem 1; the normal quantile against tabulated values and a library
  * routine; moments against closed forms; Algorithm 1's count-and-nudge walk
- * against counts known in closed form on constructed vectors.
+ * against counts known in closed form on constructed vectors; DGC_k against Top_k when the
+ * sample is the whole vector, against planted vectors whose outcome is known, and against the
+ * exact Top_k whenever its second selection runs.
  * Parity unpinned (conventions the paper does not fix; both sides implement the
  * same reading): the two-sided tail 1-k/(2d) default, the sample (n-1) standard
  * deviation, the fp32 rounding of the threshold before comparing, and the use of
@@ -65,6 +67,25 @@ int oracle_topk(int64_t d, int64_t k, const float* acc, uint32_t* idx, float* va
 int oracle_gaussiank(int64_t d, int64_t k, const float* acc, int64_t cap, double tail_div,
                      int32_t ddof, uint32_t* idx, float* val, float* eps_out,
                      oracle_result* res);
+
+/* DGC_k, the hierarchical-sampling selection the paper compares against (Sec. 3.3; Sec. 4.3
+ * uses a 1 % sample): a top-k on a sample gives a threshold, the entries at or above it are
+ * kept, and if that is more than k a second top-k runs on those.  The paper gives no more
+ * than that; the rest is this build's reading, shared by both sides (parity unpinned):
+ *   sample   one position per stratum [j*S, min((j+1)*S, d)), S = sample_stride, chosen by a
+ *            counter-based hash of (seed, j): m = ceil(d/S) positions (written to
+ *            sample_pos if it is not null);
+ *   first    k_s = ceil(k*m/d); the threshold is the k_s-th largest |acc| of the sample;
+ *   keep     every i with |acc[i]| >= threshold (n of them);
+ *   second   only if n > k: the k largest of the kept, lower index wins ties.
+ * res: nnz; rounds = top-k selections run (1 or 2); count[0] = n, count[1] = m,
+ * count[2] = k_s; thres_f32 / thres = the sample threshold; topk_key = bit pattern of the
+ * smallest kept magnitude bound (the k-th key when the second selection ran, else the
+ * threshold's); topk_ties_taken = entries equal to the k-th key kept by the second selection
+ * (0 when it did not run).  Pairs ascending in index, eps_out as for Top_k. */
+int oracle_dgck(int64_t d, int64_t k, const float* acc, int32_t sample_stride, uint64_t seed,
+                uint32_t* idx, float* val, float* eps_out, oracle_result* res,
+                uint32_t* sample_pos);
 
 /* Rand_k (Sec. 1) with the random choice passed in: dense out[i] = acc[i] on the k given
  * (distinct) indices, 0 elsewhere. */

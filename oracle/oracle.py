@@ -62,6 +62,8 @@ def lib():
         L.oracle_gaussiank.argtypes = [C.c_int64, C.c_int64, fp, C.c_int64, C.c_double, C.c_int32,
                                        up, fp, fp, C.POINTER(_Result)]
         L.oracle_randk_dense.argtypes = [C.c_int64, C.c_int64, fp, up, fp]
+        L.oracle_dgck.argtypes = [C.c_int64, C.c_int64, fp, C.c_int32, C.c_uint64, up, fp, fp,
+                                  C.POINTER(_Result), up]
         L.oracle_segmented.argtypes = [C.c_int32, ip, ip, C.c_int32, fp, ip, C.c_double, C.c_int32,
                                        up, fp, fp, C.POINTER(_Result)]
         _lib = L
@@ -131,6 +133,24 @@ def gaussiank(acc: np.ndarray, k: int, cap: int = None, tail_div: float = 2.0, d
     if rc != 0:
         raise ValueError("oracle_gaussiank: invalid arguments")
     return idx[:r.nnz], val[:r.nnz], eps, Result.of(r)
+
+
+def dgck(acc: np.ndarray, k: int, sample_stride: int = 100, seed: int = 0,
+         eps_out: np.ndarray = None, idx: np.ndarray = None, val: np.ndarray = None,
+         want_positions: bool = False):
+    """-> (idx[nnz] ascending, val[nnz], eps_out[d], Result[, sample positions]); nnz <= k."""
+    idx = np.empty(max(k, 1), np.uint32) if idx is None else idx
+    val = np.empty(max(k, 1), np.float32) if val is None else val
+    eps = np.empty_like(acc) if eps_out is None else eps_out
+    m = -(-acc.size // sample_stride) if sample_stride >= 1 else 1
+    pos = np.empty(m, np.uint32) if want_positions else None
+    r = _Result()
+    rc = lib().oracle_dgck(acc.size, k, _f(acc), sample_stride, seed, _u(idx), _f(val), _f(eps),
+                           C.byref(r), _u(pos) if want_positions else None)
+    if rc != 0:
+        raise ValueError("oracle_dgck: invalid arguments")
+    out = (idx[:r.nnz], val[:r.nnz], eps, Result.of(r))
+    return out + (pos,) if want_positions else out
 
 
 def randk_dense(acc: np.ndarray, chosen: np.ndarray) -> np.ndarray:

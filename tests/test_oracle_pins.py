@@ -409,3 +409,105 @@ def test_gaussiank_compare_is_strict_on_constant_vectors():
             assert list(res.count) == [1000] * 4 and res.nnz == 1000
             assert res.thres == 3.375 * c
         check_residual_identity(x, idx, val, eps)
+
+
+# ---- DGC_k (Sec. 3.3, Sec. 4.3): hierarchical sampling, two top-k selections -----------------
+# The paper fixes the structure (top-k on a sample -> threshold -> keep what reaches it -> top-k
+# again if that is too many); the sampling rule and the constants are this build's reading, so
+# the pins below are the cases where the outcome does not depend on that reading, plus the
+# invariants every reading must satisfy.
+
+def test_dgck_with_the_whole_vector_as_sample_is_exact_topk():
+    """Stride 1: the sample is the vector, k_s = k, the threshold is the k-th key, and the
+    second selection (run when ties push the count above k) must leave the brute-force Top_k."""
+    rng = np.random.default_rng(11)
+    ran_second = 0
+    for d in (1, 2, 7, 32, 61):
+        for acc in tiny_vectors(d, rng):
+            for k in range(1, d + 1):
+                idx, val, eps, res = O.dgck(acc, k, sample_stride=1, seed=rng.integers(1 << 40))
+                want = brute_topk(acc, k)
+                assert np.array_equal(idx, want), (d, k)
+                assert np.array_equal(val.view(np.uint32), acc[want].view(np.uint32))
+                n = int(np.count_nonzero(key_of(acc) >= np.sort(key_of(acc))[::-1][k - 1]))
+                assert res.count == (n, d, k, 0) and res.rounds == (2 if n > k else 1)
+                ran_second += res.rounds == 2
+    assert ran_second > 100
+
+
+def test_dgck_sample_threshold_and_both_branches_on_planted_vectors():
+    """The positions depend on (d, stride, seed) only.  Planting large values on chosen
+    positions fixes the sample threshold and the count above it in closed form."""
+    d, S, k = 5000, 50, 100                     # m = 100 strata, k_s = ceil(100*100/5000) = 2
+    seed = 424242
+    base = np.full(d, 0.25, np.float32)
+    base[1::2] = -0.25
+    _, _, _, res0, pos = O.dgck(base, k, S, seed, want_positions=True)
+    assert pos.size == 100
+    assert np.all(pos // S == np.arange(100))   # one position inside each stratum
+    assert len(set((pos % S).tolist())) > 10    # and not a fixed offset
+    # constant magnitude: the threshold is that magnitude, everything is kept, the second
+    # selection leaves the k lowest indices
+    idx, _, eps, res = O.dgck(base, k, S, seed)
+    assert res.count[:3] == (d, 100, 2) and res.rounds == 2 and res.thres_f32 == np.float32(0.25)
+    assert np.array_equal(idx, np.arange(k)) and res.topk_ties_taken == k
+    assert np.all(eps[:k] == 0) and np.array_equal(eps[k:], base[k:])
+    # under-selection: 7 large entries, 3 of them on sample positions -> threshold = the 2nd
+    # largest sampled = 8.0, kept = the entries >= 8.0: five of the seven
+    x = base.copy()
+    off = [int(p) for p in range(d) if p not in set(pos.tolist())][:4]
+    x[pos[10]], x[pos[20]], x[pos[30]] = 9.0, -8.0, 4.0
+    x[off[0]], x[off[1]], x[off[2]], x[off[3]] = 16.0, -8.0, 8.5, 5.0
+    idx, val, eps, res = O.dgck(x, k, S, seed)
+    want = np.sort(np.array([pos[10], pos[20], off[0], off[1], off[2]], np.uint32))
+    assert res.rounds == 1 and res.nnz == 5 and res.count[:3] == (5, 100, 2)
+    assert res.thres_f32 == np.float32(8.0) and res.topk_ties_taken == 0
+    assert np.array_equal(idx, want) and np.array_equal(val, x[want])
+    exp = x.copy()
+    exp[want] = 0
+    assert np.array_equal(eps, exp)
+    # over-selection: 150 entries of magnitude 2 (> k), two of them sampled -> threshold 2.0,
+    # kept 150 + nothing else, second selection keeps the 100 lowest-index ones
+    y = base.copy()
+    where = np.sort(np.concatenate([pos[[5, 50]], np.array(off[:4]),
+                                    np.setdiff1d(np.arange(1000, 1200), pos)[:144]]))
+    assert where.size == 150
+    y[where] = np.where(np.arange(150) % 2 == 0, 2.0, -2.0).astype(np.float32)
+    idx, _, _, res = O.dgck(y, k, S, seed)
+    assert res.count[:3] == (150, 100, 2) and res.rounds == 2 and res.nnz == k
+    assert np.array_equal(idx, where[:k].astype(np.uint32)) and res.topk_ties_taken == k
+
+
+@pytest.mark.parametrize("name", ["normal", "student", "ties"])
+def test_dgck_invariants_on_random_vectors(name):
+    """Whatever the sample: the threshold is the k_s-th largest sampled magnitude; the count is
+    the number of entries reaching it; if the count exceeds k the result is the exact Top_k
+    (the kept entries are the largest ones, so the largest k of them are the largest k of all),
+    otherwise the result is everything that reaches the threshold."""
+    rng = np.random.default_rng(5)
+    d = 40_000
+    acc = {"normal": synth.normal(d, 3, 0, 1e-3), "student": synth.student_t3(d, 4, 0, 1e-3),
+           "ties": rng.integers(-20, 21, d).astype(np.float32)}[name]
+    key = key_of(acc)
+    seen = set()
+    for S in (3, 20, 100, 1000):
+        for k in (1, 40, 400, 4000):
+            for seed in (0, 1, 99):
+                idx, val, eps, res, pos = O.dgck(acc, k, S, seed, want_positions=True)
+                m = -(-d // S)
+                ks = -(-(k * m) // d)
+                assert np.all(pos // S == np.arange(m)) and pos.max() < d
+                Ts = int(np.sort(key[pos])[::-1][ks - 1])
+                n = int(np.count_nonzero(key >= Ts))
+                assert res.count == (n, m, ks, 0)
+                assert res.thres_f32.view(np.uint32) == Ts
+                if n > k:
+                    assert res.rounds == 2 and np.array_equal(idx, brute_topk(acc, k))
+                else:
+                    assert res.rounds == 1 and np.array_equal(idx, np.nonzero(key >= Ts)[0])
+                assert np.array_equal(val.view(np.uint32), acc[idx].view(np.uint32))
+                exp = acc.copy()
+                exp[idx] = 0
+                assert np.array_equal(eps.view(np.uint32), exp.view(np.uint32))
+                seen.add(res.rounds)
+    assert seen == {1, 2}
