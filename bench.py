@@ -124,6 +124,13 @@ def main() -> int:
     gk_stage, gk_nnz, gk_rounds = traced(S.sparsify_gaussiank)
     tk_ms, tk_wall, tk_ev = timed(S.sparsify_topk)
     tk_stage, tk_nnz, _ = traced(S.sparsify_topk)
+    dg = None
+    if not args.inplace and not args.no_extras:  # the sampling comparator of Sec. 4.3 (1 % sample)
+        dg_ms, _, _ = timed(S.sparsify_dgck)
+        dg_stage, dg_nnz, dg_rounds = traced(S.sparsify_dgck)
+        dg = {"ms_per_step": round(dg_ms, 5), "nnz_mean": float(np.mean(dg_nnz)),
+              "selections_mean": float(np.mean(dg_rounds)),
+              "kernel_ms": {n: round(v, 5) for n, v in dg_stage.items()}}
 
     def gbps(bytes_per_elem, nnz_mean, ms):
         return (bytes_per_elem * d + 8.0 * nnz_mean) / (ms * 1e-3) / 1e9
@@ -205,6 +212,7 @@ def main() -> int:
                  "bytes_per_elem": tk_bpe,
                  "kernel_ms": {n: round(v, 5) for n, v in tk_stage.items()}},
         "gaussiank_speedup_over_topk": round(tk_ms / gk_ms, 3),
+        "dgck": dg,
         "also": extras,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -54,10 +54,12 @@ enum {
 /* Written on the stream; valid once the stream has been synchronised. */
 typedef struct {
   uint32_t nnz;       /* pairs written */
-  uint32_t rounds;    /* Gaussian_k: count evaluations performed, 1..4.  Top_k: 0 */
-  uint32_t count[4];  /* Gaussian_k: estimated_k of each evaluation (Alg. 1, step 7) */
+  uint32_t rounds;    /* Gaussian_k: count evaluations performed, 1..4.  Top_k: 0.  DGC_k: top-k
+                         selections performed, 1 or 2 */
+  uint32_t count[4];  /* Gaussian_k: estimated_k of each evaluation (Alg. 1, step 7).  DGC_k: entries
+                         that reach the sample's threshold, sample size, rank used in the sample */
   uint32_t flags;     /* SPARSIFY_F_* */
-  float thres_f32;    /* fp32 value the final mask compared against */
+  float thres_f32;    /* fp32 value the final mask compared against (DGC_k: the sample's threshold) */
   double mean, std;   /* Alg. 1 step 2 (std with divisor d - ddof) */
   double z;           /* upper-tail normal quantile of k / (tail_div * d) */
   double thres0;      /* mean + std * z (Alg. 1 step 4) */
@@ -80,7 +82,9 @@ typedef struct {
   void* trace;     /* NULL, or a sparsify_trace* to record per-kernel timings of this call */
   int32_t error_norms; /* 0 (default).  1: also reduce ||acc||^2 and ||residual'||^2 (fp64) into the
                       result record; the sums ride on the compaction pass, one small launch more */
-  int32_t reserved;
+  int32_t sample_stride; /* DGC_k only.  0 (default): 100, a 1 % sample (Sec. 4.3).  Otherwise the
+                      stratum length S >= 1: one sampled position per S consecutive elements */
+  uint64_t sample_seed;  /* DGC_k only: seed of the counter-based choice of those positions */
 } sparsify_opts;
 
 /* Bytes of `workspace` needed for a vector of d_total elements in num_segments segments
@@ -107,6 +111,21 @@ int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual,
  * among equal magnitudes the lower index wins).  Same arguments; cap >= k is required; exactly
  * k pairs are written.  opts: tail_div and ddof are checked but not used. */
 int sparsify_topk(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                  uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
+                  void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
+                  void* stream);
+
+/* DGC_k, the hierarchical-sampling selection the paper compares Gaussian_k with (Sec. 3.3; a
+ * 1 % sample in Sec. 4.3): an exact top-k on a sample of |acc| gives a threshold, every entry
+ * whose magnitude reaches it is kept, and if those are more than k an exact top-k (lower index
+ * wins ties) is run on them.  The paper gives only this outline; the sample (one position per
+ * stratum of opts->sample_stride elements, chosen by a hash of opts->sample_seed and the
+ * stratum's number), the rank ceil(k m / d) inside a sample of m, and ">=" are this library's
+ * reading.  Same arguments as sparsify_topk; cap >= k is required; at most k pairs are written,
+ * in ascending index order (fewer than k when the sample's threshold is too high: nothing is
+ * added then).  acc == residual is not supported (SPARSIFY_E_INVALID).  result: see the fields'
+ * comments; topk_key is the smallest magnitude that could be kept (bit pattern). */
+int sparsify_dgck(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
                   uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
                   void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
                   void* stream);

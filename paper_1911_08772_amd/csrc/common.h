@@ -50,11 +50,10 @@ struct SegCtrl {
   uint32_t n_eq;            // number of keys equal to the k-th key
   uint32_t rank_ties;       // 1 if only some of the equal keys are kept (needs index order)
   uint32_t cursor;          // output slots handed out so far (starts after the ordered part)
-  uint32_t sel_prefix[3];   // fused flat path: prefix and rank left after the digit of pass 0..2
-  uint32_t sel_krem[3];     //   (one slot per pass: a kernel reads one slot and writes the next)
-  uint32_t topk_key;        // fused flat path: the k-th key and the ties to keep
+  uint32_t sel_prefix[8];   // fused flat paths: prefix and rank left after each digit choice
+  uint32_t sel_krem[8];     //   (one slot per choice: a kernel reads one slot and writes the next)
+  uint32_t topk_key;        // fused flat paths: the k-th key and the ties to keep
   uint32_t topk_take;
-  uint32_t pad1;
 };
 
 struct Args {
@@ -88,6 +87,11 @@ struct Args {
   uint32_t moment_parts;  // flat calls: number of moment partials (accumulate workgroups)
   int32_t ddof;
   double tail_div;
+  // DGC_k
+  int64_t sample_stride;  // stratum length S
+  int64_t sample_m;       // number of strata = sample size
+  int64_t sample_k;       // rank of the threshold inside the sample
+  uint64_t sample_seed;
 };
 
 // Tile j of a segment covers the absolute range [base + j*E, base + (j+1)*E) cut to

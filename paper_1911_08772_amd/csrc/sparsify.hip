@@ -12,6 +12,7 @@
 #include "setup.h"
 #include "sparsify.h"
 #include "topk.h"
+#include "dgck.h"
 #include "topk_filter.h"
 #include "topk_flat.h"
 
@@ -97,7 +98,7 @@ Carve carve(int64_t d_total, int32_t L) {
   c.group_counts = off; off = align_up(off + sizeof(uint32_t) * kMaxGroups * kNumThres);
   c.norm_partial = off; off = align_up(off + sizeof(double) * 2 * mt);
   size_t hist_words = (size_t)256 * (size_t)L * hist_copies_of(L);
-  if (hist_words < (size_t)kTopkHistWords) hist_words = kTopkHistWords;  // four per-pass buffers (flat)
+  if (hist_words < (size_t)kDgcHistWords) hist_words = kDgcHistWords;  // per-pass buffers (flat): 4 or 8
   c.hist = off;        off = align_up(off + sizeof(uint32_t) * hist_words);
   c.total = off;
   return c;
@@ -238,7 +239,7 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 pg(tiles);
   if (!SEG && tiles <= (uint32_t)kFusedMaxTiles && !a.inplace) {  // see topk_filter.h
     const dim3 cg((tiles + kWaves - 1) / kWaves);  // one wave per tile's candidate list
-    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a);
+    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
     ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
     ln.run("topk_filter", k_topk_filter, pg, blk, a);
     ln.run("topk_cand2", k_topk_cand_hist, cg, blk, a, 2);
@@ -253,7 +254,7 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
     return;
   }
   if (!SEG && tiles <= (uint32_t)kFusedMaxTiles) {  // seven launches: see topk_flat.h
-    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a);
+    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
     ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
     ln.run("topk_hist1", k_topk_hist_fused<false>, pg, blk, a, 1);
     ln.run("topk_hist2", k_topk_hist_fused<false>, pg, blk, a, 2);
@@ -287,25 +288,62 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   }
 }
 
-int flat_call(bool gaussian, int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+// DGC_k: eleven launches (dgck.h).
+void launch_dgck(Launcher& ln, const Args& a, uint32_t tiles) {
+  const dim3 blk(kBlock), pg(tiles), cg((tiles + kWaves - 1) / kWaves);
+  ln.run("dgck_init", k_topk_init_fused, dim3(64), blk, a, (uint32_t)kDgcHistWords);
+  ln.run("dgck_accum_sample", k_dgck_accum_sample, pg, blk, a);
+  ln.run("dgck_sample1", k_dgck_lists_hist, cg, blk, a, 1);
+  ln.run("dgck_sample2", k_dgck_lists_hist, cg, blk, a, 2);
+  ln.run("dgck_sample3", k_dgck_lists_hist, cg, blk, a, 3);
+  ln.run("dgck_filter", k_dgck_filter, pg, blk, a);
+  ln.run("dgck_kept1", k_dgck_lists_hist, cg, blk, a, 5);
+  ln.run("dgck_kept2", k_dgck_lists_hist, cg, blk, a, 6);
+  ln.run("dgck_kept3", k_dgck_lists_hist, cg, blk, a, 7);
+  ln.run("dgck_final", k_dgck_final, cg, blk, a);
+  if (a.norms) {
+    ln.run("dgck_compact", k_topk_compact_ordered<true>, pg, blk, a);
+    ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
+  } else {
+    ln.run("dgck_compact", k_topk_compact_ordered<false>, pg, blk, a);
+  }
+}
+
+enum { kSelGaussian = 0, kSelTopk = 1, kSelDgc = 2 };
+
+int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* residual, float* acc,
               uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
               void* workspace, size_t workspace_bytes, const sparsify_opts* opts, void* stream) {
   if (k < 1 || k > d) return SPARSIFY_E_INVALID;
-  if (!gaussian && cap < k) return SPARSIFY_E_INVALID;
+  if (selector != kSelGaussian && cap < k) return SPARSIFY_E_INVALID;
   Args a;
   const int rc = prepare(a, 1, d, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                          workspace_bytes, opts);
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
+  const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
+  if (selector == kSelDgc) {
+    // the per-tile key lists live in the residual buffer and the list kernels use one lane per
+    // group of tiles: separate acc and at most kFusedMaxTiles tiles
+    if (a.inplace || tiles > (uint32_t)kFusedMaxTiles) return SPARSIFY_E_INVALID;
+    int64_t S = 100;
+    if (opts && opts->sample_stride != 0) S = opts->sample_stride;
+    if (S < 1) return SPARSIFY_E_INVALID;
+    a.sample_stride = S;
+    a.sample_m = (d + S - 1) / S;
+    a.sample_k = (k * a.sample_m + d - 1) / d;
+    a.sample_seed = opts ? opts->sample_seed : 0;
+  }
   Launcher ln{static_cast<hipStream_t>(stream),
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
   ln.begin();
-  const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
-  if (gaussian) {
+  if (selector == kSelGaussian) {
     launch_gaussiank<false>(ln, a, tiles);
-  } else {
+  } else if (selector == kSelTopk) {
     launch_topk<false>(ln, a, tiles);
+  } else {
+    launch_dgck(ln, a, tiles);
   }
   if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);
   return ln.err == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;
@@ -327,7 +365,7 @@ int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual,
                        uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
                        void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
                        void* stream) {
-  return flat_call(true, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
+  return flat_call(kSelGaussian, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                    workspace_bytes, opts, stream);
 }
 
@@ -335,7 +373,15 @@ int sparsify_topk(int64_t d, int64_t k, const float* grad, float* residual, floa
                   uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
                   void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
                   void* stream) {
-  return flat_call(false, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
+  return flat_call(kSelTopk, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
+                   workspace_bytes, opts, stream);
+}
+
+int sparsify_dgck(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                  uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
+                  void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
+                  void* stream) {
+  return flat_call(kSelDgc, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                    workspace_bytes, opts, stream);
 }
 

@@ -20,10 +20,9 @@ __device__ inline uint32_t* pass_hist(const Args& a, int pass) {
   return a.hist + (size_t)pass * kTopkCopies * 256;
 }
 
-// Clears the four histograms and the group totals, resets the selection state.
-__global__ __launch_bounds__(kBlock) void k_topk_init_fused(const Args a) {
-  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < (uint32_t)kTopkHistWords;
-       i += gridDim.x * kBlock)
+// Clears `hist_words` words of histograms and the group totals, resets the selection state.
+__global__ __launch_bounds__(kBlock) void k_topk_init_fused(const Args a, uint32_t hist_words) {
+  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < hist_words; i += gridDim.x * kBlock)
     a.hist[i] = 0;
   if (blockIdx.x == 0) {
     for (uint32_t i = threadIdx.x; i < (uint32_t)(kMaxGroups * kNumThres); i += kBlock)
@@ -49,6 +48,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_fused(const Args a) {
 // descending digit).  `lds` holds kWaves + 3 words.  Three barriers.
 struct Digit {
   uint32_t prefix, k_rem, count;  // extended prefix, rank left inside the digit, keys in it
+  uint32_t total;                 // keys counted by the histogram
 };
 __device__ inline Digit choose_digit(const uint32_t* hist, int pass, uint32_t prefix,
                                      uint32_t k_rem, uint32_t* lds) {
@@ -61,6 +61,11 @@ __device__ inline Digit choose_digit(const uint32_t* hist, int pass, uint32_t pr
 #pragma unroll
   for (int r = 0; r < kTopkCopies; ++r) v += x[r];
   if (bin >= nbins) v = 0;
+  if (threadIdx.x == 0) {  // what is read back when the rank exceeds the total: nothing chosen
+    lds[kWaves] = prefix << digit_bits(pass);
+    lds[kWaves + 1] = 0;
+    lds[kWaves + 2] = 0;
+  }
   uint32_t total;
   const uint32_t above = block_exclusive_scan<kWaves>(v, lds, &total);  // keys in higher digits
   if (above < k_rem && k_rem <= above + v) {
@@ -69,7 +74,7 @@ __device__ inline Digit choose_digit(const uint32_t* hist, int pass, uint32_t pr
     lds[kWaves + 2] = v;
   }
   __syncthreads();
-  const Digit d = {lds[kWaves], lds[kWaves + 1], lds[kWaves + 2]};
+  const Digit d = {lds[kWaves], lds[kWaves + 1], lds[kWaves + 2], total};
   return d;
 }
 

@@ -26,7 +26,8 @@ RESULT_BYTES = RESULT_DTYPE.itemsize  # 96
 
 class Opts(C.Structure):
     _fields_ = [("tail_div", C.c_double), ("ddof", C.c_int32), ("tile_chunks", C.c_int32),
-                ("trace", C.c_void_p), ("error_norms", C.c_int32), ("reserved", C.c_int32)]
+                ("trace", C.c_void_p), ("error_norms", C.c_int32), ("sample_stride", C.c_int32),
+                ("sample_seed", C.c_uint64)]
 
 
 _p = C.c_void_p
@@ -38,6 +39,7 @@ _flat = [C.c_int64, C.c_int64, _p, _p, _p, _p, _p, C.c_int64, _p, _p, C.c_size_t
          C.POINTER(Opts), _p]
 lib.sparsify_gaussiank.argtypes = _flat
 lib.sparsify_topk.argtypes = _flat
+lib.sparsify_dgck.argtypes = _flat
 lib.sparsify_segmented.argtypes = [C.c_int32, C.c_int64, _p, _p, C.c_int32, _p, _p, _p, _p, _p,
                                    _p, C.c_int64, _p, _p, C.c_size_t, C.POINTER(Opts), _p]
 lib.sparsify_calibration_copy.argtypes = [_p, _p, C.c_int64, _p]
@@ -50,6 +52,7 @@ lib.sparsify_trace_stage_name.restype = C.c_char_p
 lib.sparsify_trace_stage_ms.argtypes = [_p, C.c_int32, C.POINTER(C.c_float)]
 
 EXPORTS = ["sparsify_version", "sparsify_workspace_bytes", "sparsify_gaussiank", "sparsify_topk",
+           "sparsify_dgck",
            "sparsify_segmented", "sparsify_calibration_copy", "sparsify_trace_create", "sparsify_trace_destroy",
            "sparsify_trace_num_stages", "sparsify_trace_stage_name", "sparsify_trace_stage_ms"]
 
@@ -79,9 +82,11 @@ def _stream(stream) -> int:
     return stream.cuda_stream
 
 
-def _opts(tail_div: float, ddof: int, trace, tile_chunks: int = 0, error_norms: bool = False) -> Opts:
+def _opts(tail_div: float, ddof: int, trace, tile_chunks: int = 0, error_norms: bool = False,
+          sample_stride: int = 0, sample_seed: int = 0) -> Opts:
     return Opts(float(tail_div), int(ddof), int(tile_chunks),
-                trace.handle if trace is not None else None, 1 if error_norms else 0, 0)
+                trace.handle if trace is not None else None, 1 if error_norms else 0,
+                int(sample_stride), int(sample_seed))
 
 
 def version() -> str:
@@ -126,6 +131,18 @@ def sparsify_gaussiank(d, k, grad, residual, acc, out_idx, out_val, cap, result,
                                 workspace_nbytes, C.byref(o), _stream(stream))
     if check and rc != OK:
         raise SparsifyError(rc, "sparsify_gaussiank")
+    return rc
+
+
+def sparsify_dgck(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
+                  workspace_nbytes, sample_stride=0, sample_seed=0, trace=None, stream=None,
+                  check=True, tile_chunks=0, error_norms=False) -> int:
+    o = _opts(2.0, 1, trace, tile_chunks, error_norms, sample_stride, sample_seed)
+    rc = lib.sparsify_dgck(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
+                           _ptr(out_val), cap, _ptr(result), _ptr(workspace), workspace_nbytes,
+                           C.byref(o), _stream(stream))
+    if check and rc != OK:
+        raise SparsifyError(rc, "sparsify_dgck")
     return rc
 
 

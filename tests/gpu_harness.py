@@ -45,7 +45,8 @@ class FlatGpu:
         b.out_val.fill_(float("nan"))
         if not self.inplace:
             b.acc.fill_(float("nan"))
-        fn = S.sparsify_gaussiank if selector == "gaussiank" else S.sparsify_topk
+        fn = {"gaussiank": S.sparsify_gaussiank, "topk": S.sparsify_topk,
+              "dgck": S.sparsify_dgck}[selector]
         fn(self.d, k, self.grad, b.residual, b.acc, b.out_idx, b.out_val, self.cap, b.result,
            b.workspace, b.workspace_nbytes, **kw)
         torch.cuda.synchronize()
@@ -101,6 +102,15 @@ def assert_topk_result(res, ro: O.Result, what=""):
     assert int(res["rounds"]) == 0 and int(res["flags"]) == 0, (what, res)
 
 
+def assert_dgck_result(res, ro: O.Result, what=""):
+    for name in ("nnz", "rounds", "flags", "topk_key", "topk_ties_taken"):
+        assert int(res[name]) == getattr(ro, name), (what, name, res, ro)
+    assert tuple(int(c) for c in res["count"]) == tuple(ro.count), (what, res, ro)
+    g32, o32 = np.float32(res["thres_f32"]), np.float32(ro.thres_f32)
+    assert g32.view(np.uint32) == o32.view(np.uint32), (what, g32, o32)
+    assert float(res["thres"]) == ro.thres or (math.isnan(ro.thres) and math.isnan(float(res["thres"])))
+
+
 def check_flat(selector, gpu: FlatGpu, g, eps_in, k, what="", **kw):
     """One step on both sides from the same (g, eps_in); returns the oracle's eps'."""
     acc_o = O.accumulate(g, eps_in)
@@ -110,6 +120,11 @@ def check_flat(selector, gpu: FlatGpu, g, eps_in, k, what="", **kw):
                                               tail_div=kw.get("tail_div", 2.0),
                                               ddof=kw.get("ddof", 1))
         assert_gaussiank_result(got["res"], ro, what)
+    elif selector == "dgck":
+        idx_o, val_o, eps_o, ro = O.dgck(acc_o, k, kw.get("sample_stride", 0) or 100,
+                                         kw.get("sample_seed", 0))
+        assert_dgck_result(got["res"], ro, what)
+        assert np.all(np.diff(got["idx"].astype(np.int64)) > 0), what  # ascending index order
     else:
         idx_o, val_o, eps_o, ro = O.topk(acc_o, k)
         assert_topk_result(got["res"], ro, what)

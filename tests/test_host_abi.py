@@ -31,7 +31,7 @@ def test_result_record_layout_matches_header():
     assert S.RESULT_BYTES == 96
     assert S.RESULT_DTYPE.fields["mean"][1] == 32 and S.RESULT_DTYPE.fields["topk_key"][1] == 72
     assert S.RESULT_DTYPE.fields["acc_sqnorm"][1] == 80
-    assert C.sizeof(S.Opts) == 32
+    assert C.sizeof(S.Opts) == 40 and S.Opts.sample_seed.offset == 32
 
 
 def test_workspace_bytes():
@@ -56,7 +56,7 @@ def flat_args(d=1000, k=10, cap=64, **over):
     return a, n
 
 
-@pytest.mark.parametrize("fn", [S.sparsify_gaussiank, S.sparsify_topk])
+@pytest.mark.parametrize("fn", [S.sparsify_gaussiank, S.sparsify_topk, S.sparsify_dgck])
 def test_flat_calls_reject_bad_arguments_before_any_launch(fn):
     def rc(**over):
         a, _ = flat_args(**over)
@@ -77,8 +77,17 @@ def test_flat_calls_reject_bad_arguments_before_any_launch(fn):
     assert rc(workspace=0) == S.E_WORKSPACE
     assert rc(workspace=BASE + (6 << 32) + 64) == S.E_WORKSPACE   # misaligned workspace
     assert rc(workspace_nbytes=128) == S.E_WORKSPACE
-    if fn is S.sparsify_topk:
-        assert rc(k=100, cap=99) == S.E_INVALID                   # Top_k needs cap >= k
+    if fn is not S.sparsify_gaussiank:
+        assert rc(k=100, cap=99) == S.E_INVALID                   # Top_k and DGC_k need cap >= k
+
+
+def test_dgck_rejects_in_place_buffers_and_bad_sampling():
+    a, _ = flat_args()
+    common = (a["out_idx"], a["out_val"], a["cap"], a["result"], a["workspace"], a["workspace_nbytes"])
+    assert S.sparsify_dgck(a["d"], a["k"], a["grad"], a["residual"], a["residual"], *common,
+                           stream=0, check=False) == S.E_INVALID   # its key lists need the residual
+    assert S.sparsify_dgck(a["d"], a["k"], a["grad"], a["residual"], a["acc"], *common,
+                           sample_stride=-3, stream=0, check=False) == S.E_INVALID
 
 
 def test_gaussiank_rejects_bad_options():
