@@ -1,4 +1,4 @@
-"""Operator time of Gaussian_k and exact Top_k against the vector length d (k = 0.001 d),
+"""Operator time of Gaussian_k, exact Top_k and DGC_k (1 % sample) against the vector length d (k = 0.001 d),
 the shape of the paper's GPU-efficiency experiment (Sec. 4.3: d from 1 M to 512 M on one GPU).
 
 For each d: seeded N(0, 1e-3) gradients resident in HBM, residual carried over the steps,
@@ -51,7 +51,8 @@ def main() -> int:
         b = S.Buffers.allocate(d, cap, 1, False, dev)
         stream = torch.cuda.current_stream()
         out = {"d": d, "k": k}
-        for name, fn, bpe in (("gaussiank", S.sparsify_gaussiank, 24), ("topk", S.sparsify_topk, 24)):
+        for name, fn, bpe in (("gaussiank", S.sparsify_gaussiank, 24), ("topk", S.sparsify_topk, 24),
+                              ("dgck", S.sparsify_dgck, 24)):
             b.residual.zero_()
             times = []
             for s in range(args.warmup + args.steps):
@@ -68,14 +69,17 @@ def main() -> int:
             out[name] = {"ms": round(ms, 5), "GBps": round(bpe * d / (ms * 1e-3) / 1e9, 1),
                          "Gelem_per_s": round(d / (ms * 1e-3) / 1e9, 2), "nnz_last": int(res["nnz"])}
         out["topk_over_gaussiank"] = round(out["topk"]["ms"] / out["gaussiank"]["ms"], 3)
+        out["dgck_over_gaussiank"] = round(out["dgck"]["ms"] / out["gaussiank"]["ms"], 3)
         print(json.dumps(out), flush=True)
         rows.append(out)
         del grads, b
         torch.cuda.empty_cache()
-    print(f"{'d':>12} {'k':>8} {'gaussiank ms':>13} {'GB/s':>8} {'topk ms':>9} {'GB/s':>8} {'ratio':>6}")
+    print(f"{'d':>12} {'k':>8} {'gaussiank ms':>13} {'GB/s':>8} {'topk ms':>9} {'GB/s':>8} {'ratio':>6} "
+          f"{'dgck ms':>9} {'ratio':>6}")
     for r in rows:
         print(f"{r['d']:>12} {r['k']:>8} {r['gaussiank']['ms']:>13.4f} {r['gaussiank']['GBps']:>8.0f} "
-              f"{r['topk']['ms']:>9.4f} {r['topk']['GBps']:>8.0f} {r['topk_over_gaussiank']:>6.2f}")
+              f"{r['topk']['ms']:>9.4f} {r['topk']['GBps']:>8.0f} {r['topk_over_gaussiank']:>6.2f} "
+              f"{r['dgck']['ms']:>9.4f} {r['dgck_over_gaussiank']:>6.2f}")
     return 0
 
 
