@@ -77,8 +77,9 @@ def main() -> int:
     b = S.Buffers.allocate(d, cap, 1, args.inplace, dev)
     stream = torch.cuda.current_stream()
 
-    def run(fn, s, trace=None):
-        fn(d, k, grads[s], b.residual, b.acc, b.out_idx, b.out_val, cap, b.result, b.workspace,
+    def run(fn, s, trace=None, result=None):
+        fn(d, k, grads[s], b.residual, b.acc, b.out_idx, b.out_val, cap,
+           b.result if result is None else result, b.workspace,
            b.workspace_nbytes, trace=trace, stream=stream, tile_chunks=args.tile_chunks)
 
     def timed(fn):
@@ -98,18 +99,22 @@ def main() -> int:
         return max(wall_ms, e0.elapsed_time(e1)) / K, wall_ms / K, e0.elapsed_time(e1) / K
 
     def traced(fn):
-        """Same chain again with HIP events around every kernel: average duration per kernel."""
-        tr = S.Trace()
+        """The same chain again, back to back as in the timed run, with a HIP event on the stream
+        after every kernel (one trace and one result record per step, read after one final
+        synchronisation): average duration per kernel."""
+        traces = [S.Trace() for _ in range(K)]
+        records = torch.zeros((K, S.RESULT_BYTES), dtype=torch.uint8, device=dev)
         b.residual.zero_()
         for s in range(W):
             run(fn, s)
+        for i in range(K):
+            run(fn, W + i, trace=traces[i], result=records[i])
+        stream.synchronize()
         sums, nnz, rounds = {}, [], []
-        for s in range(W, W + K):
-            run(fn, s, trace=tr)
-            stream.synchronize()
-            for name, ms in tr.stages():
+        for i in range(K):
+            for name, ms in traces[i].stages():
                 sums[name] = sums.get(name, 0.0) + ms
-            r = S.decode_results(b.result)[0]
+            r = S.decode_results(records[i])[0]
             nnz.append(int(r["nnz"]))
             rounds.append(int(r["rounds"]))
         return {n: v / K for n, v in sums.items()}, nnz, rounds

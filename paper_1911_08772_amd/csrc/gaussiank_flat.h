@@ -18,17 +18,22 @@ constexpr int kFusedMaxTiles = 4096;
 constexpr int kMaxGroups = kFusedMaxTiles / kGroupTiles;          // 64
 constexpr int kMaxMomentParts = 1024;                             // accumulate workgroups at most
 
-// K1: the accumulate kernel of gaussiank.h (k_accum_moments_flat); its workgroup 0 also clears
-// the group totals the count kernel adds into.
+// K1: the accumulate kernel of gaussiank.h (k_accum_moments_flat) on `moment_parts` workgroups,
+// plus one more workgroup that streams nothing: it clears the group totals the count kernel adds
+// into and computes the normal quantile (a few microseconds of dependent fp64 arithmetic in one
+// thread, which would otherwise stick out at the end of a workgroup that also streams).
 __global__ __launch_bounds__(kBlock) void k_accum_moments_fused(const Args a) {
   __shared__ double lds[4 * kWaves];
-  if (blockIdx.x == 0) {
+  if (blockIdx.x == a.moment_parts) {
     for (uint32_t i = threadIdx.x; i < (uint32_t)(kMaxGroups * kNumThres); i += kBlock)
       a.group_counts[i] = 0;
+    if (threadIdx.x == 0)
+      a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
+    return;
   }
   const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
   MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
-  for (uint32_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+  for (uint32_t ch = blockIdx.x; ch < nchunks; ch += a.moment_parts) {
     Tile t;
     t.seg = 0;
     t.tbase = (int64_t)ch * kChunk;
@@ -39,8 +44,6 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_fused(const Args a) {
     else accum_moments_chunk<false>(a, t, m);
   }
   store_moment_partial(a, m, blockIdx.x, lds);
-  if (blockIdx.x == 0 && threadIdx.x == 0)
-    a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
 }
 
 // K3: thresholds from the moment partials (every workgroup), then the ten counts of its tile.

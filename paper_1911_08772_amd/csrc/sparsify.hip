@@ -208,7 +208,8 @@ void launch_gaussiank(Launcher& ln, Args& a, uint32_t tiles) {
     if (want < 1) want = 1;
     a.moment_parts = want;
     if (tiles <= (uint32_t)kFusedMaxTiles) {  // three launches: see gaussiank_flat.h
-      ln.run("accum_moments", k_accum_moments_fused, dim3(want), blk, a);
+      if (want >= resident && want > 1) a.moment_parts = --want;  // room for the extra workgroup
+      ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
       ln.run("gk_count", k_gk_count_fused, dim3(tiles), blk, a);
       if (a.norms) {
         ln.run("gk_compact", k_gk_compact_fused<true>, dim3(tiles), blk, a);
