@@ -35,7 +35,7 @@ struct SegCtrl {
   int64_t k, cap, out_base; // target survivors, output capacity, first output slot
   uint32_t tile0, ntiles;   // first tile id and number of tiles of this segment
   uint32_t bad;             // layout invalid: produce nothing
-  uint32_t pad0;
+  uint32_t group0;          // first of this segment's groups of 64 tiles (layer-wise calls)
   // Gaussian_k
   double z;                 // upper-tail normal quantile of k / (tail_div * d)
   double t64[kNumThres];    // ascending order of nominal ratio (see thres_pos)
@@ -78,6 +78,8 @@ struct Args {
   uint32_t* tile_counts;  // [kNumThres][max_tiles]
   uint32_t* tile_base;    // [max_tiles]
   uint32_t* group_counts; // [64][kNumThres]: totals of groups of 64 tiles (fused flat path)
+  uint32_t* seg_groups;   // [max_groups][kNumThres]: the same per segment (layer-wise calls)
+  uint32_t max_groups;
   double* norm_partial;   // [2][max_tiles]: per-tile sum of acc^2 and of residual'^2
   uint32_t* hist;         // [L][hist_copies][256]
   uint32_t* tie_base;     // [max_tiles]

@@ -1,0 +1,209 @@
+// Gaussian_k, layer-wise calls: setup + three launches.  The same idea as gaussiank_flat.h, per
+// segment: every workgroup of the count kernel merges the moment partials of its own segment's
+// tiles and derives the ten thresholds; every workgroup of the compact kernel totals its
+// segment's groups of 64 tiles, walks Algorithm 1 and finds its first output slot.  A segment's
+// groups are its own (numbered by k_seg_setup), so no total mixes two segments' thresholds.
+// All workgroups of a segment run the same arithmetic on the same inputs in the same order.
+#pragma once
+#include "common.h"
+#include "gaussiank.h"
+#include "setup.h"
+#include "tile_io.h"
+
+namespace sp {
+
+// Counts: thresholds of the tile's segment from that segment's moment partials (one pass
+// around the provisional centre P = mean of the segment's first partial, as in
+// k_gk_count_fused), then the ten counts of the tile.
+__global__ __launch_bounds__(kBlock) void k_gk_count_seg(const Args a) {
+  __shared__ double lds_m[2 * kWaves];
+  __shared__ uint32_t lds[kWaves * kNumThres];
+  const uint32_t tile = gridDim.x - 1u - blockIdx.x;
+  Span sp_;
+  if (!locate_span<true>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[sp_.seg];
+  if (c.bad) return;
+  const uint32_t parts = c.ntiles;
+  const double* pn = a.partial + c.tile0;
+  const double* pm = pn + a.max_tiles;
+  const double* pq = pm + a.max_tiles;
+  const double z = c.z;
+  const int64_t n_seg = c.end - c.start;
+  const double P = pm[0];
+  double A = 0.0, B = 0.0;
+  for (uint32_t b0 = 0; b0 < parts; b0 += 4 * kBlock) {
+    double n[4], mu[4], q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = b0 + u * kBlock + threadIdx.x;
+      const bool ok = i < parts;
+      n[u] = ok ? pn[i] : 0.0;
+      mu[u] = ok ? pm[i] : P;
+      q[u] = ok ? pq[i] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const double dm = mu[u] - P;
+      A = fma(n[u], dm, A);
+      B += fma(n[u] * dm, dm, q[u]);
+    }
+  }
+  A = wave_sum(A);
+  B = wave_sum(B);
+  if (lane_id() == 0) {
+    lds_m[2 * wave_id()] = A;
+    lds_m[2 * wave_id() + 1] = B;
+  }
+  __syncthreads();
+  A = 0.0;
+  B = 0.0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    A += lds_m[2 * w];
+    B += lds_m[2 * w + 1];
+  }
+  const double N = (double)n_seg;
+  const double mean = P + A / N;
+  double m2 = B - A * (A / N);
+  m2 = m2 < 0.0 ? 0.0 : m2;
+  const double sd = (n_seg - a.ddof < 1) ? 0.0 : sqrt(m2 / (double)(n_seg - a.ddof));
+  const double thres0 = mean + sd * z;
+  double t64[kNumThres];
+  candidate_thresholds(thres0, t64);
+  float thr[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) thr[p] = (float)t64[p];
+  const bool can_skip = thres0 > 0.0;
+  if (tile == c.tile0 && threadIdx.x == 0) {  // the segment's first tile publishes
+#pragma unroll
+    for (int p = 0; p < kNumThres; ++p) {
+      c.t64[p] = t64[p];
+      c.t32[p] = thr[p];
+    }
+    uint32_t flags = 0;
+    if (!isfinite(mean) || !isfinite(sd) || !isfinite(thres0)) flags |= SPARSIFY_F_NONFINITE;
+    c.flags = flags;
+    sparsify_result& r = a.result[sp_.seg];
+    r.mean = mean;
+    r.std = sd;
+    r.z = z;
+    r.thres0 = thres0;
+  }
+
+  uint32_t cnt[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
+    else count_chunk<false>(a, t, thr, can_skip, cnt);
+  }
+  if (lane_id() == 0) {
+#pragma unroll
+    for (int p = 0; p < kNumThres; ++p) lds[wave_id() * kNumThres + p] = cnt[p];
+  }
+  __syncthreads();
+  if (threadIdx.x < kNumThres) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) s += lds[w * kNumThres + threadIdx.x];
+    a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile] = s;  // [threshold][tile]
+    const uint32_t g = c.group0 + (tile - c.tile0) / kSegGroupTiles;
+    if (s) atomicAdd(&a.seg_groups[(size_t)g * kNumThres + threadIdx.x], s);
+  }
+}
+
+// Totals of the segment's groups (all ten thresholds) and, of the same, what lies before `tile`:
+// the groups before its own plus the tiles before it inside its group.  Results in
+// lds_tot[kNumThres] and lds_pre[kNumThres] (integer adds in LDS: order does not matter).
+// Two barriers.
+__device__ inline void segment_totals(const Args& a, const SegCtrl& c, uint32_t tile,
+                                      uint32_t* lds_tot, uint32_t* lds_pre) {
+  if (threadIdx.x < kNumThres) {
+    lds_tot[threadIdx.x] = 0;
+    lds_pre[threadIdx.x] = 0;
+  }
+  __syncthreads();
+  const uint32_t rel = tile - c.tile0;
+  const uint32_t g_own = rel / kSegGroupTiles, within = rel % kSegGroupTiles;
+  const uint32_t ng = (c.ntiles + kSegGroupTiles - 1) / kSegGroupTiles;
+  const uint32_t* grp = a.seg_groups + (size_t)c.group0 * kNumThres;  // the segment's groups are contiguous
+  for (uint32_t i0 = 0; i0 < ng * kNumThres; i0 += 4 * kBlock) {
+    uint32_t x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * kBlock + threadIdx.x;
+      x[u] = i < ng * kNumThres ? grp[i] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * kBlock + threadIdx.x;
+      if (i < ng * kNumThres && x[u] != 0) {
+        atomicAdd(&lds_tot[i % kNumThres], x[u]);
+        if (i / kNumThres < g_own) atomicAdd(&lds_pre[i % kNumThres], x[u]);
+      }
+    }
+  }
+  const uint32_t first = c.tile0 + g_own * kSegGroupTiles;  // first tile of this tile's group
+  for (uint32_t i = threadIdx.x; i < within * kNumThres; i += kBlock) {
+    const uint32_t p = i / within, j = i % within;
+    const uint32_t x = a.tile_counts[(size_t)p * a.max_tiles + first + j];
+    if (x) atomicAdd(&lds_pre[p], x);
+  }
+  __syncthreads();
+}
+
+template <bool NORMS>
+__global__ __launch_bounds__(kBlock) void k_gk_compact_seg(const Args a) {
+  __shared__ uint32_t lds_tot[kNumThres];
+  __shared__ uint32_t lds_pre[kNumThres];
+  __shared__ uint32_t lds[kSlots * kWaves];
+  __shared__ double lds_n[2 * kWaves];
+  const uint32_t tile = blockIdx.x;
+  Span sp_;
+  if (!locate_span<true>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[sp_.seg];
+  if (c.bad) return;
+  double t64[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) t64[p] = c.t64[p];
+  const uint32_t flags0 = c.flags;
+  segment_totals(a, c, tile, lds_tot, lds_pre);
+  uint32_t tot[kNumThres];
+#pragma unroll
+  for (int p = 0; p < kNumThres; ++p) tot[p] = lds_tot[p];
+  const Walk w = walk_thresholds(tot, c.k);
+  const bool overflow = (int64_t)tot[w.pos] > c.cap;
+  const double tf = t64[w.pos];
+  const float thr = (float)tf;
+  if (tile == c.tile0 && threadIdx.x == 0) {
+    uint32_t flags = flags0;
+    if (!w.in_band) flags |= SPARSIFY_F_EXHAUSTED;
+    if (overflow) flags |= SPARSIFY_F_OVERFLOW;
+    sparsify_result& r = a.result[sp_.seg];
+    r.nnz = overflow ? 0u : tot[w.pos];
+    r.rounds = w.rounds;
+    r.count[0] = w.counts[0];
+    r.count[1] = w.counts[1];
+    r.count[2] = w.counts[2];
+    r.count[3] = w.counts[3];
+    r.flags = flags;
+    r.thres = tf;
+    r.thres_f32 = thr;
+    r.topk_key = 0;
+    r.topk_ties_taken = 0;
+    r.acc_sqnorm = 0.0;
+    r.residual_sqnorm = 0.0;
+  }
+  const int64_t out0 = c.out_base + (int64_t)lds_pre[w.pos];
+  uint32_t run = 0;
+  NormAcc norms = {0.0, 0.0};
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) run = compact_chunk<true, NORMS>(a, t, thr, overflow, out0, run, lds, norms);
+    else run = compact_chunk<false, NORMS>(a, t, thr, overflow, out0, run, lds, norms);
+  }
+  if (NORMS) store_norm_partial(a, norms, tile, lds_n);
+}
+
+}  // namespace sp

@@ -53,11 +53,15 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_flat(const Args a) {
   }
 }
 
-// Segmented calls: one block walks the segments in chunks of kBlock.
+// Segmented calls: one block walks the segments in chunks of kBlock, numbers their tiles and
+// their groups of kSegGroupTiles tiles, and clears the group totals.
 // mode 0 = Top_k, 1 = Gaussian_k.
+constexpr uint32_t kSegGroupTiles = 64;
+
 __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
   __shared__ uint32_t lds_scan[kWaves + 1];
-  uint32_t carry = 0;  // tiles numbered so far (block-uniform, saturating)
+  uint32_t carry = 0;    // tiles numbered so far (block-uniform, saturating)
+  uint32_t gcarry = 0;   // groups numbered so far
   for (int base = 0; base < a.L; base += kBlock) {
     const int s = base + (int)threadIdx.x;
     uint32_t nt = 0;
@@ -75,12 +79,16 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
       if (s == a.L - 1 && end != a.d_total) bad = true;
       if (!bad) nt = seg_ntiles(start, end, a.tile_chunks);
     }
-    uint32_t total;
+    uint32_t total, gtotal;
     const uint32_t excl = block_exclusive_scan(nt, lds_scan, &total);
+    // a layout whose valid segments overlap could number more tiles than the workspace holds
+    if (s < a.L && !bad && (uint64_t)carry + excl + nt > (uint64_t)a.max_tiles) bad = true;
+    const uint32_t ng = bad ? 0u : (nt + kSegGroupTiles - 1) / kSegGroupTiles;
+    const uint32_t gexcl = block_exclusive_scan(ng, lds_scan, &gtotal);
     if (s < a.L) {
       const uint32_t tile0 = carry + excl;
-      // a layout whose valid segments overlap could number more tiles than the workspace holds
-      if (!bad && (uint64_t)tile0 + nt > (uint64_t)a.max_tiles) bad = true;
+      const uint32_t group0 = gcarry + gexcl;
+      if (!bad && (uint64_t)group0 + ng > (uint64_t)a.max_groups) bad = true;  // cannot happen: see carve
       a.tile_start[s] = tile0;
       SegCtrl& c = a.ctrl[s];
       c.start = start;
@@ -91,6 +99,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
       c.tile0 = tile0;
       c.ntiles = bad ? 0u : nt;
       c.bad = bad ? 1u : 0u;
+      c.group0 = group0;
       c.prefix = 0;
       c.k_rem = (uint32_t)k;
       c.n_eq = 0;
@@ -113,8 +122,11 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
     }
     const uint64_t next = (uint64_t)carry + total;
     carry = next > 0x40000000ull ? 0x40000000u : (uint32_t)next;
+    gcarry += gtotal;  // <= carry / 1 + L: no overflow
   }
   if (threadIdx.x == 0) a.tile_start[a.L] = carry;
+  const uint32_t words = (gcarry < a.max_groups ? gcarry : a.max_groups) * (uint32_t)kNumThres;
+  for (uint32_t i = threadIdx.x; i < words; i += kBlock) a.seg_groups[i] = 0;
 }
 
 }  // namespace sp

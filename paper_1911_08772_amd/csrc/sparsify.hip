@@ -9,6 +9,7 @@
 #include "common.h"
 #include "gaussiank.h"
 #include "gaussiank_flat.h"
+#include "gaussiank_seg.h"
 #include "setup.h"
 #include "sparsify.h"
 #include "topk.h"
@@ -82,8 +83,9 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
 uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
 
 struct Carve {
-  size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, group_counts, norm_partial, hist,
-      total;
+  size_t ctrl, tile_start, partial, tile_counts, tile_base, tie_base, group_counts, seg_groups,
+      norm_partial, hist, total;
+  uint32_t max_groups;
 };
 Carve carve(int64_t d_total, int32_t L) {
   const size_t mt = max_tiles_of(d_total, L, 1);
@@ -96,6 +98,9 @@ Carve carve(int64_t d_total, int32_t L) {
   c.tile_base = off;   off = align_up(off + sizeof(uint32_t) * mt);
   c.tie_base = off;    off = align_up(off + sizeof(uint32_t) * mt);
   c.group_counts = off; off = align_up(off + sizeof(uint32_t) * kMaxGroups * kNumThres);
+  // a segment's tiles are totalled in groups of 64 of its own: at most tiles/64 + one per segment
+  c.max_groups = (uint32_t)(mt / kGroupTiles + (size_t)L + 1);
+  c.seg_groups = off;  off = align_up(off + sizeof(uint32_t) * kNumThres * (size_t)c.max_groups);
   c.norm_partial = off; off = align_up(off + sizeof(double) * 2 * mt);
   size_t hist_words = (size_t)256 * (size_t)L * hist_copies_of(L);
   if (hist_words < (size_t)kDgcHistWords) hist_words = kDgcHistWords;  // per-pass buffers (flat): 4 or 8
@@ -168,6 +173,8 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.tile_base = reinterpret_cast<uint32_t*>(w + cv.tile_base);
   a.tie_base = reinterpret_cast<uint32_t*>(w + cv.tie_base);
   a.group_counts = reinterpret_cast<uint32_t*>(w + cv.group_counts);
+  a.seg_groups = reinterpret_cast<uint32_t*>(w + cv.seg_groups);
+  a.max_groups = cv.max_groups;
   a.norm_partial = reinterpret_cast<double*>(w + cv.norm_partial);
   a.norms = (opts && opts->error_norms) ? 1 : 0;
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
@@ -220,8 +227,16 @@ void launch_gaussiank(Launcher& ln, Args& a, uint32_t tiles) {
       return;
     }
     ln.run("accum_moments", k_accum_moments_flat, dim3(want), blk, a);
-  } else {
-    ln.run("accum_moments", k_accum_moments<SEG>, dim3(tiles), blk, a);
+  } else {  // layer-wise: setup + three launches, see gaussiank_seg.h
+    ln.run("accum_moments", k_accum_moments<true>, dim3(tiles), blk, a);
+    ln.run("gk_count", k_gk_count_seg, dim3(tiles), blk, a);
+    if (a.norms) {
+      ln.run("gk_compact", k_gk_compact_seg<true>, dim3(tiles), blk, a);
+      ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
+    } else {
+      ln.run("gk_compact", k_gk_compact_seg<false>, dim3(tiles), blk, a);
+    }
+    return;
   }
   ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), dim3(kFinBlock), a);
   ln.run("gk_count", k_gk_count<SEG>, dim3(tiles), blk, a);

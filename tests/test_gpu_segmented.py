@@ -34,6 +34,8 @@ SMALL_LAYOUTS = [
     [4095, 4097, 1, 1, 1, 8191, 2],
     [3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37, 41, 43, 47, 53, 59, 61, 67, 71, 73] * 15,
     [100_000, 7, 250_001, 64],
+    # segments of 74, 1, 171, exactly 64 and 65 tiles: several groups of 64 tiles per segment
+    [300_000, 5, 700_001, 4096 * 64, 4096 * 64 + 1],
 ]
 
 
