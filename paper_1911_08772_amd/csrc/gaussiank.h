@@ -1,7 +1,11 @@
 // Gaussian_k (Algorithm 1) on gfx950: fused accumulate + fp64 moments, on-device normal
 // quantile, one multi-threshold count pass, on-device threshold walk, ordered compaction with
-// the residual write.  All inter-block results go through per-tile partials that a small
-// per-segment kernel combines in a fixed order: no atomics, bit-reproducible output.
+// the residual write.  This file holds the building blocks shared by all forms (quantile,
+// moment accumulation, threshold candidates, the walk, count and compact of one chunk) and the
+// five-launch form of a flat call, used only when a forced tiling leaves more tiles than the
+// three-launch form's group tables hold: there a single workgroup combines the per-tile
+// partials in a fixed order between the streaming kernels.  The three-launch flat form is in
+// gaussiank_flat.h, the layer-wise form in gaussiank_seg.h.
 #pragma once
 #include "common.h"
 #include "tile_io.h"
@@ -118,12 +122,12 @@ __device__ inline void store_moment_partial(const Args& a, const MomAcc& m, uint
   }
 }
 
-template <bool SEG>
-__global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
+// Layer-wise calls: one workgroup and one partial per tile.
+__global__ __launch_bounds__(kBlock) void k_accum_moments_seg(const Args a) {
   __shared__ double lds[4 * kWaves];
   Span sp_;
-  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
-  if (SEG && a.ctrl[sp_.seg].bad) return;
+  if (!locate_span<true>(a, blockIdx.x, &sp_)) return;
+  if (a.ctrl[sp_.seg].bad) return;
   MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
@@ -134,14 +138,9 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments(const Args a) {
   // The quantile depends on the arguments only; the workgroup of a segment's first tile
   // computes it here, hidden under the stream.
   if (threadIdx.x == 0) {
-    if (!SEG) {
-      if (blockIdx.x == 0)
-        a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
-    } else {
-      SegCtrl& c = a.ctrl[sp_.seg];
-      if (blockIdx.x == c.tile0)
-        c.z = norm_isf((double)c.k / (a.tail_div * (double)(c.end - c.start)));
-    }
+    SegCtrl& c = a.ctrl[sp_.seg];
+    if (blockIdx.x == c.tile0)
+      c.z = norm_isf((double)c.k / (a.tail_div * (double)(c.end - c.start)));
   }
 }
 
@@ -210,7 +209,7 @@ __device__ inline Walk walk_thresholds(const uint32_t (&tot)[kNumThres], int64_t
   return w;
 }
 
-// ---- K2: per segment, combine partials -> mean, std, threshold candidates -------------------
+// ---- K2: combine partials -> mean, std, threshold candidates ----------------------------------
 // Two passes over the per-tile partials, no divisions per partial:
 //   N = sum n_i, mean = sum n_i mean_i / N, M2 = sum (M2_i + n_i (mean_i - mean)^2).
 __device__ inline double fin_block_sum(double v, double* lds) {
@@ -226,20 +225,13 @@ __device__ inline double fin_block_sum(double v, double* lds) {
 
 constexpr int kFinBatch = 4;  // partials per thread per round: 4096 tiles per round
 
-template <bool SEG>
 __global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
   __shared__ double lds[kFinWaves];
-  const int s = blockIdx.x;
+  const int s = 0;
   SegCtrl& c = a.ctrl[s];
-  uint32_t tile0 = 0, ntiles = a.moment_parts;  // flat: one partial per accumulate workgroup
-  int64_t n_seg = a.d_total;
-  if (SEG) {
-    if (c.bad) return;
-    tile0 = c.tile0;
-    ntiles = c.ntiles;
-    n_seg = c.end - c.start;
-  }
-  const double* pn = a.partial + tile0;
+  const uint32_t ntiles = a.moment_parts;  // one partial per accumulate workgroup
+  const int64_t n_seg = a.d_total;
+  const double* pn = a.partial;
   const double* pm = pn + a.max_tiles;
   const double* pq = pm + a.max_tiles;
   const double z = c.z;  // issued early: its latency hides under the partial loads
@@ -354,14 +346,12 @@ __device__ inline void count_chunk(const Args& a, const Tile& t, const float (&t
 
 // The tiles are visited from the last to the first: the end of acc is what the accumulate
 // kernel wrote most recently, so it is the part most likely still to sit in the last-level cache.
-template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_gk_count(const Args a) {
   __shared__ uint32_t lds[kWaves * kNumThres];
   Span sp_;
   const uint32_t tile = gridDim.x - 1u - blockIdx.x;
-  if (!locate_span<SEG>(a, tile, &sp_)) return;
-  const SegCtrl& c = a.ctrl[sp_.seg];
-  if (SEG && c.bad) return;
+  if (!locate_span<false>(a, tile, &sp_)) return;
+  const SegCtrl& c = a.ctrl[0];
   float thr[kNumThres];
 #pragma unroll
   for (int p = 0; p < kNumThres; ++p) thr[p] = c.t32[p];
@@ -387,7 +377,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_count(const Args a) {
   }
 }
 
-// ---- K4: per segment, total the counts, walk Alg. 1 steps 5-13, scan the chosen column -------
+// ---- K4: total the counts, walk Alg. 1 steps 5-13, scan the chosen column ---------------------
 constexpr int kScanPer = 4;                        // consecutive tiles per thread per scan round
 constexpr int kScanChunk = kFinBlock * kScanPer;   // 4096 tiles staged in LDS per round
 constexpr int kTotBatch = 2;
@@ -429,23 +419,15 @@ __device__ inline uint32_t scan_tiles(const uint32_t* col, uint32_t ntiles, uint
   return carry;
 }
 
-template <bool SEG>
 __global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
   __shared__ uint32_t lds_cnt[kFinWaves * kNumThres];
   __shared__ uint32_t lds_scan[kFinWaves];
   __shared__ uint32_t lds_final;
   __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
-  const int s = blockIdx.x;
+  const int s = 0;
   SegCtrl& c = a.ctrl[s];
-  uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
-  int64_t k = a.flat_k, cap = a.flat_cap;
-  if (SEG) {
-    if (c.bad) return;
-    tile0 = c.tile0;
-    ntiles = c.ntiles;
-    k = c.k;
-    cap = c.cap;
-  }
+  const uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  const int64_t k = a.flat_k, cap = a.flat_cap;
   // thread 0 needs these after the totals; ask for them now so their latency overlaps
   double t64[kNumThres];
   uint32_t flags = 0;
@@ -572,17 +554,16 @@ __device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr
   return compact_values<FULL, NORMS>(a, t, v, valid, thr, none, out0, run, lds, norms);
 }
 
-template <bool SEG, bool NORMS>
+template <bool NORMS>
 __global__ __launch_bounds__(kBlock) void k_gk_compact(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
   Span sp_;
-  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
-  const SegCtrl& c = a.ctrl[sp_.seg];
-  if (SEG && c.bad) return;
+  if (!locate_span<false>(a, blockIdx.x, &sp_)) return;
+  const SegCtrl& c = a.ctrl[0];
   const float thr = c.t_final;
   const bool none = c.select_none != 0;
-  const int64_t out0 = (SEG ? c.out_base : 0) + (int64_t)a.tile_base[blockIdx.x];
+  const int64_t out0 = (int64_t)a.tile_base[blockIdx.x];
   uint32_t run = 0;
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {

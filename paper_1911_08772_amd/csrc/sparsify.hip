@@ -15,6 +15,7 @@
 #include "topk.h"
 #include "dgck.h"
 #include "topk_filter.h"
+#include "topk_seg.h"
 #include "topk_flat.h"
 
 using namespace sp;
@@ -102,7 +103,7 @@ Carve carve(int64_t d_total, int32_t L) {
   c.max_groups = (uint32_t)(mt / kGroupTiles + (size_t)L + 1);
   c.seg_groups = off;  off = align_up(off + sizeof(uint32_t) * kNumThres * (size_t)c.max_groups);
   c.norm_partial = off; off = align_up(off + sizeof(double) * 2 * mt);
-  size_t hist_words = (size_t)256 * (size_t)L * hist_copies_of(L);
+  size_t hist_words = (size_t)kDigits * 256 * (size_t)L * hist_copies_of(L);  // [pass][segment][replica]
   if (hist_words < (size_t)kDgcHistWords) hist_words = kDgcHistWords;  // per-pass buffers (flat): 4 or 8
   c.hist = off;        off = align_up(off + sizeof(uint32_t) * hist_words);
   c.total = off;
@@ -203,49 +204,51 @@ uint32_t resident_blocks(K kernel, int block) {
   return (uint32_t)cus * (uint32_t)per_cu;
 }
 
-template <bool SEG>
-void launch_gaussiank(Launcher& ln, Args& a, uint32_t tiles) {
+// Layer-wise Gaussian_k: setup + three launches (gaussiank_seg.h).
+void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
-  if (!SEG) {
-    static const uint32_t resident = resident_blocks(k_accum_moments_fused, kBlock);
-    const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
-    uint32_t want = resident < (uint32_t)kMaxMomentParts ? resident : (uint32_t)kMaxMomentParts;
-    if (want > nchunks) want = nchunks;
-    if (want > a.max_tiles) want = a.max_tiles;
-    if (want < 1) want = 1;
-    a.moment_parts = want;
-    if (tiles <= (uint32_t)kFusedMaxTiles) {  // three launches: see gaussiank_flat.h
-      if (want >= resident && want > 1) a.moment_parts = --want;  // room for the extra workgroup
-      ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
-      ln.run("gk_count", k_gk_count_fused, dim3(tiles), blk, a);
-      if (a.norms) {
-        ln.run("gk_compact", k_gk_compact_fused<true>, dim3(tiles), blk, a);
-        ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
-      } else {
-        ln.run("gk_compact", k_gk_compact_fused<false>, dim3(tiles), blk, a);
-      }
-      return;
-    }
-    ln.run("accum_moments", k_accum_moments_flat, dim3(want), blk, a);
-  } else {  // layer-wise: setup + three launches, see gaussiank_seg.h
-    ln.run("accum_moments", k_accum_moments<true>, dim3(tiles), blk, a);
-    ln.run("gk_count", k_gk_count_seg, dim3(tiles), blk, a);
+  ln.run("accum_moments", k_accum_moments_seg, dim3(tiles), blk, a);
+  ln.run("gk_count", k_gk_count_seg, dim3(tiles), blk, a);
+  if (a.norms) {
+    ln.run("gk_compact", k_gk_compact_seg<true>, dim3(tiles), blk, a);
+    ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
+  } else {
+    ln.run("gk_compact", k_gk_compact_seg<false>, dim3(tiles), blk, a);
+  }
+}
+
+// Flat Gaussian_k: three launches (gaussiank_flat.h); five when a forced tiling leaves more
+// tiles than the fused kernels' group tables hold.
+void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
+  const dim3 blk(kBlock);
+  static const uint32_t resident = resident_blocks(k_accum_moments_fused, kBlock);
+  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  uint32_t want = resident < (uint32_t)kMaxMomentParts ? resident : (uint32_t)kMaxMomentParts;
+  if (want > nchunks) want = nchunks;
+  if (want > a.max_tiles) want = a.max_tiles;
+  if (want < 1) want = 1;
+  a.moment_parts = want;
+  if (tiles <= (uint32_t)kFusedMaxTiles) {
+    if (want >= resident && want > 1) a.moment_parts = --want;  // room for the extra workgroup
+    ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
+    ln.run("gk_count", k_gk_count_fused, dim3(tiles), blk, a);
     if (a.norms) {
-      ln.run("gk_compact", k_gk_compact_seg<true>, dim3(tiles), blk, a);
-      ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
+      ln.run("gk_compact", k_gk_compact_fused<true>, dim3(tiles), blk, a);
+      ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
     } else {
-      ln.run("gk_compact", k_gk_compact_seg<false>, dim3(tiles), blk, a);
+      ln.run("gk_compact", k_gk_compact_fused<false>, dim3(tiles), blk, a);
     }
     return;
   }
-  ln.run("gk_threshold", k_gk_threshold<SEG>, dim3(a.L), dim3(kFinBlock), a);
-  ln.run("gk_count", k_gk_count<SEG>, dim3(tiles), blk, a);
-  ln.run("gk_decide", k_gk_decide<SEG>, dim3(a.L), dim3(kFinBlock), a);
+  ln.run("accum_moments", k_accum_moments_flat, dim3(want), blk, a);
+  ln.run("gk_threshold", k_gk_threshold, dim3(1), dim3(kFinBlock), a);
+  ln.run("gk_count", k_gk_count, dim3(tiles), blk, a);
+  ln.run("gk_decide", k_gk_decide, dim3(1), dim3(kFinBlock), a);
   if (a.norms) {
-    ln.run("gk_compact", k_gk_compact<SEG, true>, dim3(tiles), blk, a);
-    ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+    ln.run("gk_compact", k_gk_compact<true>, dim3(tiles), blk, a);
+    ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
   } else {
-    ln.run("gk_compact", k_gk_compact<SEG, false>, dim3(tiles), blk, a);
+    ln.run("gk_compact", k_gk_compact<false>, dim3(tiles), blk, a);
   }
 }
 
@@ -266,6 +269,20 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
       ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
     } else {
       ln.run("topk_compact", k_topk_compact_ordered<false>, pg, blk, a);
+    }
+    return;
+  }
+  if (SEG && !a.inplace) {  // layer-wise with candidate filtering: see topk_seg.h
+    ln.run("topk_accum_hist", k_topk_accum_hist<true>, pg, blk, a);
+    ln.run("topk_filter", k_topk_filter_seg, pg, blk, a);
+    ln.run("topk_cand2", k_topk_cand_hist_seg, pg, blk, a, 2);
+    ln.run("topk_cand3", k_topk_cand_hist_seg, pg, blk, a, 3);
+    ln.run("topk_final", k_topk_cand_final_seg, pg, blk, a);
+    if (a.norms) {
+      ln.run("topk_compact", k_topk_compact_ordered_seg<true>, pg, blk, a);
+      ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
+    } else {
+      ln.run("topk_compact", k_topk_compact_ordered_seg<false>, pg, blk, a);
     }
     return;
   }
@@ -355,7 +372,7 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
   ln.begin();
   if (selector == kSelGaussian) {
-    launch_gaussiank<false>(ln, a, tiles);
+    launch_gaussiank_flat(ln, a, tiles);
   } else if (selector == kSelTopk) {
     launch_topk<false>(ln, a, tiles);
   } else {
@@ -423,9 +440,9 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   const uint32_t tiles = max_tiles_of(d_total, num_segments, a.tile_chunks);
   ln.run("seg_setup", k_seg_setup, dim3(1), dim3(kBlock), a, (int)mode);
   if (mode == 1) {
-    launch_gaussiank<true>(ln, a, tiles);
+    launch_gaussiank_seg(ln, a, tiles);
   } else {
-    const size_t n = (size_t)256 * (size_t)num_segments * a.hist_copies;
+    const size_t n = (size_t)kDigits * 256 * (size_t)num_segments * a.hist_copies;
     ln.run("hist_zero", k_fill_u32, dim3((unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024)),
            dim3(256), a.hist, n, 0u);
     launch_topk<true>(ln, a, tiles);

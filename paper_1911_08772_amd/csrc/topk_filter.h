@@ -208,16 +208,24 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final(const Args a) {
 }
 
 // ---- compaction in index order, residual write -------------------------------------------------
+// `out0`, `cap`: first slot and capacity of the output range; `none`: select nothing.
+struct OrderedSel {
+  uint32_t T, take;
+  bool rank_ties, none;
+  int64_t out0, cap;
+};
 template <bool FULL, bool NORMS>
-__device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, uint32_t T, uint32_t take,
-                                             bool rank_ties, uint32_t& out_run, uint32_t& tie_run,
+__device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, const OrderedSel& o,
+                                             uint32_t& out_run, uint32_t& tie_run,
                                              uint32_t* lds, NormAcc& norms) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+  const uint32_t T = o.T, take = o.take;
+  const bool rank_ties = o.rank_ties;
   uint32_t sel = 0, eq = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
-    if (FULL || ((valid >> i) & 1u)) {
+    if ((FULL || ((valid >> i) & 1u)) && !o.none) {
       const uint32_t key = mag_key(v[i]);
       sel |= ((key > T || (!rank_ties && key == T)) ? 1u : 0u) << i;
       eq |= ((rank_ties && key == T) ? 1u : 0u) << i;
@@ -249,9 +257,9 @@ __device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, uint3
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if ((sel >> (4 * j + q)) & 1u) {
-        if ((int64_t)r < a.flat_cap) {
-          a.out_idx[r] = (uint32_t)(i0 + q);
-          a.out_val[r] = v[4 * j + q];
+        if ((int64_t)r < o.cap) {
+          a.out_idx[o.out0 + r] = (uint32_t)(i0 + q);
+          a.out_val[o.out0 + r] = v[4 * j + q];
         }
         ++r;
       }
@@ -275,8 +283,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   Span sp_;
   if (!locate_span<false>(a, tile, &sp_)) return;
   const SegCtrl& c = a.ctrl[0];
-  const uint32_t T = c.topk_key, take = c.topk_take;
-  const bool rank_ties = c.rank_ties != 0;
+  const OrderedSel o = {c.topk_key, c.topk_take, c.rank_ties != 0, false, 0, a.flat_cap};
+  const uint32_t take = o.take;
+  const bool rank_ties = o.rank_ties;
   const uint32_t g = tile / kGroupTiles, g0 = g * kGroupTiles, within = tile - g0;
   if (wave_id() == 0) {  // survivors and ties before this tile: whole groups, then tiles of its own
     uint32_t x = 0, y = 0;
@@ -299,8 +308,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    if (t.full) ordered_compact_chunk<true, NORMS>(a, t, T, take, rank_ties, out_run, tie_run, lds, norms);
-    else ordered_compact_chunk<false, NORMS>(a, t, T, take, rank_ties, out_run, tie_run, lds, norms);
+    if (t.full) ordered_compact_chunk<true, NORMS>(a, t, o, out_run, tie_run, lds, norms);
+    else ordered_compact_chunk<false, NORMS>(a, t, o, out_run, tie_run, lds, norms);
   }
   if (NORMS) store_norm_partial(a, norms, tile, lds_n);
 }

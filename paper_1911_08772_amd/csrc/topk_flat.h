@@ -50,9 +50,11 @@ struct Digit {
   uint32_t prefix, k_rem, count;  // extended prefix, rank left inside the digit, keys in it
   uint32_t total;                 // keys counted by the histogram
 };
+__device__ inline Digit digit_from_bins(uint32_t v, int pass, uint32_t prefix, uint32_t k_rem,
+                                        uint32_t* lds);
+
 __device__ inline Digit choose_digit(const uint32_t* hist, int pass, uint32_t prefix,
                                      uint32_t k_rem, uint32_t* lds) {
-  const uint32_t nbins = 1u << digit_bits(pass);
   const uint32_t bin = 255u - threadIdx.x;
   uint32_t x[kTopkCopies];
 #pragma unroll
@@ -60,6 +62,29 @@ __device__ inline Digit choose_digit(const uint32_t* hist, int pass, uint32_t pr
   uint32_t v = 0;
 #pragma unroll
   for (int r = 0; r < kTopkCopies; ++r) v += x[r];
+  return digit_from_bins(v, pass, prefix, k_rem, lds);
+}
+
+// The same with a run-time number of replicas (layer-wise calls).
+__device__ inline Digit choose_digit_n(const uint32_t* hist, uint32_t copies, int pass,
+                                       uint32_t prefix, uint32_t k_rem, uint32_t* lds) {
+  const uint32_t bin = 255u - threadIdx.x;
+  uint32_t v = 0;
+  for (uint32_t r0 = 0; r0 < copies; r0 += 8) {
+    uint32_t x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = (r0 + u < copies) ? hist[(size_t)(r0 + u) * 256 + bin] : 0u;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v += x[u];
+  }
+  return digit_from_bins(v, pass, prefix, k_rem, lds);
+}
+
+// `v`: this thread's bin count (thread order = descending digit).
+__device__ inline Digit digit_from_bins(uint32_t v, int pass, uint32_t prefix, uint32_t k_rem,
+                                        uint32_t* lds) {
+  const uint32_t nbins = 1u << digit_bits(pass);
+  const uint32_t bin = 255u - threadIdx.x;
   if (bin >= nbins) v = 0;
   if (threadIdx.x == 0) {  // what is read back when the rank exceeds the total: nothing chosen
     lds[kWaves] = prefix << digit_bits(pass);

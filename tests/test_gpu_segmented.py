@@ -77,6 +77,27 @@ def test_ties_and_output_ranges_too_small(mode):
     assert res[0]["nnz"] > 0 and res[3]["nnz"] > 0
 
 
+@pytest.mark.parametrize("inplace", [False, True])
+def test_topk_ranked_ties_in_segments_of_many_tiles(inplace):
+    """Segments of 74, 171 and 65 tiles (several groups of 64 tiles each) filled with a handful
+    of values: the k-th key of a segment is shared by thousands of entries spread over all its
+    tiles, and only the lowest-index ones are kept."""
+    sizes = [300_000, 5, 700_001, 4096 * 64 + 1, 17]
+    rng = np.random.default_rng(8)
+    d = int(np.sum(sizes))
+    vecs = [rng.integers(-3, 4, d).astype(np.float32), np.full(d, 0.5, np.float32)]
+    late = np.zeros(d, np.float32)
+    late[300_005 + 690_000:300_005 + 700_001] = -1.0   # every tie of segment 2 in its last tiles
+    vecs.append(late)
+    for rho_den in (3, 1000):
+        seg_off, seg_k, caps = layout(sizes, rho_den=rho_den, cap_mult=1)
+        gpu = SegGpu(seg_off, seg_k, caps, inplace)
+        for n, g in enumerate(vecs):
+            eps = np.zeros(d, np.float32)
+            gpu.set_residual(eps)
+            check_segmented(0, gpu, g, eps, what=f"ties vec {n} rho 1/{rho_den} inplace={inplace}")
+
+
 def test_invalid_segments_are_flagged_and_produce_nothing():
     d = 10_000
     seg_off = np.array([0, 3000, 2000, 10_000], np.int64)   # segment 1 runs backwards
