@@ -1,10 +1,16 @@
 // Exact Top_k (Sec. 1 definition) by radix select over the bit pattern of |acc|: four digit
-// passes (8, 8, 8, 7 bits, most significant first) with per-wave histograms in LDS, a
-// per-segment digit choice after each pass, then compaction of {key > T} plus the lowest-index
-// ties.  Global atomics on one address cost tens of nanoseconds each on this chip, so the
-// global histogram is replicated and the output slots of the bulk of the survivors come from
-// a scan of per-tile counts; only the few survivors that share the k-th key's leading 24 bits
-// take their slots from an atomic cursor.
+// passes (8, 8, 8, 7 bits, most significant first) with per-wave histograms in LDS, a digit
+// choice after each pass, then compaction of {key > T} plus the lowest-index ties.  This file
+// holds the building blocks (digit layout, histogram flush, the accumulate kernel with the first
+// digit's histogram, tie counting, one chunk of the cursor-based compaction) and the general
+// twelve-launch form with one single-workgroup "select" kernel per segment after each pass; it
+// serves layer-wise calls in place and flat calls whose forced tiling exceeds the fused forms'
+// tables.  The forms normally used are in topk_filter.h (flat), topk_seg.h (layer-wise) and
+// topk_flat.h (flat, in place).
+// Global atomics on one address cost tens of nanoseconds each on this chip, so the global
+// histogram is replicated and the output slots of the bulk of the survivors come from a scan of
+// per-tile counts; only the few survivors that share the k-th key's leading 24 bits take their
+// slots from an atomic cursor.
 #pragma once
 #include "common.h"
 #include "gaussiank.h"

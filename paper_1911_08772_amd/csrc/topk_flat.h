@@ -1,9 +1,11 @@
-// Exact Top_k, flat vectors: seven launches instead of twelve.  The per-segment "select"
-// kernels of topk.h are latency-bound single workgroups that each cost a launch; here every
-// workgroup of the next pass chooses the digit itself from the replicated histogram of the
-// previous pass (same arithmetic, same inputs: all agree), each pass has its own histogram
-// buffer (cleared once by the init kernel), and every compact workgroup finds its output base
-// from per-group totals of the sure survivors.
+// Exact Top_k, flat vectors, accumulator aliased to the residual (in-place mode): seven launches
+// with three full digit passes.  (With a separate accumulator the candidate-filtering form of
+// topk_filter.h is used instead; it shares this file's initialisation and digit choice.)
+// The per-segment "select" kernels of topk.h are latency-bound single workgroups that each cost a
+// launch; here every workgroup of the next pass chooses the digit itself from the replicated
+// histogram of the previous pass (same arithmetic, same inputs: all agree), each pass has its own
+// histogram buffer (cleared once by the init kernel), and every compact workgroup finds its
+// output base from per-group totals of the sure survivors.
 //
 // Used when the vector has at most kFusedMaxTiles tiles (always, unless tile_chunks is forced).
 #pragma once
