@@ -28,7 +28,7 @@ def random_vector(rng, d, kind):
     return (rng.uniform(-1, 1, d) * (rng.uniform(0, 1, d) < 0.3)).astype(np.float32)
 
 
-@pytest.mark.parametrize("selector", ["gaussiank", "topk"])
+@pytest.mark.parametrize("selector", ["gaussiank", "topk", "dgck"])
 def test_flat_random_cases(selector):
     rng = np.random.default_rng(20261127)
     for case in range(120):
@@ -37,10 +37,13 @@ def test_flat_random_cases(selector):
         k = min(max(k, 1), d)
         g = random_vector(rng, d, int(rng.integers(0, 5)))
         eps = random_vector(rng, d, int(rng.integers(0, 5))) if rng.random() < 0.7 else np.zeros(d, np.float32)
-        inplace = bool(rng.random() < 0.4)
-        cap = d if selector == "topk" or rng.random() < 0.5 else int(rng.integers(1, d + 1))
-        cap = max(cap, k) if selector == "topk" else cap
+        inplace = bool(rng.random() < 0.4) and selector != "dgck"
+        cap = d if selector != "gaussiank" or rng.random() < 0.5 else int(rng.integers(1, d + 1))
+        cap = max(cap, k) if selector != "gaussiank" else cap
         kw = {"tile_chunks": int(rng.choice([0, 0, 1, 2, 3, 7]))}
+        if selector == "dgck":
+            kw["sample_stride"] = int(rng.choice([0, 1, 2, 10, 100, 333, 5000]))
+            kw["sample_seed"] = int(rng.integers(0, 1 << 62))
         if selector == "gaussiank":
             kw["tail_div"] = float(rng.choice([2.0, 2.0, 1.0, 3.5]))
             kw["ddof"] = int(rng.choice([1, 1, 0]))
@@ -103,7 +106,7 @@ def test_calibration_copy():
     assert S.sparsify_calibration_copy(dst, dst, n, check=False) == S.E_INVALID
 
 
-@pytest.mark.parametrize("selector", ["gaussiank", "topk"])
+@pytest.mark.parametrize("selector", ["gaussiank", "topk", "dgck"])
 def test_calls_can_be_captured_in_a_hip_graph(selector):
     """The library never synchronises, allocates or uses memset nodes, so a call can be captured
     once and replayed on new gradients; every replay is checked against the oracle chain, with
@@ -112,7 +115,7 @@ def test_calls_can_be_captured_in_a_hip_graph(selector):
     d, k, cap = wl.d, wl.k, 4 * wl.k
     b = S.Buffers.allocate(d, cap)
     grad = torch.zeros(d, device="cuda:0")
-    fn = S.sparsify_gaussiank if selector == "gaussiank" else S.sparsify_topk
+    fn = {"gaussiank": S.sparsify_gaussiank, "topk": S.sparsify_topk, "dgck": S.sparsify_dgck}[selector]
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):   # warm-up outside capture (first-call queries of the runtime)
@@ -134,7 +137,7 @@ def test_calls_can_be_captured_in_a_hip_graph(selector):
         torch.cuda.synchronize()
         acc_o = O.accumulate(g, eps)
         idx_o, val_o, eps, ro = (O.gaussiank(acc_o, k, cap=cap) if selector == "gaussiank"
-                                 else O.topk(acc_o, k))
+                                 else O.topk(acc_o, k) if selector == "topk" else O.dgck(acc_o, k))
         res = S.decode_results(b.result)[0]
         n = int(res["nnz"])
         assert n == ro.nnz
