@@ -123,7 +123,8 @@ int sparsify_topk(int64_t d, int64_t k, const float* grad, float* residual, floa
  * stratum's number), the rank ceil(k m / d) inside a sample of m, and ">=" are this library's
  * reading.  Same arguments as sparsify_topk; cap >= k is required; at most k pairs are written,
  * in ascending index order (fewer than k when the sample's threshold is too high: nothing is
- * added then).  acc == residual is not supported (SPARSIFY_E_INVALID).  result: see the fields'
+ * added then).  acc == residual is not supported, nor an opts->tile_chunks that leaves more than
+ * 4096 tiles (both SPARSIFY_E_INVALID).  result: see the fields'
  * comments; topk_key is the smallest magnitude that could be kept (bit pattern). */
 int sparsify_dgck(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
                   uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
