@@ -215,6 +215,8 @@ def main() -> int:
                  "elements_per_s": round(d / (tk_ms * 1e-3), 1),
                  "pct_hbm_peak": round(100.0 * tk_gbps / HBM_PEAK_GBPS, 2),
                  "bytes_per_elem": tk_bpe,
+                 # context only (Sec. 3.3: a tensor library's topk() on a Tesla V100, same d and k)
+                 "paper_v100_ms": 400.0 if (wl.d == 25_557_032 and k == 25_558) else None,
                  "kernel_ms": {n: round(v, 5) for n, v in tk_stage.items()}},
         "gaussiank_speedup_over_topk": round(tk_ms / gk_ms, 3),
         "dgck": dg,
