@@ -25,6 +25,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--pool", type=int, default=4, help="distinct gradients cycled through")
+    ap.add_argument("--tile-chunks", type=int, default=0, help="tuning: 4096-element chunks per workgroup")
     args = ap.parse_args()
 
     import numpy as np
@@ -59,7 +60,7 @@ def main() -> int:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
                 fn(d, k, grads[s % args.pool], b.residual, b.acc, b.out_idx, b.out_val, cap, b.result,
-                   b.workspace, b.workspace_nbytes, stream=stream)
+                   b.workspace, b.workspace_nbytes, stream=stream, tile_chunks=args.tile_chunks)
                 e1.record(stream)
                 torch.cuda.synchronize()
                 if s >= args.warmup:
