@@ -75,6 +75,8 @@ struct Args {
   SegCtrl* ctrl;
   uint32_t* tile_start;   // [L+1], segmented only
   double* partial;        // [3][max_tiles]: n, mean, M2
+  double* folded;         // [3][1024]: the same after a fold of the per-chunk partials (long vectors)
+  uint32_t use_folded;    // the count kernel reads `folded` (stride 1024) instead of `partial`
   uint32_t* tile_counts;  // [kNumThres][max_tiles]
   uint32_t* tile_base;    // [max_tiles]
   uint32_t* group_counts; // [64][kNumThres]: totals of groups of 64 tiles (fused flat path)
