@@ -211,6 +211,10 @@ uint32_t resident_blocks(K kernel, int block) {
   return (uint32_t)cus * (uint32_t)per_cu;
 }
 
+// Vectors of more chunks than this (82 M elements) use the chunk-per-workgroup accumulate: measured
+// even with the resident grid at 67 M elements, 2 % faster at 100 M, 9 % at 537 M.
+constexpr uint32_t kChunkGridFrom = 20000;
+
 // Layer-wise Gaussian_k: setup + three launches (gaussiank_seg.h).
 void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
@@ -226,9 +230,6 @@ void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
 
 // Flat Gaussian_k: three launches (gaussiank_flat.h); five when a forced tiling leaves more
 // tiles than the fused kernels' group tables hold.
-// Vectors of more chunks than this (82 M elements) use the chunk-per-workgroup accumulate: measured
-// even with the resident grid at 67 M elements, 2 % faster at 100 M, 9 % at 537 M.
-constexpr uint32_t kChunkGridFrom = 20000;
 void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   static const uint32_t resident = resident_blocks(k_accum_moments_fused, kBlock);
@@ -276,7 +277,9 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   if (!SEG && tiles <= (uint32_t)kFusedMaxTiles && !a.inplace) {  // see topk_filter.h
     const dim3 cg((tiles + kWaves - 1) / kWaves);  // one wave per tile's candidate list
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
-    ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
+    const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+    if (nchunks > kChunkGridFrom) ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks), blk, a);
+    else ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
     ln.run("topk_filter", k_topk_filter, pg, blk, a);
     ln.run("topk_cand2", k_topk_cand_hist, cg, blk, a, 2);
     ln.run("topk_cand3", k_topk_cand_hist, cg, blk, a, 3);
