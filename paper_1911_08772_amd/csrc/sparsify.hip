@@ -198,17 +198,13 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   return SPARSIFY_OK;
 }
 
-// Workgroups of `kernel` that fit on the device at once (cached per kernel; falls back to a
-// conservative figure if the runtime cannot tell).
-template <class K>
-uint32_t resident_blocks(K kernel, int block) {
-  int dev = 0, cus = 0, per_cu = 0;
+// Compute units of the current device (cached; a conservative figure if the runtime cannot tell).
+uint32_t compute_units() {
+  int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block, 0) != hipSuccess ||
-      cus < 1 || per_cu < 1)
-    return 1024;
-  return (uint32_t)cus * (uint32_t)per_cu;
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    return 256;
+  return (uint32_t)cus;
 }
 
 // Vectors of more chunks than this (82 M elements) use the chunk-per-workgroup accumulate: measured
@@ -232,9 +228,12 @@ void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
 // tiles than the fused kernels' group tables hold.
 void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
-  static const uint32_t resident = resident_blocks(k_accum_moments_fused, kBlock);
+  // The streaming grid of the accumulate kernel: one workgroup per compute unit (measured on 256
+  // CUs: 256 workgroups beat 512 and 1024 by about 1.5 % end to end, and the count kernel's
+  // prologue has fewer partials to merge; 128 or 384 are clearly worse).
+  static const uint32_t cus = compute_units();
   const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
-  uint32_t want = resident < (uint32_t)kMaxMomentParts ? resident : (uint32_t)kMaxMomentParts;
+  uint32_t want = cus < (uint32_t)kMaxMomentParts ? cus : (uint32_t)kMaxMomentParts;
   if (want > nchunks) want = nchunks;
   if (want > a.max_tiles) want = a.max_tiles;
   if (want < 1) want = 1;
@@ -246,7 +245,6 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
       ln.run("accum_moments", k_accum_moments_chunks, dim3(nchunks + 1), blk, a);
       ln.run("fold_moments", k_fold_moments, dim3(a.moment_parts), blk, a);
     } else {
-      if (want >= resident && want > 1) a.moment_parts = --want;  // room for the extra workgroup
       ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
     }
     ln.run("gk_count", k_gk_count_fused, dim3(tiles), blk, a);
@@ -278,8 +276,12 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
     const dim3 cg((tiles + kWaves - 1) / kWaves);  // one wave per tile's candidate list
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
     const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
-    if (nchunks > kChunkGridFrom) ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks), blk, a);
-    else ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
+    if (nchunks > kChunkGridFrom) {
+      ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks), blk, a);
+    } else {
+      static const uint32_t cus = compute_units();
+      ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
+    }
     ln.run("topk_filter", k_topk_filter, pg, blk, a);
     ln.run("topk_cand2", k_topk_cand_hist, cg, blk, a, 2);
     ln.run("topk_cand3", k_topk_cand_hist, cg, blk, a, 3);
@@ -308,7 +310,11 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   }
   if (!SEG && tiles <= (uint32_t)kFusedMaxTiles) {  // seven launches: see topk_flat.h
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
-    ln.run("topk_accum_hist", k_topk_accum_hist<false>, pg, blk, a);
+    {
+      static const uint32_t cus = compute_units();
+      const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+      ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
+    }
     ln.run("topk_hist1", k_topk_hist_fused<false>, pg, blk, a, 1);
     ln.run("topk_hist2", k_topk_hist_fused<false>, pg, blk, a, 2);
     ln.run("topk_hist3", k_topk_hist_fused<true>, pg, blk, a, 3);

@@ -38,6 +38,33 @@ __device__ inline uint32_t* tile_candidates(const Args& a, uint32_t tile) {
   return reinterpret_cast<uint32_t*>(a.resid) + (int64_t)tile * a.tile_chunks * kChunk;
 }
 
+// ---- accumulate, flat vectors -------------------------------------------------------------------
+// A resident grid (one workgroup per compute unit) walks the chunks with a grid stride and
+// flushes its histogram once: the same shape as the Gaussian_k accumulate kernel.
+__global__ __launch_bounds__(kBlock) void k_topk_accum_hist_resident(const Args a) {
+  __shared__ uint32_t h[kWaves][256];
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  for (uint32_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+    Tile t;
+    t.seg = 0;
+    t.tbase = (int64_t)ch * kChunk;
+    t.lo = t.tbase;
+    t.hi = (t.tbase + kChunk < a.d_total) ? t.tbase + kChunk : a.d_total;
+    t.full = t.tbase + kChunk <= a.d_total;
+    if (t.full) accum_hist_tile<true>(a, t, h[wave_id()]);
+    else accum_hist_tile<false>(a, t, h[wave_id()]);
+  }
+  __syncthreads();
+  const int bin = threadIdx.x;
+  uint32_t v = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) v += h[w][bin];
+  if (v) atomicAdd(&pass_hist(a, 0)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+}
+
 // ---- accumulate for long vectors ---------------------------------------------------------------
 // One chunk per workgroup in dispatch order (see k_accum_moments_chunks): beyond the last-level
 // cache this streams faster than one multi-chunk tile per workgroup.  The histogram flush then
