@@ -98,6 +98,26 @@ def test_topk_ranked_ties_in_segments_of_many_tiles(inplace):
             check_segmented(0, gpu, g, eps, what=f"ties vec {n} rho 1/{rho_den} inplace={inplace}")
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+def test_twenty_thousand_tiny_segments(mode):
+    """Many more segments than tiles of any one of them: sizes 1..120, k_l from 1 to the whole
+    segment, a few output ranges too small."""
+    rng = np.random.default_rng(31 + mode)
+    L = 20_000
+    sizes = rng.integers(1, 121, L).astype(np.int64)
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    seg_k = np.minimum(sizes, np.maximum(1, (sizes * rng.uniform(0, 1, L)).astype(np.int64)))
+    caps = np.where(rng.random(L) < 0.05, 0, 2 * sizes + 2).astype(np.int64)
+    d = int(seg_off[-1])
+    g = (rng.standard_normal(d) * 10.0 ** rng.integers(-4, 2, d)).astype(np.float32)
+    g[rng.integers(0, d, d // 20)] = 0.5     # ties
+    eps = np.zeros(d, np.float32)
+    gpu = SegGpu(seg_off, seg_k, caps)
+    for step in range(2):
+        gpu.set_residual(eps)
+        eps = check_segmented(mode, gpu, g, eps, what=f"20000 segments mode {mode} step {step}")
+
+
 def test_invalid_segments_are_flagged_and_produce_nothing():
     d = 10_000
     seg_off = np.array([0, 3000, 2000, 10_000], np.int64)   # segment 1 runs backwards
