@@ -225,6 +225,28 @@ __device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t* lds, uint3
   return before + inc - v;
 }
 
+// Histogram increments in LDS.  Atomics of one wave instruction that name the same LDS address
+// are performed one after the other, so data that puts every element into one bin (an all-zero
+// or constant vector: a frozen layer, say) would make the digit passes several times slower.
+// When all active lanes name the same bin, one lane adds the lot.
+__device__ inline void wave_hist_add(uint32_t* h, uint32_t bin, bool active) {
+  const uint64_t act = __ballot(active);
+  if (act == 0) return;
+  const int first = (int)__builtin_ctzll(act);
+  const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, first);
+  if (__ballot(active && bin == b0) == act) {
+    if (lane_id() == first) atomicAdd(&h[b0], (uint32_t)__builtin_popcountll(act));
+  } else if (active) {
+    atomicAdd(&h[bin], 1u);
+  }
+}
+// Cheap guess, once per chunk, whether the careful forms above are worth their instructions:
+// true when the 64 lanes' first elements all fall into one bin (practically never on
+// bell-shaped data, always on constant data).
+__device__ inline bool wave_bins_look_uniform(uint32_t bin) {
+  return __ballot(bin == (uint32_t)__builtin_amdgcn_readfirstlane((int)bin)) == ~0ull;
+}
+
 // Workgroups of the per-segment finalising kernels: one block per segment reads thousands of
 // per-tile partials that other XCDs wrote, so every load pays a full trip to memory; they use
 // 1024 threads and issue their loads in unrolled batches to pay that latency once.

@@ -100,8 +100,8 @@ __global__ __launch_bounds__(kBlock) void k_dgck_lists_hist(const Args a, int st
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
   uint32_t* hw = h[wave_id()];
-  for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key) {
-    if ((key >> hi_shift) == dg.prefix) atomicAdd(&hw[(key >> shift) & mask], 1u);
+  for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key, bool valid) {
+    wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
   });
   __syncthreads();
   const int bin = threadIdx.x;
@@ -128,6 +128,16 @@ __device__ inline void dgck_filter_chunk(const Args& a, const Tile& t, uint32_t 
   if (lane_id() == 63) base = atomicAdd(lds_cursor, inc);
   base = __shfl(base, 63, 64);
   uint32_t pos = base + inc - n;
+  if (wave_bins_look_uniform(cmask == 0xFFFFu ? mag_key(v[0]) >> 23 : 256u + lane_id())) {
+    // everything kept and the first elements share a bin: constant data, aggregate
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const uint32_t key = mag_key(v[i]);
+      list[pos++] = key;
+      wave_hist_add(h, key >> 23, true);
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
     if ((cmask >> i) & 1u) {
@@ -214,9 +224,9 @@ __global__ __launch_bounds__(kBlock) void k_dgck_final(const Args a) {
   }
   const uint32_t tile = blockIdx.x * kWaves + wave_id();
   uint32_t gt = 0, eq = 0;
-  for_each_candidate(a, tile, ntiles, [&](uint32_t key) {
-    gt += key > T ? 1u : 0u;
-    eq += key == T ? 1u : 0u;
+  for_each_candidate(a, tile, ntiles, [&](uint32_t key, bool valid) {
+    gt += (valid && key > T) ? 1u : 0u;
+    eq += (valid && key == T) ? 1u : 0u;
   });
   gt = wave_sum(gt);
   eq = wave_sum(eq);

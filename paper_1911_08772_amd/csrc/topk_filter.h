@@ -116,12 +116,23 @@ __device__ inline uint32_t filter_chunk(const Args& a, const Tile& t, uint32_t E
     if (lane_id() == 63) base = atomicAdd(lds_cursor, wave_total);  // LDS: one per wave and chunk
     base = __shfl(base, 63, 64);
     uint32_t pos = base + inc - n;
+    if (wave_bins_look_uniform(cmask == 0xFFFFu ? (mag_key(v[0]) >> 15) & 255u : 256u + lane_id())) {
+      // every element of the wave's chunk is a candidate and the first ones share a bin:
+      // constant data, aggregate the histogram increments
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-      if ((cmask >> i) & 1u) {
+      for (int i = 0; i < kPerThread; ++i) {
         const uint32_t key = mag_key(v[i]);
         cand[pos++] = key;
-        atomicAdd(&h[(key >> 15) & 255u], 1u);
+        wave_hist_add(h, (key >> 15) & 255u, true);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < kPerThread; ++i) {
+        if ((cmask >> i) & 1u) {
+          const uint32_t key = mag_key(v[i]);
+          cand[pos++] = key;
+          atomicAdd(&h[(key >> 15) & 255u], 1u);
+        }
       }
     }
   }
@@ -173,7 +184,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_filter(const Args a) {
 
 // ---- digit passes 2 and 3 over the candidates -------------------------------------------------
 // One wave per tile's candidate list (a few hundred keys as a rule), four lists per workgroup.
-// `fn(key)` is called for every candidate of the wave's tile.
+// `fn(key, valid)` is called by the whole wave for every 64 candidates of its tile (`valid` false in
+// the lanes past the end of the list).
 constexpr int kCandBatch = 4;
 template <typename F>
 __device__ inline void for_each_candidate(const Args& a, uint32_t tile, uint32_t ntiles, F fn) {
@@ -189,7 +201,7 @@ __device__ inline void for_each_candidate(const Args& a, uint32_t tile, uint32_t
     }
 #pragma unroll
     for (int u = 0; u < kCandBatch; ++u)
-      if (i0 + u * 64 + lane_id() < n) fn(key[u]);
+      if (i0 + u * 64 < n) fn(key[u], i0 + u * 64 + lane_id() < n);  // wave-uniform condition
   }
 }
 
@@ -210,8 +222,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const Args a, int pas
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
   uint32_t* hw = h[wave_id()];
-  for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key) {
-    if ((key >> hi_shift) == dg.prefix) atomicAdd(&hw[(key >> shift) & mask], 1u);
+  for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key, bool valid) {
+    wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
   });
   __syncthreads();
   const int bin = threadIdx.x;
@@ -242,9 +254,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final(const Args a) {
   const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
   const uint32_t tile = blockIdx.x * kWaves + wave_id();
   uint32_t gt = 0, eq = 0;
-  for_each_candidate(a, tile, ntiles, [&](uint32_t key) {
-    gt += key > T ? 1u : 0u;
-    eq += key == T ? 1u : 0u;
+  for_each_candidate(a, tile, ntiles, [&](uint32_t key, bool valid) {
+    gt += (valid && key > T) ? 1u : 0u;
+    eq += (valid && key == T) ? 1u : 0u;
   });
   gt = wave_sum(gt);
   eq = wave_sum(eq);

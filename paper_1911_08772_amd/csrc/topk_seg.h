@@ -88,9 +88,10 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist_seg(const Args a, int
   const uint32_t n = tile_row(a, kRowCand)[tile];
   const uint32_t* cand = span_candidates(a, sp_);
   uint32_t* hw = h[wave_id()];
-  for (uint32_t i = threadIdx.x; i < n; i += kBlock) {
-    const uint32_t key = cand[i];
-    if ((key >> hi_shift) == dg.prefix) atomicAdd(&hw[(key >> shift) & mask], 1u);
+  for (uint32_t i0 = 0; i0 < n; i0 += kBlock) {  // block-uniform trip count
+    const uint32_t i = i0 + threadIdx.x;
+    const uint32_t key = i < n ? cand[i] : 0u;
+    wave_hist_add(hw, (key >> shift) & mask, i < n && (key >> hi_shift) == dg.prefix);
   }
   __syncthreads();
   flush_seg_hist(a, pass, sp_.seg, h);
