@@ -258,17 +258,25 @@ constexpr int kFinWaves = kFinBlock / 64;
 // thread's first flagged element of slot j; returns the number flagged in the whole tile.
 // One barrier; `lds` must hold kSlots * kWaves words and may be reused after the next barrier.
 __device__ inline uint32_t tile_rank(uint32_t sel, uint32_t* lds, uint32_t (&first)[kSlots]) {
+  if (__ballot(sel != 0) == 0) {  // wave-uniform: nothing flagged in this wave's 1024 elements
 #pragma unroll
-  for (int j = 0; j < kSlots; ++j) {
-    uint32_t tot = 0, mine = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const uint64_t m = __ballot((sel >> (4 * j + q)) & 1u);
-      tot += (uint32_t)__builtin_popcountll(m);
-      mine += lanes_below(m);
+    for (int j = 0; j < kSlots; ++j) {
+      first[j] = 0;
+      if (lane_id() == 0) lds[j * kWaves + wave_id()] = 0;
     }
-    first[j] = mine;
-    if (lane_id() == 0) lds[j * kWaves + wave_id()] = tot;
+  } else {
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+      uint32_t tot = 0, mine = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint64_t m = __ballot((sel >> (4 * j + q)) & 1u);
+        tot += (uint32_t)__builtin_popcountll(m);
+        mine += lanes_below(m);
+      }
+      first[j] = mine;
+      if (lane_id() == 0) lds[j * kWaves + wave_id()] = tot;
+    }
   }
   __syncthreads();
   uint32_t run = 0;
