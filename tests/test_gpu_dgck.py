@@ -80,3 +80,14 @@ def test_cfg3_headline_size_two_steps():
     for step in range(2):
         wl.grad(step, out=g)
         eps = check_flat("dgck", gpu, g, eps, wl.k, what=f"cfg3 dgck step {step}", sample_seed=step)
+
+
+def test_cfg2_chain_of_five_steps():
+    """VGG-16-sized mixture workload: the residual grows heavy-tailed over the steps."""
+    wl = synth.workload("cfg2_vgg16")
+    gpu = FlatGpu(wl.d, cap=4 * wl.k)
+    eps = np.zeros(wl.d, np.float32)
+    g = np.empty(wl.d, np.float32)
+    for step in range(5):
+        wl.grad(step, out=g)
+        eps = check_flat("dgck", gpu, g, eps, wl.k, what=f"cfg2 dgck step {step}", sample_seed=100 + step)

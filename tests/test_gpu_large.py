@@ -14,7 +14,7 @@ from paper_1911_08772_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("selector", ["gaussiank", "topk"])
+@pytest.mark.parametrize("selector", ["gaussiank", "topk", "dgck"])
 def test_134m_elements_against_oracle(selector):
     d = (1 << 27) + 3
     k = synth.k_of(d, 1000)
