@@ -16,6 +16,12 @@ namespace sp {
 constexpr int kGroupTiles = 64;                                   // tiles per group
 constexpr int kFusedMaxTiles = 4096;
 constexpr int kMaxGroups = kFusedMaxTiles / kGroupTiles;          // 64
+// Long vectors (Gaussian_k): groups of kBigGroupTiles tiles, up to kBigMaxTiles tiles, so that a
+// tile can stay three chunks long (with tiles of tens of chunks, thousands of workgroups stream
+// from places hundreds of kilobytes apart and the memory system slows down).
+constexpr int kBigGroupTiles = 256;
+constexpr int kBigMaxGroups = 256;
+constexpr int kBigMaxTiles = kBigGroupTiles * kBigMaxGroups;     // 65536
 constexpr int kMaxMomentParts = 1024;                             // accumulate workgroups at most
 
 // K1: the accumulate kernel of gaussiank.h (k_accum_moments_flat) on `moment_parts` workgroups,
@@ -55,7 +61,7 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_chunks(const Args a) {
   __shared__ double lds[4 * kWaves];
   const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
   if (blockIdx.x == nchunks) {  // the extra workgroup: see k_accum_moments_fused
-    for (uint32_t i = threadIdx.x; i < (uint32_t)(kMaxGroups * kNumThres); i += kBlock)
+    for (uint32_t i = threadIdx.x; i < (uint32_t)(kBigMaxGroups * kNumThres); i += kBlock)
       a.group_counts[i] = 0;
     if (threadIdx.x == 0)
       a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
@@ -122,6 +128,7 @@ __global__ __launch_bounds__(kBlock) void k_fold_moments(const Args a) {
 // K3: thresholds from the moment partials (every workgroup), then the ten counts of its tile.
 // One pass over the partials around the provisional centre P = mean of partial 0:
 //   A = sum n_i (mean_i - P), B = sum M2_i + n_i (mean_i - P)^2, mean = P + A/N, M2 = B - A^2/N.
+template <int GT>  // tiles per group
 __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
   __shared__ double lds_m[2 * kWaves];
   __shared__ uint32_t lds[kWaves * kNumThres];
@@ -213,16 +220,16 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) s += lds[w * kNumThres + threadIdx.x];
     a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile] = s;  // [threshold][tile]
-    if (s) atomicAdd(&a.group_counts[(tile / kGroupTiles) * kNumThres + threadIdx.x], s);
+    if (s) atomicAdd(&a.group_counts[(tile / GT) * kNumThres + threadIdx.x], s);
   }
 }
 
 // K5: every workgroup totals the group counts, walks Alg. 1 steps 5-13, finds the first output
 // slot of its tile (groups before its own + tiles before it inside its group), then compacts.
-template <bool NORMS>
+template <bool NORMS, int GT, int MG>  // tiles per group, groups at most
 __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
-  __shared__ uint32_t lds_g[kMaxGroups * kNumThres];    // group totals [group][threshold]
-  __shared__ uint32_t lds_t[kGroupTiles * kNumThres];   // counts of my group's tiles [threshold][tile]
+  __shared__ uint32_t lds_g[MG * kNumThres];    // group totals [group][threshold]
+  __shared__ uint32_t lds_t[GT * kNumThres];    // counts of my group's tiles [threshold][tile]
   __shared__ uint32_t lds_tot[kNumThres];
   __shared__ uint32_t lds_base;
   __shared__ uint32_t lds[kSlots * kWaves];
@@ -232,12 +239,12 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   if (!locate_span<false>(a, tile, &sp_)) return;
   SegCtrl& c = a.ctrl[0];
   const uint32_t ntiles = gridDim.x;
-  const uint32_t ngroups = (ntiles + kGroupTiles - 1) / kGroupTiles;
-  const uint32_t g = tile / kGroupTiles, g0 = g * kGroupTiles, within = tile - g0;
+  const uint32_t ngroups = (ntiles + GT - 1) / GT;
+  const uint32_t g = tile / GT, g0 = g * GT, within = tile - g0;
 
   for (uint32_t i = threadIdx.x; i < ngroups * kNumThres; i += kBlock) lds_g[i] = a.group_counts[i];
-  for (uint32_t i = threadIdx.x; i < (uint32_t)(kGroupTiles * kNumThres); i += kBlock) {
-    const uint32_t p = i / kGroupTiles, j = i % kGroupTiles;
+  for (uint32_t i = threadIdx.x; i < (uint32_t)(GT * kNumThres); i += kBlock) {
+    const uint32_t p = i / GT, j = i % GT;
     lds_t[i] = (j < within) ? a.tile_counts[(size_t)p * a.max_tiles + g0 + j] : 0u;
   }
   double t64[kNumThres];
@@ -258,8 +265,11 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   const bool overflow = (int64_t)tot[w.pos] > a.flat_cap;
   if (wave_id() == 0) {
     uint32_t x = 0;
-    if ((uint32_t)lane_id() < g) x += lds_g[lane_id() * kNumThres + w.pos];      // kMaxGroups == 64 lanes
-    x += lds_t[w.pos * kGroupTiles + lane_id()];                                  // kGroupTiles == 64 lanes
+#pragma unroll
+    for (int j = 0; j < MG; j += 64)
+      if ((uint32_t)(j + lane_id()) < g) x += lds_g[(j + lane_id()) * kNumThres + w.pos];
+#pragma unroll
+    for (int j = 0; j < GT; j += 64) x += lds_t[w.pos * GT + j + lane_id()];  // zero from `within` on
     x = wave_sum(x);
     if (lane_id() == 0) lds_base = x;
   }
@@ -296,6 +306,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   if (NORMS) store_norm_partial(a, norms, tile, lds_n);
 }
 
-static_assert(kMaxGroups == 64 && kGroupTiles == 64, "one lane per group and per tile of a group");
+static_assert(kMaxGroups % 64 == 0 && kGroupTiles % 64 == 0 && kBigMaxGroups % 64 == 0 &&
+              kBigGroupTiles % 64 == 0, "whole waves of lanes walk the groups and a group's tiles");
 
 }  // namespace sp

@@ -104,7 +104,7 @@ Carve carve(int64_t d_total, int32_t L) {
   c.tile_counts = off; off = align_up(off + sizeof(uint32_t) * kNumThres * mt);
   c.tile_base = off;   off = align_up(off + sizeof(uint32_t) * mt);
   c.tie_base = off;    off = align_up(off + sizeof(uint32_t) * mt);
-  c.group_counts = off; off = align_up(off + sizeof(uint32_t) * kMaxGroups * kNumThres);
+  c.group_counts = off; off = align_up(off + sizeof(uint32_t) * kBigMaxGroups * kNumThres);
   // a segment's tiles are totalled in groups of 64 of its own: at most tiles/64 + one per segment
   c.max_groups = (uint32_t)(mt / kGroupTiles + (size_t)L + 1);
   c.seg_groups = off;  off = align_up(off + sizeof(uint32_t) * kNumThres * (size_t)c.max_groups);
@@ -238,21 +238,30 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   if (want > a.max_tiles) want = a.max_tiles;
   if (want < 1) want = 1;
   a.moment_parts = want;
-  if (tiles <= (uint32_t)kFusedMaxTiles) {
-    if (nchunks > kChunkGridFrom) {  // long vector: one chunk per workgroup, then a fold
-      a.moment_parts = nchunks < (uint32_t)kMaxMomentParts ? nchunks : (uint32_t)kMaxMomentParts;
-      a.use_folded = 1;
-      ln.run("accum_moments", k_accum_moments_chunks, dim3(nchunks + 1), blk, a);
-      ln.run("fold_moments", k_fold_moments, dim3(a.moment_parts), blk, a);
-    } else {
-      ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
-    }
-    ln.run("gk_count", k_gk_count_fused, dim3(tiles), blk, a);
+  if (nchunks > kChunkGridFrom && tiles <= (uint32_t)kBigMaxTiles) {
+    // long vector: one chunk per workgroup and a fold of the partials, then short tiles in
+    // groups of kBigGroupTiles
+    a.moment_parts = nchunks < (uint32_t)kMaxMomentParts ? nchunks : (uint32_t)kMaxMomentParts;
+    a.use_folded = 1;
+    ln.run("accum_moments", k_accum_moments_chunks, dim3(nchunks + 1), blk, a);
+    ln.run("fold_moments", k_fold_moments, dim3(a.moment_parts), blk, a);
+    ln.run("gk_count", k_gk_count_fused<kBigGroupTiles>, dim3(tiles), blk, a);
     if (a.norms) {
-      ln.run("gk_compact", k_gk_compact_fused<true>, dim3(tiles), blk, a);
+      ln.run("gk_compact", k_gk_compact_fused<true, kBigGroupTiles, kBigMaxGroups>, dim3(tiles), blk, a);
       ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
     } else {
-      ln.run("gk_compact", k_gk_compact_fused<false>, dim3(tiles), blk, a);
+      ln.run("gk_compact", k_gk_compact_fused<false, kBigGroupTiles, kBigMaxGroups>, dim3(tiles), blk, a);
+    }
+    return;
+  }
+  if (nchunks <= kChunkGridFrom && tiles <= (uint32_t)kFusedMaxTiles) {
+    ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
+    ln.run("gk_count", k_gk_count_fused<kGroupTiles>, dim3(tiles), blk, a);
+    if (a.norms) {
+      ln.run("gk_compact", k_gk_compact_fused<true, kGroupTiles, kMaxGroups>, dim3(tiles), blk, a);
+      ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
+    } else {
+      ln.run("gk_compact", k_gk_compact_fused<false, kGroupTiles, kMaxGroups>, dim3(tiles), blk, a);
     }
     return;
   }
@@ -381,6 +390,15 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
+  if (selector == kSelGaussian && !(opts && opts->tile_chunks != 0)) {
+    // long vectors: three chunks per tile as long as the larger group tables hold the tiles
+    const int64_t chunks = (d + kChunk - 1) / kChunk;
+    if (chunks > (int64_t)kChunkGridFrom) {
+      uint32_t c = 3;
+      while ((chunks + c - 1) / c > (int64_t)kBigMaxTiles) c += 2;
+      a.tile_chunks = c;
+    }
+  }
   const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
   if (selector == kSelDgc) {
     // the per-tile key lists live in the residual buffer and the list kernels use one lane per
