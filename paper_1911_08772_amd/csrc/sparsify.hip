@@ -207,9 +207,10 @@ uint32_t compute_units() {
   return (uint32_t)cus;
 }
 
-// Vectors of more chunks than this (164 M elements) use the chunk-per-workgroup accumulate:
-// measured even with the resident grid at 134 M elements, 4 % faster at 268 M, 6 % at 537 M.
-constexpr uint32_t kChunkGridFrom = 40000;
+// Vectors of more chunks than this (123 M elements) use the chunk-per-workgroup accumulate and,
+// for Gaussian_k, the larger group tables: measured 3 % slower than the resident form at 67 M and
+// 100 M elements, 2 % faster at 134 M, 5 % at 268 M and 537 M.
+constexpr uint32_t kChunkGridFrom = 30000;
 
 // Layer-wise Gaussian_k: setup + three launches (gaussiank_seg.h).
 void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
