@@ -282,40 +282,33 @@ template <bool SEG>
 void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   const dim3 pg(tiles);
-  if (!SEG && tiles <= (uint32_t)kFusedMaxTiles && !a.inplace) {  // see topk_filter.h
-    const dim3 cg((tiles + kWaves - 1) / kWaves);  // one wave per tile's candidate list
+  const uint32_t nchunks_flat = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  const bool big = nchunks_flat > kChunkGridFrom;  // long vector: larger group tables
+  if (!SEG && !a.inplace && tiles <= (uint32_t)(big ? kBigMaxTiles : kFusedMaxTiles)) {  // see topk_filter.h
+    // one wave per tile's candidate list, several lists per wave when there are many tiles
+    uint32_t lists = (tiles + kWaves - 1) / kWaves;
+    if (lists > 4096) lists = 4096;
+    const dim3 cg(lists);
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
-    const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
-    if (nchunks > kChunkGridFrom) {
-      ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks), blk, a);
+    if (big) {
+      ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks_flat), blk, a);
     } else {
       static const uint32_t cus = compute_units();
-      ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
+      ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks_flat ? cus : nchunks_flat), blk, a);
     }
     ln.run("topk_filter", k_topk_filter, pg, blk, a);
     ln.run("topk_cand2", k_topk_cand_hist, cg, blk, a, 2);
     ln.run("topk_cand3", k_topk_cand_hist, cg, blk, a, 3);
-    ln.run("topk_final", k_topk_cand_final, cg, blk, a);
-    if (a.norms) {
-      ln.run("topk_compact", k_topk_compact_ordered<true>, pg, blk, a);
-      ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+    if (big) {
+      ln.run("topk_final", k_topk_cand_final<kBigGroupTiles>, cg, blk, a);
+      if (a.norms) ln.run("topk_compact", k_topk_compact_ordered<true, kBigGroupTiles, kBigMaxGroups>, pg, blk, a);
+      else ln.run("topk_compact", k_topk_compact_ordered<false, kBigGroupTiles, kBigMaxGroups>, pg, blk, a);
     } else {
-      ln.run("topk_compact", k_topk_compact_ordered<false>, pg, blk, a);
+      ln.run("topk_final", k_topk_cand_final<kGroupTiles>, cg, blk, a);
+      if (a.norms) ln.run("topk_compact", k_topk_compact_ordered<true, kGroupTiles, kMaxGroups>, pg, blk, a);
+      else ln.run("topk_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups>, pg, blk, a);
     }
-    return;
-  }
-  if (SEG && !a.inplace) {  // layer-wise with candidate filtering: see topk_seg.h
-    ln.run("topk_accum_hist", k_topk_accum_hist<true>, pg, blk, a);
-    ln.run("topk_filter", k_topk_filter_seg, pg, blk, a);
-    ln.run("topk_cand2", k_topk_cand_hist_seg, pg, blk, a, 2);
-    ln.run("topk_cand3", k_topk_cand_hist_seg, pg, blk, a, 3);
-    ln.run("topk_final", k_topk_cand_final_seg, pg, blk, a);
-    if (a.norms) {
-      ln.run("topk_compact", k_topk_compact_ordered_seg<true>, pg, blk, a);
-      ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
-    } else {
-      ln.run("topk_compact", k_topk_compact_ordered_seg<false>, pg, blk, a);
-    }
+    if (a.norms) ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
     return;
   }
   if (!SEG && tiles <= (uint32_t)kFusedMaxTiles) {  // seven launches: see topk_flat.h
@@ -371,10 +364,10 @@ void launch_dgck(Launcher& ln, const Args& a, uint32_t tiles) {
   ln.run("dgck_kept3", k_dgck_lists_hist, cg, blk, a, 7);
   ln.run("dgck_final", k_dgck_final, cg, blk, a);
   if (a.norms) {
-    ln.run("dgck_compact", k_topk_compact_ordered<true>, pg, blk, a);
+    ln.run("dgck_compact", k_topk_compact_ordered<true, kGroupTiles, kMaxGroups>, pg, blk, a);
     ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
   } else {
-    ln.run("dgck_compact", k_topk_compact_ordered<false>, pg, blk, a);
+    ln.run("dgck_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups>, pg, blk, a);
   }
 }
 
@@ -391,7 +384,8 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
-  if (selector == kSelGaussian && !(opts && opts->tile_chunks != 0)) {
+  if ((selector == kSelGaussian || (selector == kSelTopk && !a.inplace)) &&
+      !(opts && opts->tile_chunks != 0)) {
     // long vectors: three chunks per tile as long as the larger group tables hold the tiles
     const int64_t chunks = (d + kChunk - 1) / kChunk;
     if (chunks > (int64_t)kChunkGridFrom) {

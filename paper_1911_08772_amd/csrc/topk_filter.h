@@ -222,9 +222,12 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const Args a, int pas
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
   uint32_t* hw = h[wave_id()];
-  for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key, bool valid) {
-    wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
-  });
+  // one wave per list; with more lists than waves in the grid a wave takes several
+  for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
+    for_each_candidate(a, tile, ntiles, [&](uint32_t key, bool valid) {
+      wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
+    });
+  }
   __syncthreads();
   const int bin = threadIdx.x;
   uint32_t v = 0;
@@ -236,6 +239,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const Args a, int pas
 // After the last digit: T, the ties to keep, whether they must be ranked; per tile, the number of
 // survivors (keys above T; keys equal to T as well when all of them are kept) and, when ties are
 // ranked, the number of keys equal to T.
+template <int GT>  // tiles per group
 __global__ __launch_bounds__(kBlock) void k_topk_cand_final(const Args a) {
   __shared__ uint32_t lds_sel[kWaves + 3];
   SegCtrl& c = a.ctrl[0];
@@ -252,22 +256,23 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final(const Args a) {
     r.topk_ties_taken = dg.k_rem;
   }
   const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
-  const uint32_t tile = blockIdx.x * kWaves + wave_id();
-  uint32_t gt = 0, eq = 0;
-  for_each_candidate(a, tile, ntiles, [&](uint32_t key, bool valid) {
-    gt += (valid && key > T) ? 1u : 0u;
-    eq += (valid && key == T) ? 1u : 0u;
-  });
-  gt = wave_sum(gt);
-  eq = wave_sum(eq);
-  if (tile < ntiles && lane_id() == 0) {
-    const uint32_t taken = tile_row(a, kRowAbove)[tile] + gt + (rank_ties ? 0u : eq);
-    tile_row(a, kRowTake)[tile] = taken;
-    uint32_t* grp = a.group_counts + (tile / kGroupTiles) * kNumThres;
-    if (taken) atomicAdd(&grp[kColTake], taken);
-    if (rank_ties) {
-      tile_row(a, kRowTies)[tile] = eq;
-      if (eq) atomicAdd(&grp[kColTies], eq);
+  for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
+    uint32_t gt = 0, eq = 0;
+    for_each_candidate(a, tile, ntiles, [&](uint32_t key, bool valid) {
+      gt += (valid && key > T) ? 1u : 0u;
+      eq += (valid && key == T) ? 1u : 0u;
+    });
+    gt = wave_sum(gt);
+    eq = wave_sum(eq);
+    if (lane_id() == 0) {
+      const uint32_t taken = tile_row(a, kRowAbove)[tile] + gt + (rank_ties ? 0u : eq);
+      tile_row(a, kRowTake)[tile] = taken;
+      uint32_t* grp = a.group_counts + (tile / GT) * kNumThres;
+      if (taken) atomicAdd(&grp[kColTake], taken);
+      if (rank_ties) {
+        tile_row(a, kRowTies)[tile] = eq;
+        if (eq) atomicAdd(&grp[kColTies], eq);
+      }
     }
   }
 }
@@ -339,7 +344,7 @@ __device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, const
   __syncthreads();  // lds is reused by the next chunk
 }
 
-template <bool NORMS>
+template <bool NORMS, int GT, int MG>  // tiles per group, groups at most
 __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ uint32_t lds_base[2];
@@ -351,14 +356,24 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   const OrderedSel o = {c.topk_key, c.topk_take, c.rank_ties != 0, false, 0, a.flat_cap};
   const uint32_t take = o.take;
   const bool rank_ties = o.rank_ties;
-  const uint32_t g = tile / kGroupTiles, g0 = g * kGroupTiles, within = tile - g0;
+  const uint32_t g = tile / GT, g0 = g * GT, within = tile - g0;
   if (wave_id() == 0) {  // survivors and ties before this tile: whole groups, then tiles of its own
     uint32_t x = 0, y = 0;
-    if ((uint32_t)lane_id() < g) x += a.group_counts[lane_id() * kNumThres + kColTake];
-    if ((uint32_t)lane_id() < within) x += tile_row(a, kRowTake)[g0 + lane_id()];
-    if (rank_ties) {
-      if ((uint32_t)lane_id() < g) y += a.group_counts[lane_id() * kNumThres + kColTies];
-      if ((uint32_t)lane_id() < within) y += tile_row(a, kRowTies)[g0 + lane_id()];
+#pragma unroll
+    for (int j0 = 0; j0 < MG; j0 += 64) {
+      const uint32_t j = j0 + lane_id();
+      if (j < g) {
+        x += a.group_counts[j * kNumThres + kColTake];
+        if (rank_ties) y += a.group_counts[j * kNumThres + kColTies];
+      }
+    }
+#pragma unroll
+    for (int j0 = 0; j0 < GT; j0 += 64) {
+      const uint32_t j = j0 + lane_id();
+      if (j < within) {
+        x += tile_row(a, kRowTake)[g0 + j];
+        if (rank_ties) y += tile_row(a, kRowTies)[g0 + j];
+      }
     }
     x = wave_sum(x);
     y = wave_sum(y);

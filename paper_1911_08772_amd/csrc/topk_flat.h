@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_fused(const Args a, uint32
   for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < hist_words; i += gridDim.x * kBlock)
     a.hist[i] = 0;
   if (blockIdx.x == 0) {
-    for (uint32_t i = threadIdx.x; i < (uint32_t)(kMaxGroups * kNumThres); i += kBlock)
+    for (uint32_t i = threadIdx.x; i < (uint32_t)(kBigMaxGroups * kNumThres); i += kBlock)
       a.group_counts[i] = 0;
     if (threadIdx.x == 0) {
       SegCtrl& c = a.ctrl[0];
