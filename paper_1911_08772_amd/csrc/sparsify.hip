@@ -311,6 +311,20 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
     if (a.norms) ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
     return;
   }
+  if (SEG && !a.inplace) {  // layer-wise with candidate filtering: see topk_seg.h
+    ln.run("topk_accum_hist", k_topk_accum_hist<true>, pg, blk, a);
+    ln.run("topk_filter", k_topk_filter_seg, pg, blk, a);
+    ln.run("topk_cand2", k_topk_cand_hist_seg, pg, blk, a, 2);
+    ln.run("topk_cand3", k_topk_cand_hist_seg, pg, blk, a, 3);
+    ln.run("topk_final", k_topk_cand_final_seg, pg, blk, a);
+    if (a.norms) {
+      ln.run("topk_compact", k_topk_compact_ordered_seg<true>, pg, blk, a);
+      ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
+    } else {
+      ln.run("topk_compact", k_topk_compact_ordered_seg<false>, pg, blk, a);
+    }
+    return;
+  }
   if (!SEG && tiles <= (uint32_t)kFusedMaxTiles) {  // seven launches: see topk_flat.h
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
     {

@@ -191,7 +191,7 @@ def test_stream_argument_and_trace():
     b = gpu.b
     gpu.grad.copy_(torch.from_numpy(g))
     torch.cuda.synchronize()
-    for fn, n_stage in ((S.sparsify_gaussiank, 3), (S.sparsify_topk, 7)):
+    for fn, n_stage in ((S.sparsify_gaussiank, 3), (S.sparsify_topk, 7), (S.sparsify_dgck, 11)):
         b.residual.zero_()
         torch.cuda.synchronize()
         fn(wl.d, wl.k, gpu.grad, b.residual, b.acc, b.out_idx, b.out_val, gpu.cap, b.result,
@@ -202,5 +202,5 @@ def test_stream_argument_and_trace():
         res = S.decode_results(b.result)[0]
         assert res["nnz"] > 0
         idx_o, val_o, eps_o, _ = (O.gaussiank(g, wl.k, cap=gpu.cap) if fn is S.sparsify_gaussiank
-                                  else O.topk(g, wl.k))
+                                  else O.topk(g, wl.k) if fn is S.sparsify_topk else O.dgck(g, wl.k))
         assert same_bits(b.residual.cpu().numpy(), eps_o)

@@ -148,3 +148,27 @@ def test_cfg4_segmented_workload(mode):
         wl.grad(step, out=g)
         eps = check_segmented(mode, gpu, g, eps, what=f"cfg4 mode {mode} step {step}")
         progress(f"cfg4 mode {mode} step {step} ok")
+
+
+def test_layer_wise_calls_take_the_short_launch_sequences():
+    """The kernels behind a call are visible through the trace: setup + three launches for
+    Gaussian_k, eight launches for Top_k with a separate accumulator (candidate filtering),
+    the long general sequence only in place."""
+    seg_off, seg_k, caps = layout([100_000, 7, 250_001, 64])
+    want = {(1, False): ["seg_setup", "accum_moments", "gk_count", "gk_compact"],
+            (0, False): ["seg_setup", "hist_zero", "topk_accum_hist", "topk_filter", "topk_cand2",
+                         "topk_cand3", "topk_final", "topk_compact"]}
+    g = seg_grad(seg_off, 5, 0, [1e-2, 1.0, 1e-3, 1e-1])
+    for inplace in (False, True):
+        gpu = SegGpu(seg_off, seg_k, caps, inplace)
+        for mode in (1, 0):
+            tr = S.Trace()
+            gpu.set_residual(np.zeros_like(g))
+            gpu.step(mode, g, trace=tr)
+            names = [n for n, _ in tr.stages()]
+            if (mode, inplace) in want:
+                assert names == want[(mode, inplace)], names
+            elif mode == 1:
+                assert names == want[(1, False)], names
+            else:
+                assert len(names) == 13 and names[-1] == "topk_compact", names
