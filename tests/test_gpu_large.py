@@ -37,7 +37,10 @@ def test_properties_at_sizes_beyond_the_oracle(d):
     key = g.view(np.uint32) & np.uint32(0x7FFFFFFF)
     gpu = FlatGpu(d, cap)
     # Gaussian_k: the mask is exactly {|acc| > thres_f32}; counts and residual follow
-    got = gpu.step("gaussiank", g, k)
+    tr = S.Trace()
+    got = gpu.step("gaussiank", g, k, trace=tr)
+    # vectors this long take the chunk-per-workgroup accumulate and the fold of its partials
+    assert [n for n, _ in tr.stages()] == ["accum_moments", "fold_moments", "gk_count", "gk_compact"]
     res = got["res"]
     t32 = np.float32(res["thres_f32"])
     want = np.nonzero(np.abs(g) > t32)[0].astype(np.uint32)
@@ -54,7 +57,9 @@ def test_properties_at_sizes_beyond_the_oracle(d):
     progress(f"d={d} gaussiank ok")
     # Top_k: exactly k, every kept magnitude >= every dropped one, ties only at the k-th key
     gpu.b.residual.zero_()
-    got = gpu.step("topk", g, k)
+    got = gpu.step("topk", g, k, trace=tr)
+    assert [n for n, _ in tr.stages()] == ["topk_init", "topk_accum_hist", "topk_filter", "topk_cand2",
+                                           "topk_cand3", "topk_final", "topk_compact"]
     res = got["res"]
     idx = np.sort(got["idx"])
     assert idx.size == k and np.all(np.diff(idx.astype(np.int64)) > 0)
