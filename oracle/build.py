@@ -6,13 +6,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "liboracle.so")
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, src: str = None, out: str = None) -> str:
+    """Compiles oracle.cpp (or another source file with the same interface) into a library."""
+    out = out or LIB
     cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
-           "-shared", "-fPIC", os.path.join(HERE, "oracle.cpp"), "-o", LIB]
+           "-I", HERE, "-shared", "-fPIC", src or os.path.join(HERE, "oracle.cpp"), "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 def ensure_built() -> str:

@@ -4,6 +4,7 @@ Only tests, the smoke check and the benchmark's CPU-baseline leg import this mod
 HIP library and its Python binding never do.  Arrays are numpy, host memory.
 """
 import ctypes as C
+import os
 from dataclasses import dataclass
 
 import numpy as np
@@ -47,7 +48,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(_build.ensure_built())
+        # ORACLE_LIBRARY names another build of oracle.cpp to load instead: the mutation check of
+        # the pins (tests/test_oracle_mutants.py) runs the pins against deliberately broken copies
+        L = C.CDLL(os.environ.get("ORACLE_LIBRARY") or _build.ensure_built())
         fp, up, ip = C.POINTER(C.c_float), C.POINTER(C.c_uint32), C.POINTER(C.c_int64)
         L.oracle_accumulate.argtypes = [C.c_int64, fp, fp, fp]
         L.oracle_accumulate.restype = None

@@ -49,6 +49,103 @@ def tiny_vectors(d, rng):
     return out
 
 
+# ---- Eq. (2): the accumulator is one correctly rounded fp32 sum ------------------------------
+
+def fraction_to_f32_bits(x: Fraction, sign_if_zero: int) -> int:
+    """Bit pattern of the binary32 value nearest to the rational x (ties to even, gradual
+    underflow, overflow to infinity), worked out in integer arithmetic."""
+    if x == 0:
+        return sign_if_zero << 31
+    sign = 1 if x < 0 else 0
+    m = -x if sign else x
+    e = m.numerator.bit_length() - m.denominator.bit_length()      # 2^e <= m < 2^(e+1), maybe off by 1
+    if Fraction(2) ** e > m:
+        e -= 1
+    assert Fraction(2) ** e <= m < Fraction(2) ** (e + 1)
+    q = max(e, -126) - 23                                            # exponent of one unit in the last place
+    scaled = m / Fraction(2) ** q
+    n = scaled.numerator // scaled.denominator
+    rem = scaled - n
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (n & 1)):
+        n += 1
+    # n units of 2^q; n may have reached 2^24 (carry into the next binade): the encoding below
+    # absorbs that because the exponent field is simply added
+    if e < -126:
+        bits = n                                                     # denormal (or the smallest normal)
+    else:
+        bits = ((e + 127) << 23) + (n - (1 << 23))
+    if bits >= 0x7F800000:
+        bits = 0x7F800000                                            # past the largest finite value
+    return (sign << 31) | bits
+
+
+def exact_fp32_sum_bits(g: np.float32, e: np.float32) -> int:
+    """What Eq. (2) asks of one element: g + eps rounded once to fp32, from exact arithmetic."""
+    if np.isnan(g) or np.isnan(e):
+        return -1                                                    # any NaN will do
+    if np.isinf(g) or np.isinf(e):
+        if np.isinf(g) and np.isinf(e) and (g > 0) != (e > 0):
+            return -1                                                # Inf - Inf
+        big = g if np.isinf(g) else e
+        return 0x7F800000 | ((1 << 31) if big < 0 else 0)
+    both_negative_zero = int(np.signbit(g) and np.signbit(e))        # x + y = -0 only for (-0) + (-0)
+    return fraction_to_f32_bits(Fraction(float(g)) + Fraction(float(e)), both_negative_zero)
+
+
+def test_accumulate_is_one_correctly_rounded_fp32_add():
+    """Eq. (2) / Sec. 3.1, u = g + eps in the paper's fp32: every element of the oracle's
+    accumulator equals the exact rational sum rounded once to nearest-even.  (A detour through
+    fp64 would not be a mistake: 53 >= 2*24 + 2 bits make the double rounding of a sum
+    innocuous; a subtraction, a truncation, flushed denormals or a lost sign of zero would.)"""
+    rng = np.random.default_rng(20)
+    f32 = np.float32
+    tiny = f32(1e-45)                                                # smallest denormal
+    big = f32(np.finfo(np.float32).max)
+    planted = [
+        (f32(1.5), f32(-1.5)),                  # exact cancellation gives +0
+        (f32(0.0), f32(-0.0)), (f32(-0.0), f32(0.0)), (f32(-0.0), f32(-0.0)), (f32(0.0), f32(0.0)),
+        (tiny, tiny), (f32(3) * tiny, f32(-5) * tiny), (f32(2.0 ** -126), -tiny),   # denormal results
+        (f32(2.0 ** -126), f32(-(2.0 ** -126) * (1 - 2.0 ** -23))),                 # normal - normal = denormal
+        (big, big), (-big, -big), (big, f32(2.0 ** 103)), (big, f32(2.0 ** 102)),    # overflow and its edge
+        (f32(np.inf), f32(1.0)), (f32(-np.inf), f32(np.inf)), (f32(np.nan), f32(1.0)), (f32(1.0), f32(np.nan)),
+        (f32(1.0), f32(2.0 ** -24)),            # tie, even neighbour below
+        (f32(1.0 + 2.0 ** -23), f32(2.0 ** -24)),  # tie, even neighbour above
+        (f32(1.0), f32(2.0 ** -24 * (1 + 2.0 ** -23))),   # just above the tie
+        (f32(1.0), f32(-(2.0 ** -25))), (f32(1.0), f32(-(2.0 ** -25) * (1 + 2.0 ** -23))),
+        (f32(1.0), f32(2.0 ** -60)), (f32(-3.0e10), f32(1.0e-12)),   # exponents far apart
+        (f32(0.1), f32(0.2)), (f32(16777216.0), f32(1.0)), (f32(16777216.0), f32(3.0)),
+    ]
+    g = np.array([p[0] for p in planted], f32)
+    e = np.array([p[1] for p in planted], f32)
+    # seeded pairs: gradient-like, wide exponent spread, and denormal ranges
+    n = 1000
+    mant = rng.standard_normal(n)
+    g = np.concatenate([g, (mant * 10.0 ** rng.uniform(-44, 38, n)).astype(f32)])
+    e = np.concatenate([e, (rng.standard_normal(n) * 10.0 ** rng.uniform(-44, 38, n)).astype(f32)])
+    g = np.concatenate([g, (rng.standard_normal(n) * 1e-3).astype(f32)])
+    e = np.concatenate([e, (rng.standard_normal(n) * 1e-3).astype(f32)])
+    with np.errstate(over="ignore", invalid="ignore"):
+        acc = O.accumulate(g, e)
+    got = acc.view(np.uint32)
+    for i in range(g.size):
+        want = exact_fp32_sum_bits(g[i], e[i])
+        if want < 0:
+            assert np.isnan(acc[i]), (i, g[i], e[i], acc[i])
+        else:
+            assert int(got[i]) == want, (i, g[i], e[i], acc[i], hex(int(got[i])), hex(want))
+    # eps = 0 (the first iteration, eps_0 = 0): the accumulator carries g's bits, -0 included
+    zero = np.zeros_like(g)
+    keep = ~np.isnan(g)
+    carried = O.accumulate(g, zero).view(np.uint32)[keep]
+    want0 = g.view(np.uint32)[keep].copy()
+    want0[want0 == 0x80000000] = 0                                   # (-0) + (+0) = +0
+    assert np.array_equal(carried, want0)
+    # the rounding helper itself, against the float conversions of the language
+    for v in [0.1, 1 / 3, 1e-40, 3e-45, 7e-46, 3.4028235e38, 3.4028236e38, 1e39, 16777217.0]:
+        with np.errstate(over="ignore"):
+            assert fraction_to_f32_bits(Fraction(v), 0) == int(f32(v).view(np.uint32)), v
+
+
 # ---- P1/P2/P3: Top_k definition, exactly k survivors, residual identity ---------------------
 
 def test_topk_matches_brute_force_sort_on_tiny_vectors():
@@ -156,14 +253,15 @@ def test_norm_isf_against_tabulated_values_and_library():
 
 def test_moments_closed_form_arithmetic_progression():
     # x_j = a + j*h, j = 0..d-1: mean = a + (d-1)h/2, sum of squared deviations = h^2 d (d^2-1)/12
-    d, a, h = 40_001, 0.25, 2.0 ** -9
-    x = (a + np.arange(d) * h).astype(np.float32)
-    assert np.array_equal(x.astype(np.float64), a + np.arange(d) * h)  # exactly representable
-    for ddof in (0, 1):
-        mean, std = O.moments(x, ddof)
-        assert mean == a + (d - 1) * h / 2
-        var = Fraction(h) ** 2 * d * (d * d - 1) / 12 / (d - ddof)
-        assert math.isclose(std, math.sqrt(var), rel_tol=1e-13)
+    # (the second progression runs from -70.5 up through zero: the signs matter)
+    for d, a, h in [(40_001, 0.25, 2.0 ** -9), (40_001, -70.5, 2.0 ** -9)]:
+        x = (a + np.arange(d) * h).astype(np.float32)
+        assert np.array_equal(x.astype(np.float64), a + np.arange(d) * h)  # exactly representable
+        for ddof in (0, 1):
+            mean, std = O.moments(x, ddof)
+            assert mean == a + (d - 1) * h / 2
+            var = Fraction(h) ** 2 * d * (d * d - 1) / 12 / (d - ddof)
+            assert math.isclose(std, math.sqrt(var), rel_tol=1e-13)
 
 
 def test_moments_against_numpy_and_one_pass():
