@@ -47,8 +47,9 @@ enum {
   SPARSIFY_F_OVERFLOW = 1u,  /* more survivors than `cap`: nothing selected, residual' = acc */
   SPARSIFY_F_NONFINITE = 2u, /* mean, std or threshold not finite */
   SPARSIFY_F_EXHAUSTED = 4u, /* four count evaluations used, last one still outside the band */
-  SPARSIFY_F_BADSEGMENT = 8u /* segmented call: this segment's offsets or k are invalid;
-                                the segment is left untouched apart from acc */
+  SPARSIFY_F_BADSEGMENT = 8u /* segmented call: this segment's offsets, k or output range are
+                                invalid (or its start lies before an earlier offset); no kernel
+                                touches its stretch of acc, residual or the output */
 };
 
 /* Written on the stream; valid once the stream has been synchronised. */
@@ -143,7 +144,8 @@ int sparsify_dgck(int64_t d, int64_t k, const float* grad, float* residual, floa
  *   out_cap   number of elements in out_idx / out_val (>= out_off[num_segments])
  *   results   sparsify_result[num_segments]
  * Indices are positions in the flat buffer.  The three layout arrays are read on the device
- * only; a segment whose entries are invalid gets SPARSIFY_F_BADSEGMENT and produces nothing. */
+ * only; a segment whose entries are invalid, or that starts before an earlier entry of seg_off
+ * (so that it could overlap an earlier segment), gets SPARSIFY_F_BADSEGMENT and produces nothing. */
 int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg_off,
                        const int64_t* seg_k, int32_t mode, const float* grad, float* residual,
                        float* acc, uint32_t* out_idx, float* out_val, const int64_t* out_off,
@@ -159,8 +161,8 @@ void sparsify_trace_destroy(sparsify_trace* t);
 int32_t sparsify_trace_num_stages(const sparsify_trace* t);
 /* name of stage i (kernel name), valid until the next traced call */
 const char* sparsify_trace_stage_name(const sparsify_trace* t, int32_t i);
-/* duration of stage i in milliseconds, and the elements it processed per launch; returns
- * SPARSIFY_E_INVALID if i is out of range or the events are not complete */
+/* duration of stage i in milliseconds (from the event before its launch to the event after it);
+ * returns SPARSIFY_E_INVALID if i is out of range or the events are not complete */
 int sparsify_trace_stage_ms(sparsify_trace* t, int32_t i, float* ms);
 
 /* Measurement aid: copies n floats (n a positive multiple of 4; both DEVICE pointers 16-byte

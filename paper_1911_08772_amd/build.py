@@ -47,15 +47,22 @@ def _stale(lib, srcs):
                                             for s in srcs)
 
 
+def _sparsify_sources():
+    return ([os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h"))] +
+            [os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h")])
+
+
 def ensure_synth() -> str:
-    if not os.path.exists(LIB_SYNTH):
+    """Path of the built generator; (re)builds it when it is missing or older than its source."""
+    if _stale(LIB_SYNTH, [os.path.join(CSRC, "synth.c")]):
         build_synth()
     return LIB_SYNTH
 
 
 def ensure_sparsify() -> str:
-    """Path of the built HIP library; builds it only if no built library is there."""
-    if not os.path.exists(LIB_SPARSIFY):
+    """Path of the built HIP library; (re)builds it when it is missing or older than any of its
+    sources, so that a test run never silently exercises the binary of an earlier edit."""
+    if _stale(LIB_SPARSIFY, _sparsify_sources()):
         build_sparsify()
     return LIB_SPARSIFY
 

@@ -58,10 +58,38 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_flat(const Args a) {
 // mode 0 = Top_k, 1 = Gaussian_k.
 constexpr uint32_t kSegGroupTiles = 64;
 
+// Largest of the values held by the threads before the calling one (thread order), and the largest
+// of all: a segment may start only at or after every earlier offset, or two valid segments could
+// overlap.  `lds` holds kWaves words of 8 bytes.  Two barriers.
+__device__ inline int64_t block_exclusive_max(int64_t v, int64_t lowest, int64_t* lds, int64_t* all) {
+  int64_t inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int64_t o = __shfl_up(inc, off, 64);
+    if (lane_id() >= off && o > inc) inc = o;
+  }
+  int64_t before = __shfl_up(inc, 1, 64);
+  if (lane_id() == 0) before = lowest;
+  if (lane_id() == 63) lds[wave_id()] = inc;
+  __syncthreads();
+  int64_t total = lowest;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const int64_t x = lds[w];
+    if (w < wave_id() && x > before) before = x;
+    if (x > total) total = x;
+  }
+  __syncthreads();
+  *all = total;
+  return before;
+}
+
 __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
   __shared__ uint32_t lds_scan[kWaves + 1];
+  __shared__ int64_t lds_max[kWaves];
   uint32_t carry = 0;    // tiles numbered so far (block-uniform, saturating)
   uint32_t gcarry = 0;   // groups numbered so far
+  int64_t off_max = 0;   // largest offset among the segments of earlier rounds
   for (int base = 0; base < a.L; base += kBlock) {
     const int s = base + (int)threadIdx.x;
     uint32_t nt = 0;
@@ -77,8 +105,15 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
               o0 >= 0 && o1 >= o0 && o1 <= a.out_cap);
       if (s == 0 && start != 0) bad = true;
       if (s == a.L - 1 && end != a.d_total) bad = true;
-      if (!bad) nt = seg_ntiles(start, end, a.tile_chunks);
     }
+    {  // offsets must not step back behind an earlier one (seg_off non-decreasing up to here)
+      const int64_t lowest = (int64_t)1 << 63;
+      int64_t round_max;
+      const int64_t before = block_exclusive_max(s < a.L ? start : lowest, lowest, lds_max, &round_max);
+      if (s < a.L && (start < before || start < off_max)) bad = true;
+      if (round_max > off_max) off_max = round_max;
+    }
+    if (s < a.L && !bad) nt = seg_ntiles(start, end, a.tile_chunks);
     uint32_t total, gtotal;
     const uint32_t excl = block_exclusive_scan(nt, lds_scan, &total);
     // a layout whose valid segments overlap could number more tiles than the workspace holds

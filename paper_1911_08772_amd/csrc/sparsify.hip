@@ -69,13 +69,20 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // stay few.  Odd on purpose: with a power-of-two tile size the workgroups, which advance in step,
 // sit a power of two bytes apart and crowd the same memory channels (measured: 4 chunks per tile
 // 5 % slower than 3 or 5).
+// Vectors of more chunks than kChunkGridFrom (123 M elements) use the chunk-per-workgroup
+// accumulate and, where the selector has the larger group tables (`big_tables`: Gaussian_k and
+// Top_k with a separate accumulator), keep three chunks per tile as long as those tables hold the
+// tiles: measured 3 % slower than the resident form at 67 M and 100 M elements, 2 % faster at
+// 134 M, 5 % at 268 M and 537 M.
 constexpr int64_t kTargetTiles = 4096;
 constexpr int64_t kOneChunkLimit = 1536;
-uint32_t tile_chunks_of(int64_t d_total) {
+constexpr uint32_t kChunkGridFrom = 30000;
+uint32_t tile_chunks_of(int64_t d_total, bool big_tables) {
   const int64_t chunks = (d_total + kChunk - 1) / kChunk;
   if (chunks <= kOneChunkLimit) return 1;
+  const int64_t most = (big_tables && chunks > (int64_t)kChunkGridFrom) ? kBigMaxTiles : kTargetTiles;
   uint32_t c = 3;
-  while ((chunks + c - 1) / c > kTargetTiles) c += 2;
+  while ((chunks + c - 1) / c > most) c += 2;
   return c;
 }
 
@@ -187,7 +194,7 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.norms = (opts && opts->error_norms) ? 1 : 0;
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
   a.hist_copies = hist_copies_of(L);
-  a.tile_chunks = tile_chunks_of(d_total);
+  a.tile_chunks = tile_chunks_of(d_total, false);
   if (opts && opts->tile_chunks != 0) {
     if (opts->tile_chunks < 0 || opts->tile_chunks > (1 << 20)) return SPARSIFY_E_INVALID;
     a.tile_chunks = (uint32_t)opts->tile_chunks;
@@ -206,11 +213,6 @@ uint32_t compute_units() {
     return 256;
   return (uint32_t)cus;
 }
-
-// Vectors of more chunks than this (123 M elements) use the chunk-per-workgroup accumulate and,
-// for Gaussian_k, the larger group tables: measured 3 % slower than the resident form at 67 M and
-// 100 M elements, 2 % faster at 134 M, 5 % at 268 M and 537 M.
-constexpr uint32_t kChunkGridFrom = 30000;
 
 // Layer-wise Gaussian_k: setup + three launches (gaussiank_seg.h).
 void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
@@ -398,16 +400,8 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
-  if ((selector == kSelGaussian || (selector == kSelTopk && !a.inplace)) &&
-      !(opts && opts->tile_chunks != 0)) {
-    // long vectors: three chunks per tile as long as the larger group tables hold the tiles
-    const int64_t chunks = (d + kChunk - 1) / kChunk;
-    if (chunks > (int64_t)kChunkGridFrom) {
-      uint32_t c = 3;
-      while ((chunks + c - 1) / c > (int64_t)kBigMaxTiles) c += 2;
-      a.tile_chunks = c;
-    }
-  }
+  if (!(opts && opts->tile_chunks != 0))
+    a.tile_chunks = tile_chunks_of(d, selector == kSelGaussian || (selector == kSelTopk && !a.inplace));
   const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
   if (selector == kSelDgc) {
     // the per-tile key lists live in the residual buffer and the list kernels use one lane per

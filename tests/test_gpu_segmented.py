@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from gpu_harness import SegGpu, check_segmented, progress, same_bits
+from oracle import oracle as O
 from paper_1911_08772_amd import sparsify as S
 from paper_1911_08772_amd import synth
 
@@ -133,6 +134,40 @@ def test_invalid_segments_are_flagged_and_produce_nothing():
             assert out["res"][l]["flags"] == S.F_BADSEGMENT and out["res"][l]["nnz"] == 0
         assert np.all(out["idx"][200:] == -1)
         gpu.b.residual.zero_()
+
+
+def test_segments_that_step_back_behind_an_earlier_offset_are_flagged():
+    """A layout whose offsets are not monotone: a segment that is valid on its own but starts
+    before an earlier offset could overlap an earlier segment, so it is flagged and skipped; the
+    segments before the step back are processed as usual."""
+    d = 20_000
+    #                     seg0 [0,9000)  seg1 backwards  seg2 [5000,6000)  seg3 [6000,20000)
+    seg_off = np.array([0, 9000, 5000, 6000, 20_000], np.int64)
+    seg_k = np.array([9, 1, 1, 14], np.int64)
+    caps = np.array([100, 100, 100, 100], np.int64)
+    gpu = SegGpu(seg_off, seg_k, caps)
+    g = synth.normal(d, 6, 0, 1.0)
+    for mode in (0, 1):
+        gpu.b.residual.zero_()
+        gpu.b.acc.fill_(float("nan"))
+        out = gpu.step(mode, g)
+        assert out["res"][0]["flags"] == 0 and out["res"][0]["nnz"] > 0
+        for l in (1, 2, 3):
+            assert out["res"][l]["flags"] == S.F_BADSEGMENT and out["res"][l]["nnz"] == 0, l
+        assert np.all(out["idx"][100:] == -1)
+        # segment 0 alone was processed: its stretch equals the flat oracle on it, the rest of
+        # acc was never written
+        acc_o = O.accumulate(g[:9000], np.zeros(9000, np.float32))
+        assert same_bits(out["acc"][:9000], acc_o)
+        assert np.all(np.isnan(out["acc"][9000:]))
+        if mode == 0:
+            idx_o, val_o, eps_o, _ = O.topk(acc_o, 9)
+        else:
+            idx_o, val_o, eps_o, ro = O.gaussiank(acc_o, 9, cap=100)
+        n = int(out["res"][0]["nnz"])
+        assert np.array_equal(np.sort(out["idx"][:n].view(np.uint32)), idx_o)
+        assert same_bits(out["eps"][:9000], eps_o)
+        assert not out["eps"][9000:].any()
 
 
 @pytest.mark.parametrize("mode", [0, 1])
