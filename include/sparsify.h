@@ -108,6 +108,20 @@ int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual,
                        void* workspace, size_t workspace_bytes, const sparsify_opts* opts,
                        void* stream);
 
+/* sparsify_gaussiank for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as sparsify_gaussiank except that there is no workspace
+ * argument: the partial results live in a 4 MiB array built into the library (one copy per GPU,
+ * held until the process ends), which limits d to 2^27 = 134,217,728 elements; a larger d returns
+ * SPARSIFY_E_WORKSPACE before anything is launched.  The call allocates nothing and frees
+ * nothing.  The array keeps the previous call's contents (the kernels rewrite what they read) and
+ * every call on one GPU shares it: calls that overlap on one GPU, on whatever streams, race;
+ * order them on one stream or with events.  The first call on a device looks up the array's
+ * device address (once per device, with that device current). */
+int sparsify_gaussiank_static(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                              uint32_t* out_idx, float* out_val, int64_t cap,
+                              sparsify_result* result, const sparsify_opts* opts, void* stream);
+
 /* Exact Top_k compressor (definition in Sec. 1: the k entries largest in absolute value;
  * among equal magnitudes the lower index wins).  Same arguments; cap >= k is required; exactly
  * k pairs are written.  opts: tail_div and ddof are checked but not used. */

@@ -4,6 +4,7 @@
 
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -19,6 +20,14 @@
 #include "topk_flat.h"
 
 using namespace sp;
+
+// ---- built-in workspace of the entry point that allocates nothing ------------------------------
+// One copy per GPU the library runs on, held until the process ends.  In host code the array's
+// name is only a handle for the runtime's symbol lookup: the device address is looked up once per
+// device (static_scratch below) and that pointer is what the kernels receive.
+constexpr size_t kStaticScratchBytes = size_t(4) << 20;
+constexpr int64_t kStaticMaxD = int64_t(1) << 27;  // workspace of 2^27 elements: 3.06 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // ---- per-kernel timing (optional) -----------------------------------------------------------
 constexpr int kMaxStages = 24;
@@ -389,6 +398,24 @@ void launch_dgck(Launcher& ln, const Args& a, uint32_t tiles) {
 
 enum { kSelGaussian = 0, kSelTopk = 1, kSelDgc = 2 };
 
+// Device address of this device's copy of `scratch`, looked up on the first call made with that
+// device current and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPARSIFY_E_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SPARSIFY_E_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SPARSIFY_OK;
+}
+
 int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* residual, float* acc,
               uint32_t* out_idx, float* out_val, int64_t cap, sparsify_result* result,
               void* workspace, size_t workspace_bytes, const sparsify_opts* opts, void* stream) {
@@ -447,6 +474,20 @@ int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual,
                        void* stream) {
   return flat_call(kSelGaussian, d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                    workspace_bytes, opts, stream);
+}
+
+int sparsify_gaussiank_static(int64_t d, int64_t k, const float* grad, float* residual, float* acc,
+                              uint32_t* out_idx, float* out_val, int64_t cap,
+                              sparsify_result* result, const sparsify_opts* opts, void* stream) {
+  if (d > kStaticMaxD) return SPARSIFY_E_WORKSPACE;  // beyond what the built-in workspace holds
+  if (d < 1 || k < 1 || k > d) return SPARSIFY_E_INVALID;
+  static_assert(kStaticScratchBytes % 256 == 0, "the workspace is carved in 256-byte units");
+  if (carve(d, 1).total > kStaticScratchBytes) return SPARSIFY_E_WORKSPACE;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != SPARSIFY_OK) return rc;
+  return flat_call(kSelGaussian, d, k, grad, residual, acc, out_idx, out_val, cap, result, ws,
+                   kStaticScratchBytes, opts, stream);
 }
 
 int sparsify_topk(int64_t d, int64_t k, const float* grad, float* residual, float* acc,

@@ -40,6 +40,8 @@ _flat = [C.c_int64, C.c_int64, _p, _p, _p, _p, _p, C.c_int64, _p, _p, C.c_size_t
 lib.sparsify_gaussiank.argtypes = _flat
 lib.sparsify_topk.argtypes = _flat
 lib.sparsify_dgck.argtypes = _flat
+lib.sparsify_gaussiank_static.argtypes = [C.c_int64, C.c_int64, _p, _p, _p, _p, _p, C.c_int64, _p,
+                                          C.POINTER(Opts), _p]
 lib.sparsify_segmented.argtypes = [C.c_int32, C.c_int64, _p, _p, C.c_int32, _p, _p, _p, _p, _p,
                                    _p, C.c_int64, _p, _p, C.c_size_t, C.POINTER(Opts), _p]
 lib.sparsify_calibration_copy.argtypes = [_p, _p, C.c_int64, _p]
@@ -52,7 +54,7 @@ lib.sparsify_trace_stage_name.restype = C.c_char_p
 lib.sparsify_trace_stage_ms.argtypes = [_p, C.c_int32, C.POINTER(C.c_float)]
 
 EXPORTS = ["sparsify_version", "sparsify_workspace_bytes", "sparsify_gaussiank", "sparsify_topk",
-           "sparsify_dgck",
+           "sparsify_dgck", "sparsify_gaussiank_static",
            "sparsify_segmented", "sparsify_calibration_copy", "sparsify_trace_create", "sparsify_trace_destroy",
            "sparsify_trace_num_stages", "sparsify_trace_stage_name", "sparsify_trace_stage_ms"]
 
@@ -131,6 +133,22 @@ def sparsify_gaussiank(d, k, grad, residual, acc, out_idx, out_val, cap, result,
                                 workspace_nbytes, C.byref(o), _stream(stream))
     if check and rc != OK:
         raise SparsifyError(rc, "sparsify_gaussiank")
+    return rc
+
+
+STATIC_MAX_D = 1 << 27
+
+
+def sparsify_gaussiank_static(d, k, grad, residual, acc, out_idx, out_val, cap, result,
+                              tail_div=2.0, ddof=1, trace=None, stream=None, check=True,
+                              tile_chunks=0, error_norms=False) -> int:
+    """sparsify_gaussiank on the library's built-in workspace (d <= STATIC_MAX_D)."""
+    o = _opts(tail_div, ddof, trace, tile_chunks, error_norms)
+    rc = lib.sparsify_gaussiank_static(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
+                                       _ptr(out_val), cap, _ptr(result), C.byref(o),
+                                       _stream(stream))
+    if check and rc != OK:
+        raise SparsifyError(rc, "sparsify_gaussiank_static")
     return rc
 
 

@@ -116,3 +116,14 @@ def test_segmented_rejects_bad_arguments():
     assert rc(seg_k=seg + 4) == S.E_INVALID
     assert rc(d=0) == S.E_INVALID
     assert rc(L=50) == S.E_WORKSPACE  # workspace sized for 3 segments
+
+
+def test_static_workspace_call_rejects_long_vectors_before_anything_else():
+    """The entry point without a workspace argument holds at most 2^27 elements' worth of partial
+    results: a longer vector is refused on the host, before any device call."""
+    a, _ = flat_args()
+    rc = S.sparsify_gaussiank_static(S.STATIC_MAX_D + 1, 10, a["grad"], a["residual"], a["acc"],
+                                     a["out_idx"], a["out_val"], a["cap"], a["result"], stream=0,
+                                     check=False)
+    assert rc == S.E_WORKSPACE
+    assert S.workspace_bytes(S.STATIC_MAX_D, 1) <= 4 << 20 < S.workspace_bytes(2 * S.STATIC_MAX_D, 1)
