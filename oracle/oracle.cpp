@@ -245,6 +245,25 @@ int oracle_randk_dense(int64_t d, int64_t k, const float* acc, const uint32_t* c
   return 0;
 }
 
+int oracle_scatter_add(int64_t d, int32_t num_lists, const uint32_t* idx, const float* val,
+                       int64_t list_stride, const uint32_t* nnz, float scale, float* dense) {
+  if (d < 1 || d >= (int64_t(1) << 31) || num_lists < 1 || list_stride < 0) return 1;
+  for (int32_t p = 0; p < num_lists; ++p) {
+    if ((int64_t)nnz[p] > list_stride) return 1;
+    for (uint32_t j = 0; j < nnz[p]; ++j)
+      if ((int64_t)idx[(int64_t)p * list_stride + j] >= d) return 1;
+  }
+  for (int64_t i = 0; i < d; ++i) dense[i] = 0.0f;
+  // the sum over the workers of Eq. (2): worker after worker, each list from its first pair on
+  for (int32_t p = 0; p < num_lists; ++p) {
+    const uint32_t* pi = idx + (int64_t)p * list_stride;
+    const float* pv = val + (int64_t)p * list_stride;
+    for (uint32_t j = 0; j < nnz[p]; ++j) dense[pi[j]] = dense[pi[j]] + pv[j];
+  }
+  for (int64_t i = 0; i < d; ++i) dense[i] = dense[i] * scale;  // 1/P for the average of Eq. (2)
+  return 0;
+}
+
 int oracle_segmented(int32_t num_segments, const int64_t* seg_off, const int64_t* seg_k,
                      int32_t mode, const float* acc, const int64_t* out_off, double tail_div,
                      int32_t ddof, uint32_t* idx, float* val, float* eps_out,

@@ -15,7 +15,9 @@
  * routine; moments against closed forms; Algorithm 1's count-and-nudge walk
  * against counts known in closed form on constructed vectors; DGC_k against Top_k when the
  * sample is the whole vector, against planted vectors whose outcome is known, and against the
- * exact Top_k whenever its second selection runs.
+ * exact Top_k whenever its second selection runs; the aggregation of sparse lists against
+ * a numpy scatter (one worker, disjoint workers), exact integer sums in any order, a planted
+ * collision whose fp32 sum depends on the order of the workers, and a sequential library sum.
  * Parity unpinned (conventions the paper does not fix; both sides implement the
  * same reading): the two-sided tail 1-k/(2d) default, the sample (n-1) standard
  * deviation, the fp32 rounding of the threshold before comparing, and the use of
@@ -91,6 +93,15 @@ int oracle_dgck(int64_t d, int64_t k, const float* acc, int32_t sample_stride, u
  * (distinct) indices, 0 elsewhere. */
 int oracle_randk_dense(int64_t d, int64_t k, const float* acc, const uint32_t* chosen,
                        float* dense_out);
+
+/* Decompression and aggregation, the sum over the P workers in Eq. (2):
+ *   dense = scale * sum_p Comp_k(acc_p),   Comp_k(acc_p) given as worker p's (index, value) pairs.
+ * Worker p's pairs are idx/val[p*list_stride + j], j < nnz[p].  Every element starts at +0 and
+ * receives its contributions one fp32 addition at a time, worker 0 first, each worker's pairs in
+ * list order; at the end every element is multiplied once by `scale` in fp32 (1 gives the plain
+ * sum, 1/P the average that Eq. (2) applies).  Invalid (index >= d, nnz[p] > list_stride): 1. */
+int oracle_scatter_add(int64_t d, int32_t num_lists, const uint32_t* idx, const float* val,
+                       int64_t list_stride, const uint32_t* nnz, float scale, float* dense);
 
 /* Layer-wise form: the flat routine applied to each [seg_off[l], seg_off[l+1]) with
  * seg_k[l]; indices are positions in the flat buffer; segment l's pairs start at

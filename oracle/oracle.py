@@ -67,6 +67,7 @@ def lib():
         L.oracle_randk_dense.argtypes = [C.c_int64, C.c_int64, fp, up, fp]
         L.oracle_dgck.argtypes = [C.c_int64, C.c_int64, fp, C.c_int32, C.c_uint64, up, fp, fp,
                                   C.POINTER(_Result), up]
+        L.oracle_scatter_add.argtypes = [C.c_int64, C.c_int32, up, fp, C.c_int64, up, C.c_float, fp]
         L.oracle_segmented.argtypes = [C.c_int32, ip, ip, C.c_int32, fp, ip, C.c_double, C.c_int32,
                                        up, fp, fp, C.POINTER(_Result)]
         _lib = L
@@ -179,3 +180,15 @@ def segmented(acc: np.ndarray, seg_off: np.ndarray, seg_k: np.ndarray, mode: int
     if rc != 0:
         raise ValueError("oracle_segmented: invalid arguments")
     return idx, val, eps, [Result.of(res[l]) for l in range(L)]
+
+
+def scatter_add(d: int, idx: np.ndarray, val: np.ndarray, nnz: np.ndarray, scale: float = 1.0,
+                out: np.ndarray = None) -> np.ndarray:
+    """idx, val: [P, stride] (uint32, float32); nnz: uint32[P] -> dense float32[d]."""
+    assert idx.ndim == 2 and idx.shape == val.shape and nnz.shape == (idx.shape[0],)
+    dense = np.empty(d, np.float32) if out is None else out
+    rc = lib().oracle_scatter_add(d, idx.shape[0], _u(idx.reshape(-1)), _f(val.reshape(-1)),
+                                  idx.shape[1], _u(nnz), scale, _f(dense))
+    if rc != 0:
+        raise ValueError("oracle_scatter_add: invalid arguments")
+    return dense

@@ -96,6 +96,23 @@ MUTANTS = [
     ("dgck_rank_in_sample_rounds_down",
      [("const int64_t ks = (k * m + d - 1) / d;", "const int64_t ks = std::max<int64_t>(1, (k * m) / d);", 1)],
      "dgck"),
+    ("scatter_add_overwrites",
+     [("dense[pi[j]] = dense[pi[j]] + pv[j];", "dense[pi[j]] = pv[j];", 1)],
+     "scatter_add"),
+    ("scatter_add_takes_the_workers_backwards",
+     [("for (int32_t p = 0; p < num_lists; ++p) {\n    const uint32_t* pi",
+       "for (int32_t p = num_lists - 1; p >= 0; --p) {\n    const uint32_t* pi", 1)],
+     "scatter_add"),
+    ("scatter_add_scales_every_pair",
+     [("dense[pi[j]] = dense[pi[j]] + pv[j];", "dense[pi[j]] = dense[pi[j]] + pv[j] * scale;", 1),
+      ("dense[i] = dense[i] * scale;", "dense[i] = dense[i];", 1)],
+     "scatter_add"),
+    ("scatter_add_sums_in_fp64",
+     [("for (int64_t i = 0; i < d; ++i) dense[i] = 0.0f;\n  // the sum over",
+       "std::vector<double> wide((size_t)d, 0.0);\n  // the sum over", 1),
+      ("dense[pi[j]] = dense[pi[j]] + pv[j];", "wide[pi[j]] += (double)pv[j];", 1),
+      ("dense[i] = dense[i] * scale;", "dense[i] = (float)wide[(size_t)i] * scale;", 1)],
+     "scatter_add"),
     ("segment_indices_stay_local",
      [("sidx[j] += (uint32_t)a;", "sidx[j] += 0u;", 1)],
      "segmented"),

@@ -609,3 +609,105 @@ def test_dgck_invariants_on_random_vectors(name):
                 assert np.array_equal(eps.view(np.uint32), exp.view(np.uint32))
                 seen.add(res.rounds)
     assert seen == {1, 2}
+
+
+# ---- the sum over the workers in Eq. (2): aggregation of the sparse lists --------------------
+
+def pad_lists(lists, stride=None):
+    """[(idx array, val array)] per worker -> idx[P, stride], val[P, stride], nnz[P]."""
+    P = len(lists)
+    stride = max([len(i) for i, _ in lists] + [1]) if stride is None else stride
+    idx = np.full((P, stride), 0xFFFFFFFF, np.uint32)      # padding that must never be read
+    val = np.full((P, stride), np.nan, np.float32)
+    nnz = np.zeros(P, np.uint32)
+    for p, (i, v) in enumerate(lists):
+        idx[p, :len(i)] = i
+        val[p, :len(i)] = v
+        nnz[p] = len(i)
+    return idx, val, nnz
+
+
+def test_scatter_add_of_one_worker_is_the_dense_form_of_comp_k():
+    """P = 1: the aggregate is Comp_k(acc) itself, so acc == dense + eps' (Eq. (2))."""
+    rng = np.random.default_rng(30)
+    for d, k in [(1, 1), (50, 7), (20_000, 20), (20_000, 2000)]:
+        acc = (rng.standard_normal(d) * 0.01).astype(np.float32)
+        for sel in (O.topk, O.gaussiank):
+            i, v, eps, _ = sel(acc, k)
+            dense = O.scatter_add(d, *pad_lists([(i, v)]))
+            want = np.zeros(d, np.float32)
+            want[i] = v                                      # numpy's own scatter
+            assert np.array_equal(dense.view(np.uint32), want.view(np.uint32))
+            assert np.array_equal(dense + eps, acc)
+            assert np.all((dense == 0) | (eps == 0))
+
+
+def test_scatter_add_of_disjoint_workers_is_their_union_and_empty_lists_add_nothing():
+    rng = np.random.default_rng(31)
+    d, P = 10_000, 5
+    perm = rng.permutation(d)[:2000].astype(np.uint32)
+    parts = np.array_split(perm, P)
+    lists = [(np.sort(pp), rng.standard_normal(pp.size).astype(np.float32)) for pp in parts]
+    lists.insert(2, (np.zeros(0, np.uint32), np.zeros(0, np.float32)))     # a worker that sent nothing
+    dense = O.scatter_add(d, *pad_lists(lists, stride=700))
+    want = np.zeros(d, np.float32)
+    for i, v in lists:
+        want[i] = v
+    assert np.array_equal(dense.view(np.uint32), want.view(np.uint32))
+    empty = [(np.zeros(0, np.uint32), np.zeros(0, np.float32))] * 3
+    assert not O.scatter_add(77, *pad_lists(empty)).view(np.uint32).any()   # all +0
+
+
+def test_scatter_add_takes_the_workers_in_order():
+    """Three workers hit one index with 1e8, -1e8 and 1: in fp32, (1e8 + -1e8) + 1 = 1 but
+    (1e8 + 1) + -1e8 = 0 and (1 + 1e8) + -1e8 = 0: the sum is taken worker 0 first."""
+    one = lambda i, v: (np.array([i], np.uint32), np.array([v], np.float32))
+    for order, want in [((1e8, -1e8, 1.0), 1.0), ((1e8, 1.0, -1e8), 0.0), ((1.0, 1e8, -1e8), 0.0),
+                        ((-1e8, 1.0, 1e8), 0.0), ((1.0, -1e8, 1e8), 0.0), ((-1e8, 1e8, 1.0), 1.0)]:
+        dense = O.scatter_add(9, *pad_lists([one(4, order[0]), one(4, order[1]), one(4, order[2])]))
+        assert dense[4] == np.float32(want), (order, dense[4])
+        assert not dense[[0, 1, 2, 3, 5, 6, 7, 8]].any()
+    # inside one list the pairs are taken from the first on (a list with a repeated index)
+    rep = (np.array([4, 4, 4], np.uint32), np.array([1e8, 1.0, -1e8], np.float32))
+    assert O.scatter_add(9, *pad_lists([rep]))[4] == np.float32(0.0)
+
+
+def test_scatter_add_with_collisions_against_exact_and_sequential_sums():
+    rng = np.random.default_rng(32)
+    d, P, n = 3000, 16, 400
+    lists = []
+    for _ in range(P):
+        i = np.sort(rng.choice(d, n, replace=False)).astype(np.uint32)
+        lists.append((i, rng.integers(-1000, 1001, n).astype(np.float32)))
+    idx, val, nnz = pad_lists(lists)
+    # small integers: every partial sum is exact in fp32, so any order gives the exact sum
+    exact = np.zeros(d, np.int64)
+    for i, v in lists:
+        np.add.at(exact, i, v.astype(np.int64))
+    dense = O.scatter_add(d, idx, val, nnz)
+    assert np.array_equal(dense, exact.astype(np.float32))
+    assert (np.bincount(np.concatenate([i for i, _ in lists]), minlength=d) > 1).sum() > 500
+    # scale = 1/P, the average of Eq. (2): one fp32 multiplication of the finished sum
+    avg = O.scatter_add(d, idx, val, nnz, scale=1.0 / P)
+    assert np.array_equal(avg, exact.astype(np.float32) * np.float32(1.0 / P))
+    # rounding sums: numpy's unbuffered in-order accumulation in fp32, worker after worker
+    lists = [(i, (rng.standard_normal(i.size) * 10.0 ** rng.uniform(-6, 6, i.size)).astype(np.float32))
+             for i, _ in lists]
+    idx, val, nnz = pad_lists(lists)
+    want = np.zeros(d, np.float32)
+    for i, v in lists:
+        np.add.at(want, i, v)
+    dense = O.scatter_add(d, idx, val, nnz)
+    assert np.array_equal(dense.view(np.uint32), want.view(np.uint32))
+    third = np.float32(1.0 / 3.0)
+    assert np.array_equal(O.scatter_add(d, idx, val, nnz, scale=float(third)).view(np.uint32),
+                          (want * third).view(np.uint32))
+
+
+def test_scatter_add_rejects_indices_and_counts_out_of_range():
+    i, v = np.array([[1, 5]], np.uint32), np.array([[1.0, 2.0]], np.float32)
+    with pytest.raises(ValueError):
+        O.scatter_add(5, i, v, np.array([2], np.uint32))       # index 5 in a vector of 5
+    with pytest.raises(ValueError):
+        O.scatter_add(9, i, v, np.array([3], np.uint32))       # more pairs than the list holds
+    assert O.scatter_add(9, i, v, np.array([1], np.uint32))[5] == 0.0   # pairs beyond nnz are not read
