@@ -166,6 +166,34 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
                        int64_t out_cap, sparsify_result* results, void* workspace,
                        size_t workspace_bytes, const sparsify_opts* opts, void* stream);
 
+/* Decompression and aggregation: the sum over the P workers in Eq. (2),
+ *     dense = scale * sum_p Comp_k(acc_p),
+ * from the workers' compacted lists (as they sit in one buffer after an all-gather).
+ *   d            length of dense, 1 <= d < 2^31
+ *   num_lists    P, 1 <= P <= 1024
+ *   idx, val     uint32 / fp32 [P][list_stride], DEVICE: worker p's pairs are entries
+ *                p*list_stride + j, j < nnz of worker p.  Every list must be strictly ascending
+ *                in index (sparsify_gaussiank, sparsify_dgck and sparsify_topk with a separate
+ *                accumulator write their pairs that way) with indices below d.
+ *   nnz          DEVICE: worker p's pair count is the uint32 at byte offset p*nnz_stride_bytes
+ *                (4 for a plain array; sizeof(sparsify_result) to read the counts straight from an
+ *                array of result records, whose first field is nnz)
+ *   scale        every element is multiplied by it once at the end: 1 for the sum, 1/P for the
+ *                average that Eq. (2) applies
+ *   dense        fp32[d], out, 16-byte aligned: every element is written.  Element i starts at +0
+ *                and receives its contributions one fp32 addition at a time in worker order
+ *                (worker 0 first), so the result is reproducible bit for bit; no workspace, no
+ *                floating-point atomics
+ *   status       one uint32, out, DEVICE: 0, or bit 0 = some list is not strictly ascending or
+ *                holds an index >= d, bit 1 = some count exceeds list_stride (it is cut to
+ *                list_stride).  With a bit set the contents of dense are unspecified; nothing
+ *                outside dense is written whatever the lists hold.
+ * Argument errors (sizes, null or misaligned pointers, dense overlapping an input) return
+ * SPARSIFY_E_INVALID before anything is launched.  The call enqueues two kernels and returns. */
+int sparsify_scatter_add(int64_t d, int32_t num_lists, const uint32_t* idx, const float* val,
+                         int64_t list_stride, const uint32_t* nnz, int64_t nnz_stride_bytes,
+                         float scale, float* dense, uint32_t* status, void* stream);
+
 /* Optional per-kernel timing of one call (used by the benchmark for its roofline figure).
  * A trace owns HIP events (host objects, no device memory).  Pass it in sparsify_opts.trace;
  * after the stream has been synchronised, read the stages of the most recent traced call. */

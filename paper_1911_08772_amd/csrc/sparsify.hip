@@ -11,6 +11,7 @@
 #include "gaussiank.h"
 #include "gaussiank_flat.h"
 #include "gaussiank_seg.h"
+#include "scatter_add.h"
 #include "setup.h"
 #include "sparsify.h"
 #include "topk.h"
@@ -537,6 +538,51 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   }
   if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);
   return ln.err == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;
+}
+
+int sparsify_scatter_add(int64_t d, int32_t num_lists, const uint32_t* idx, const float* val,
+                         int64_t list_stride, const uint32_t* nnz, int64_t nnz_stride_bytes,
+                         float scale, float* dense, uint32_t* status, void* stream) {
+  if (d < 1 || d >= (int64_t(1) << 31) || num_lists < 1 || num_lists > kScatterMaxLists ||
+      list_stride < 1 || list_stride >= (int64_t(1) << 31))
+    return SPARSIFY_E_INVALID;
+  if (!idx || !val || !nnz || !dense || !status || nnz_stride_bytes < 4 || (nnz_stride_bytes & 3) != 0)
+    return SPARSIFY_E_INVALID;
+  if (misaligned(idx, 4) || misaligned(val, 4) || misaligned(nnz, 4) || misaligned(status, 4) ||
+      misaligned(dense, 16))
+    return SPARSIFY_E_INVALID;
+  const size_t pairs = (size_t)num_lists * (size_t)list_stride;
+  const Range rd = range_of(dense, 4 * (size_t)d);
+  const Range others[] = {range_of(idx, 4 * pairs), range_of(val, 4 * pairs),
+                          range_of(nnz, (size_t)(num_lists - 1) * (size_t)nnz_stride_bytes + 4),
+                          range_of(status, 4)};
+  for (const Range& r : others)
+    if (overlap(rd, r)) return SPARSIFY_E_INVALID;
+  if (overlap(others[3], others[0]) || overlap(others[3], others[1]) || overlap(others[3], others[2]))
+    return SPARSIFY_E_INVALID;
+
+  ScatterArgs a;
+  a.d = d;
+  a.P = num_lists;
+  a.idx = idx;
+  a.val = val;
+  a.stride = list_stride;
+  a.nnz = nnz;
+  a.nnz_step = nnz_stride_bytes / 4;
+  a.scale = scale;
+  a.dense = dense;
+  a.status = status;
+  // spans of whole chunks, few enough that all workgroups are resident together (their searches
+  // then overlap), many enough to fill the chip
+  const int64_t chunks = (d + kChunk - 1) / kChunk;
+  a.span_chunks = (uint32_t)((chunks + 2047) / 2048);
+  a.nspans = (uint32_t)((chunks + a.span_chunks - 1) / a.span_chunks);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  k_fill_u32<<<dim3(1), dim3(64), 0, st>>>(status, 1, 0u);
+  if (hipGetLastError() != hipSuccess) return SPARSIFY_E_LAUNCH;
+  k_scatter_add<<<dim3(kScatterCheckers + a.nspans), dim3(kBlock),
+                  sizeof(uint32_t) * scatter_table_words(num_lists), st>>>(a);
+  return hipGetLastError() == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;
 }
 
 int sparsify_calibration_copy(float* dst, const float* src, int64_t n, void* stream) {

@@ -44,6 +44,8 @@ lib.sparsify_gaussiank_static.argtypes = [C.c_int64, C.c_int64, _p, _p, _p, _p, 
                                           C.POINTER(Opts), _p]
 lib.sparsify_segmented.argtypes = [C.c_int32, C.c_int64, _p, _p, C.c_int32, _p, _p, _p, _p, _p,
                                    _p, C.c_int64, _p, _p, C.c_size_t, C.POINTER(Opts), _p]
+lib.sparsify_scatter_add.argtypes = [C.c_int64, C.c_int32, _p, _p, C.c_int64, _p, C.c_int64,
+                                     C.c_float, _p, _p, _p]
 lib.sparsify_calibration_copy.argtypes = [_p, _p, C.c_int64, _p]
 lib.sparsify_trace_create.restype = _p
 lib.sparsify_trace_destroy.argtypes = [_p]
@@ -54,7 +56,7 @@ lib.sparsify_trace_stage_name.restype = C.c_char_p
 lib.sparsify_trace_stage_ms.argtypes = [_p, C.c_int32, C.POINTER(C.c_float)]
 
 EXPORTS = ["sparsify_version", "sparsify_workspace_bytes", "sparsify_gaussiank", "sparsify_topk",
-           "sparsify_dgck", "sparsify_gaussiank_static",
+           "sparsify_dgck", "sparsify_gaussiank_static", "sparsify_scatter_add",
            "sparsify_segmented", "sparsify_calibration_copy", "sparsify_trace_create", "sparsify_trace_destroy",
            "sparsify_trace_num_stages", "sparsify_trace_stage_name", "sparsify_trace_stage_ms"]
 
@@ -187,6 +189,22 @@ def sparsify_segmented(num_segments, d_total, seg_off, seg_k, mode, grad, residu
                                 _ptr(workspace), workspace_nbytes, C.byref(o), _stream(stream))
     if check and rc != OK:
         raise SparsifyError(rc, "sparsify_segmented")
+    return rc
+
+
+SCATTER_F_BAD_LIST, SCATTER_F_BAD_COUNT = 1, 2
+SCATTER_MAX_LISTS = 1024
+
+
+def sparsify_scatter_add(d, num_lists, idx, val, list_stride, nnz, dense, status, scale=1.0,
+                         nnz_stride_bytes=4, stream=None, check=True) -> int:
+    """dense = scale * sum over the lists; `nnz` may point into an array of result records
+    (nnz_stride_bytes = RESULT_BYTES)."""
+    rc = lib.sparsify_scatter_add(d, num_lists, _ptr(idx), _ptr(val), list_stride, _ptr(nnz),
+                                  nnz_stride_bytes, float(scale), _ptr(dense), _ptr(status),
+                                  _stream(stream))
+    if check and rc != OK:
+        raise SparsifyError(rc, "sparsify_scatter_add")
     return rc
 
 

@@ -1,0 +1,160 @@
+"""GPU parity of sparsify_scatter_add (the sum over the workers in Eq. (2)) against the CPU
+oracle's plain loops: every element of the dense result bit for bit, including elements whose
+fp32 sum depends on the order of the workers."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_harness import DEV, progress, same_bits
+from oracle import oracle as O
+from paper_1911_08772_amd import sparsify as S
+from paper_1911_08772_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def random_lists(rng, d, P, counts, wide=False):
+    """P strictly ascending index lists with fp32 values; idx/val [P, stride], nnz [P]."""
+    stride = max(max(counts), 1) + int(rng.integers(0, 5))
+    idx = np.full((P, stride), 0xFFFFFFFF, np.uint32)   # padding: must never be applied
+    val = np.full((P, stride), np.nan, np.float32)
+    for p, n in enumerate(counts):
+        idx[p, :n] = np.sort(rng.choice(d, n, replace=False))
+        v = rng.standard_normal(n)
+        if wide:
+            v = v * 10.0 ** rng.uniform(-8, 8, n)
+        val[p, :n] = v.astype(np.float32)
+    return idx, val, np.asarray(counts, np.uint32)
+
+
+def gpu_scatter(d, idx, val, nnz, scale=1.0, guard=64):
+    """Runs the call on a dense buffer with guard words on both sides; returns (dense, status)."""
+    P, stride = idx.shape
+    buf = torch.full((d + 2 * guard,), 12345.0, dtype=torch.float32, device=DEV)
+    dense = buf[guard:guard + d]
+    status = torch.full((1,), 0x55, dtype=torch.int32, device=DEV)
+    S.sparsify_scatter_add(d, P, torch.from_numpy(idx.view(np.int32)).to(DEV),
+                           torch.from_numpy(val).to(DEV), stride,
+                           torch.from_numpy(nnz.view(np.int32)).to(DEV), dense, status, scale=scale)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert np.all(host[:guard] == 12345.0) and np.all(host[guard + d:] == 12345.0)
+    return host[guard:guard + d], int(status.cpu().numpy()[0])
+
+
+@pytest.mark.parametrize("d,P,per_list", [
+    (1, 1, 1), (1, 3, 1), (100, 2, 30), (4096, 16, 40), (4097, 16, 41), (8191, 5, 8191),
+    (100_003, 16, 100), (100_003, 17, 3000), (1_000_005, 40, 1000), (3_000_001, 16, 3000),
+    (20_000, 8, 5000),          # thousands of pairs per chunk: several register rounds
+    (50_000, 1024, 7),          # the largest number of lists
+    (9_000_000, 16, 9000),      # spans of several chunks
+])
+def test_matches_oracle(d, P, per_list):
+    rng = np.random.default_rng(d * 31 + P)
+    counts = [int(min(d, max(0, per_list + rng.integers(-per_list // 2, per_list // 2 + 1))))
+              for _ in range(P)]
+    counts[rng.integers(0, P)] = 0 if P > 1 else counts[0]    # a worker that sent nothing
+    for wide, scale in [(False, 1.0), (True, 1.0 / P), (True, -3.0)]:
+        idx, val, nnz = random_lists(rng, d, P, counts, wide)
+        want = O.scatter_add(d, idx, val, nnz, scale)
+        got, status = gpu_scatter(d, idx, val, nnz, scale)
+        assert status == 0
+        assert same_bits(got, want), (d, P, wide, scale, np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))[:5])
+
+
+def test_worker_order_decides_the_rounded_sum():
+    """Three workers hit one element with 1e8, -1e8, 1: worker order gives 1, any other order 0."""
+    d = 70_000
+    for where in (0, 4095, 4096, 69_999):
+        for order, want in [((1e8, -1e8, 1.0), 1.0), ((1e8, 1.0, -1e8), 0.0), ((1.0, 1e8, -1e8), 0.0)]:
+            idx = np.full((3, 4), where, np.uint32)
+            val = np.zeros((3, 4), np.float32)
+            val[:, 0] = order
+            nnz = np.ones(3, np.uint32)
+            got, status = gpu_scatter(d, idx, val, nnz)
+            assert status == 0 and got[where] == np.float32(want), (where, order, got[where])
+            assert same_bits(got, O.scatter_add(d, idx, val, nnz))
+
+
+def test_all_lists_empty_gives_zeros_and_counts_come_from_result_records():
+    d, P, stride = 10_001, 4, 50
+    idx = np.zeros((P, stride), np.uint32)
+    val = np.ones((P, stride), np.float32)
+    got, status = gpu_scatter(d, idx, val, np.zeros(P, np.uint32))
+    assert status == 0 and not got.view(np.uint32).any()
+    # nnz read straight from an array of result records (first field of each record)
+    rng = np.random.default_rng(5)
+    idx, val, nnz = random_lists(rng, d, P, [10, 0, 33, 50 - 4])
+    stride = idx.shape[1]
+    rec = np.zeros(P, S.RESULT_DTYPE)
+    rec["nnz"] = nnz
+    rec["rounds"] = 0xFFFFFFFF       # neighbours of the field must not be read as counts
+    dense = torch.empty(d, dtype=torch.float32, device=DEV)
+    status_t = torch.zeros(1, dtype=torch.int32, device=DEV)
+    S.sparsify_scatter_add(d, P, torch.from_numpy(idx.view(np.int32)).to(DEV),
+                           torch.from_numpy(val).to(DEV), stride,
+                           torch.from_numpy(rec.view(np.uint8)).to(DEV), dense, status_t,
+                           nnz_stride_bytes=S.RESULT_BYTES)
+    torch.cuda.synchronize()
+    assert int(status_t.cpu()[0]) == 0
+    assert same_bits(dense.cpu().numpy(), O.scatter_add(d, idx, val, nnz))
+
+
+def test_bad_lists_are_flagged_and_nothing_is_written_outside_dense():
+    rng = np.random.default_rng(6)
+    d, P = 50_000, 6
+    idx, val, nnz = random_lists(rng, d, P, [500] * P)
+    cases = []
+    a = idx.copy(); a[2, 100], a[2, 101] = a[2, 101], a[2, 100]; cases.append((a, nnz, S.SCATTER_F_BAD_LIST))
+    a = idx.copy(); a[4, 7] = a[4, 6]; cases.append((a, nnz, S.SCATTER_F_BAD_LIST))              # repeated index
+    a = idx.copy(); a[5, 499] = d; cases.append((a, nnz, S.SCATTER_F_BAD_LIST))                   # index == d
+    a = idx.copy(); a[0, 499] = 0xFFFFFFF0; cases.append((a, nnz, S.SCATTER_F_BAD_LIST))
+    n2 = nnz.copy(); n2[3] = idx.shape[1] + 1000; cases.append((idx, n2, S.SCATTER_F_BAD_COUNT | S.SCATTER_F_BAD_LIST))
+    a = rng.integers(0, 2 ** 32, idx.shape, dtype=np.uint64).astype(np.uint32)                   # garbage
+    cases.append((a, nnz, S.SCATTER_F_BAD_LIST))
+    for bad_idx, bad_nnz, want in cases:
+        _, status = gpu_scatter(d, bad_idx, val, bad_nnz)   # gpu_scatter checks the guard words
+        assert status & want == want and status & ~3 == 0, (status, want)
+    got, status = gpu_scatter(d, idx, val, nnz)             # and the status word is cleared again
+    assert status == 0 and same_bits(got, O.scatter_add(d, idx, val, nnz))
+
+
+@pytest.mark.parametrize("selector", ["gaussiank", "topk"])
+def test_aggregates_sixteen_workers_of_the_resnet50_sized_workload(selector):
+    """P = 16 workers each compress their own gradient of the ResNet-50-sized workload on the GPU;
+    their pair lists, as the compressor wrote them, are aggregated with scale 1/P and compared with
+    the oracle's loop over the same lists; run twice: the result is reproducible bit for bit."""
+    wl = synth.workload("cfg3_resnet50")
+    P, d, k = 16, wl.d, wl.k
+    cap = 4 * k
+    out_idx = torch.zeros((P, cap), dtype=torch.int32, device=DEV)
+    out_val = torch.zeros((P, cap), dtype=torch.float32, device=DEV)
+    results = torch.zeros((P, S.RESULT_BYTES), dtype=torch.uint8, device=DEV)
+    b = S.Buffers.allocate(d, cap, 1, False, DEV)
+    grad = torch.empty(d, dtype=torch.float32, device=DEV)
+    g = np.empty(d, np.float32)
+    fn = S.sparsify_gaussiank if selector == "gaussiank" else S.sparsify_topk
+    for p in range(P):
+        synth.normal(d, wl.seed + 100, p, 1e-3, out=g)      # worker p's own gradient
+        grad.copy_(torch.from_numpy(g))
+        b.residual.zero_()
+        fn(d, k, grad, b.residual, b.acc, out_idx[p], out_val[p], cap, results[p], b.workspace,
+           b.workspace_nbytes)
+    dense = torch.empty(d, dtype=torch.float32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    outs = []
+    for _ in range(2):
+        dense.fill_(float("nan"))
+        S.sparsify_scatter_add(d, P, out_idx, out_val, cap, results, dense, status, scale=1.0 / P,
+                               nnz_stride_bytes=S.RESULT_BYTES)
+        torch.cuda.synchronize()
+        assert int(status.cpu()[0]) == 0
+        outs.append(dense.cpu().numpy())
+    nnz = S.decode_results(results.reshape(-1))["nnz"].astype(np.uint32)
+    assert nnz.min() > 0
+    want = O.scatter_add(d, out_idx.cpu().numpy().view(np.uint32), out_val.cpu().numpy(), nnz,
+                         scale=1.0 / P)
+    assert same_bits(outs[0], want) and same_bits(outs[1], want)
+    hit = np.count_nonzero(want)
+    assert hit <= int(nnz.sum()) and hit > 0.9 * int(nnz.sum())
+    progress(f"scatter_add cfg3 {selector}: pairs={int(nnz.sum())} nonzero={hit}")

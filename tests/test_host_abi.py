@@ -127,3 +127,23 @@ def test_static_workspace_call_rejects_long_vectors_before_anything_else():
                                      check=False)
     assert rc == S.E_WORKSPACE
     assert S.workspace_bytes(S.STATIC_MAX_D, 1) <= 4 << 20 < S.workspace_bytes(2 * S.STATIC_MAX_D, 1)
+
+
+def test_scatter_add_rejects_bad_arguments_before_any_launch():
+    def rc(**over):
+        a = dict(d=1000, P=4, idx=BASE, val=BASE + (1 << 32), stride=64, nnz=BASE + (2 << 32),
+                 dense=BASE + (3 << 32), status=BASE + (4 << 32), nnz_stride_bytes=4)
+        a.update(over)
+        return S.sparsify_scatter_add(a["d"], a["P"], a["idx"], a["val"], a["stride"], a["nnz"],
+                                      a["dense"], a["status"], nnz_stride_bytes=a["nnz_stride_bytes"],
+                                      stream=0, check=False)
+    assert rc(d=0) == S.E_INVALID and rc(d=1 << 31) == S.E_INVALID
+    assert rc(P=0) == S.E_INVALID and rc(P=S.SCATTER_MAX_LISTS + 1) == S.E_INVALID
+    assert rc(stride=0) == S.E_INVALID
+    assert rc(idx=0) == S.E_INVALID and rc(val=0) == S.E_INVALID and rc(nnz=0) == S.E_INVALID
+    assert rc(dense=0) == S.E_INVALID and rc(status=0) == S.E_INVALID
+    assert rc(dense=BASE + (3 << 32) + 4) == S.E_INVALID          # dense must be 16-byte aligned
+    assert rc(nnz_stride_bytes=0) == S.E_INVALID and rc(nnz_stride_bytes=6) == S.E_INVALID
+    assert rc(dense=BASE + 64) == S.E_INVALID                     # dense overlaps the index lists
+    assert rc(dense=BASE + (1 << 32)) == S.E_INVALID              # dense is the value buffer
+    assert rc(status=BASE + (3 << 32) + 400) == S.E_INVALID       # status inside dense
