@@ -4,13 +4,17 @@ gradient vector (d = 25,557,032, rho = 0.001) on one MI355X.
 One step = one pass of the whole hot path on a fresh synthetic gradient already resident in
 HBM: accumulate, select (Algorithm 1), compact, residual, with the residual carried from step
 to step as in Eq. (2).  `value` is algorithmic GB/s of the Gaussian_k path (24 B per element +
-8 B per survivor); the exact Top_k path, timed the same way, is reported beside it.
+8 B per survivor); the exact Top_k path, timed the same way, is reported beside it, and under
+`also`: the same two selectors on the workloads that do not fit the last-level cache (LSTM-sized,
+66 M elements) or sit below the headline (VGG-16-sized), in place, layer-wise, the sampling
+comparator DGC_k, and the aggregation of 16 workers' lists (sparsify_scatter_add).
 
 Prints ONE JSON line.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -31,6 +35,168 @@ GK_INPLACE_BYTES_PER_ELEM = 20   # the compaction pass only reads acc (and zeroe
 TOPK_INPLACE_BYTES_PER_ELEM = 28  # no room for candidates: 12 + 3 full digit passes + r acc
 
 
+class Flat:
+    """One flat compressor instance on a pool of gradients resident in HBM (step s uses gradient
+    s modulo the pool size): timed chains and traced chains of W warm-up + K steps."""
+
+    def __init__(self, S, torch, wl, grads, K, W, inplace=False, tile_chunks=0):
+        self.S, self.torch, self.wl, self.grads, self.K, self.W = S, torch, wl, grads, K, W
+        self.d, self.k = wl.d, wl.k
+        self.cap = max(4 * wl.k, 1024)
+        self.tile_chunks = tile_chunks
+        self.b = S.Buffers.allocate(wl.d, self.cap, 1, inplace, "cuda:0")
+        self.stream = torch.cuda.current_stream()
+
+    def run(self, fn, s, trace=None, result=None):
+        b = self.b
+        fn(self.d, self.k, self.grads[s % len(self.grads)], b.residual, b.acc, b.out_idx, b.out_val,
+           self.cap, b.result if result is None else result, b.workspace, b.workspace_nbytes,
+           trace=trace, stream=self.stream, tile_chunks=self.tile_chunks)
+
+    def timed(self, fn):
+        """W warm-up steps then exactly K timed steps, bracketed by synchronisations; returns
+        (ms per step, wall ms per step, event ms per step)."""
+        torch, K, W = self.torch, self.K, self.W
+        self.b.residual.zero_()
+        for s in range(W):
+            self.run(fn, s)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(self.stream)
+        for s in range(W, W + K):
+            self.run(fn, s)
+        e1.record(self.stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        return max(wall_ms, e0.elapsed_time(e1)) / K, wall_ms / K, e0.elapsed_time(e1) / K
+
+    def traced(self, fn):
+        """The same chain again, back to back as in the timed run, with a HIP event on the stream
+        after every kernel (one trace and one result record per step, read after one final
+        synchronisation): average duration per kernel, nnz and rounds per step."""
+        S, torch, K, W = self.S, self.torch, self.K, self.W
+        traces = [S.Trace() for _ in range(K)]
+        records = torch.zeros((K, S.RESULT_BYTES), dtype=torch.uint8, device="cuda:0")
+        self.b.residual.zero_()
+        for s in range(W):
+            self.run(fn, s)
+        for i in range(K):
+            self.run(fn, W + i, trace=traces[i], result=records[i])
+        self.stream.synchronize()
+        sums, nnz, rounds = {}, [], []
+        for i in range(K):
+            for name, ms in traces[i].stages():
+                sums[name] = sums.get(name, 0.0) + ms
+            r = S.decode_results(records[i])[0]
+            nnz.append(int(r["nnz"]))
+            rounds.append(int(r["rounds"]))
+        return {n: v / K for n, v in sums.items()}, nnz, rounds
+
+    def spread(self, fn, repeats):
+        """The timed chain `repeats` more times: min and median of ms per step."""
+        xs = [self.timed(fn)[0] for _ in range(repeats)]
+        return {"repeats": repeats, "min_ms": round(min(xs), 5),
+                "median_ms": round(statistics.median(xs), 5), "max_ms": round(max(xs), 5)}
+
+
+def park_gradients(torch, wl, n):
+    """n fresh gradients of the workload, generated on the host and parked in HBM."""
+    import numpy as np
+    host = np.empty(wl.d, np.float32)
+    grads = [torch.empty(wl.d, dtype=torch.float32, device="cuda:0") for _ in range(n)]
+    for s in range(n):
+        wl.grad(s, out=host)
+        grads[s].copy_(torch.from_numpy(host))
+    torch.cuda.synchronize()
+    return grads
+
+
+def gbps(bytes_per_elem, d, nnz_mean, ms):
+    return (bytes_per_elem * d + 8.0 * nnz_mean) / (ms * 1e-3) / 1e9
+
+
+def dominant(stage, d):
+    """The streaming kernel with the longest average duration and its algorithmic GB/s."""
+    dom = max((n for n in stage if KERNEL_BYTES_PER_ELEM.get(n, 0) > 0), key=lambda n: stage[n])
+    nbytes = KERNEL_BYTES_PER_ELEM[dom] * d
+    return dom, nbytes, nbytes / (stage[dom] * 1e-3) / 1e9
+
+
+def side_workload(S, torch, synth, name, K, W):
+    """Gaussian_k and Top_k on another workload: a shorter chain, one fresh gradient per step."""
+    import numpy as np
+    wl = synth.workload(name)
+    pool = K + W
+    grads = park_gradients(torch, wl, pool)
+    f = Flat(S, torch, wl, grads, K, W)
+    gk_ms, _, _ = f.timed(S.sparsify_gaussiank)
+    gk_stage, gk_nnz, gk_rounds = f.traced(S.sparsify_gaussiank)
+    tk_ms, _, _ = f.timed(S.sparsify_topk)
+    tk_stage, _, _ = f.traced(S.sparsify_topk)
+    dom, nbytes, dom_gbps = dominant(gk_stage, wl.d)
+    g = gbps(GK_BYTES_PER_ELEM, wl.d, float(np.mean(gk_nnz)), gk_ms)
+    t = gbps(TOPK_BYTES_PER_ELEM, wl.d, float(wl.k), tk_ms)
+    out = {"workload": wl.describe(), "gradient_pool": pool, "steps": K, "warmup": W,
+           "working_set_MB": round(12 * wl.d / 1e6, 1),
+           "gaussiank": {"ms_per_step": round(gk_ms, 5), "GBps": round(g, 2),
+                         "pct_hbm_peak": round(100.0 * g / HBM_PEAK_GBPS, 2),
+                         "nnz_mean": float(np.mean(gk_nnz)), "rounds_mean": float(np.mean(gk_rounds)),
+                         "kernel_ms": {n: round(v, 5) for n, v in gk_stage.items()}},
+           "topk": {"ms_per_step": round(tk_ms, 5), "GBps": round(t, 2),
+                    "pct_hbm_peak": round(100.0 * t / HBM_PEAK_GBPS, 2),
+                    "kernel_ms": {n: round(v, 5) for n, v in tk_stage.items()}},
+           "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 2),
+                        "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
+                        "bytes_per_launch": nbytes, "avg_ms": round(gk_stage[dom], 5)}}
+    del f, grads
+    torch.cuda.empty_cache()
+    return out
+
+
+def scatter_add_bench(S, torch, wl, grads, K, W):
+    """Aggregation of P = 16 workers' Gaussian_k lists of this workload (each worker compresses
+    its own gradient with a zero residual), scale 1/P: ms per call and algorithmic GB/s
+    (4 bytes per element written + 8 bytes per pair read)."""
+    import numpy as np
+    P, d, k = 16, wl.d, wl.k
+    cap = max(4 * k, 1024)
+    b = S.Buffers.allocate(d, cap, 1, False, "cuda:0")
+    idx = torch.zeros((P, cap), dtype=torch.int32, device="cuda:0")
+    val = torch.zeros((P, cap), dtype=torch.float32, device="cuda:0")
+    rec = torch.zeros((P, S.RESULT_BYTES), dtype=torch.uint8, device="cuda:0")
+    for p in range(P):
+        b.residual.zero_()
+        S.sparsify_gaussiank(d, k, grads[p % len(grads)], b.residual, b.acc, idx[p], val[p], cap,
+                             rec[p], b.workspace, b.workspace_nbytes)
+    dense = torch.empty(d, dtype=torch.float32, device="cuda:0")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+
+    def call():
+        S.sparsify_scatter_add(d, P, idx, val, cap, rec, dense, status, scale=1.0 / P,
+                               nnz_stride_bytes=S.RESULT_BYTES, stream=stream)
+    for _ in range(W):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(K):
+        call()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / K
+    pairs = int(S.decode_results(rec.reshape(-1))["nnz"].sum())
+    nbytes = 4 * d + 8 * pairs
+    g = nbytes / (ms * 1e-3) / 1e9
+    return {"lists": P, "pairs": pairs, "scale": "1/16", "ms_per_call": round(ms, 5),
+            "bytes_per_call": nbytes, "GBps": round(g, 2), "status": int(status.cpu()[0]),
+            "roofline": {"bound": "hbm", "kernel": "scatter_add", "achieved": round(g, 2),
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(g / HBM_PEAK_GBPS, 4)},
+            "note": "4 B per element written + 8 B per pair read"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,10 +206,13 @@ def main() -> int:
     ap.add_argument("--inplace", action="store_true", help="acc aliases residual")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the in-place and layer-wise timings reported beside the headline")
+                    help="skip everything reported under `also` (other workloads, in place, layer-wise, "
+                         "DGC_k, scatter-add) and the repeats")
     ap.add_argument("--tile-chunks", type=int, default=0, help="tuning: 4096-element chunks per workgroup")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain copy kernel of 4d bytes each way (counter scaling)")
+    ap.add_argument("--gradient-pool", type=int, default=0,
+                    help="distinct gradients kept in HBM and cycled (default: one per step)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "
@@ -62,105 +231,43 @@ def main() -> int:
     dev = "cuda:0"
     wl = synth.workload(args.workload)
     d, k = wl.d, wl.k
-    cap = max(4 * k, 1024)
     K, W = args.steps, args.warmup
-    n_grads = K + W
+    n_grads = args.gradient_pool if args.gradient_pool > 0 else K + W
 
-    # fresh gradients, generated on the host and parked in HBM before any timing
-    host = np.empty(d, np.float32)
-    grads = [torch.empty(d, dtype=torch.float32, device=dev) for _ in range(n_grads)]
-    for s in range(n_grads):
-        wl.grad(s, out=host)
-        grads[s].copy_(torch.from_numpy(host))
-    torch.cuda.synchronize()
-
-    b = S.Buffers.allocate(d, cap, 1, args.inplace, dev)
-    stream = torch.cuda.current_stream()
-
-    def run(fn, s, trace=None, result=None):
-        fn(d, k, grads[s], b.residual, b.acc, b.out_idx, b.out_val, cap,
-           b.result if result is None else result, b.workspace,
-           b.workspace_nbytes, trace=trace, stream=stream, tile_chunks=args.tile_chunks)
-
-    def timed(fn):
-        """W warm-up steps then exactly K timed steps; returns (ms per step, nnz per step)."""
-        b.residual.zero_()
-        for s in range(W):
-            run(fn, s)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record(stream)
-        for s in range(W, W + K):
-            run(fn, s)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3
-        return max(wall_ms, e0.elapsed_time(e1)) / K, wall_ms / K, e0.elapsed_time(e1) / K
-
-    def traced(fn):
-        """The same chain again, back to back as in the timed run, with a HIP event on the stream
-        after every kernel (one trace and one result record per step, read after one final
-        synchronisation): average duration per kernel."""
-        traces = [S.Trace() for _ in range(K)]
-        records = torch.zeros((K, S.RESULT_BYTES), dtype=torch.uint8, device=dev)
-        b.residual.zero_()
-        for s in range(W):
-            run(fn, s)
-        for i in range(K):
-            run(fn, W + i, trace=traces[i], result=records[i])
-        stream.synchronize()
-        sums, nnz, rounds = {}, [], []
-        for i in range(K):
-            for name, ms in traces[i].stages():
-                sums[name] = sums.get(name, 0.0) + ms
-            r = S.decode_results(records[i])[0]
-            nnz.append(int(r["nnz"]))
-            rounds.append(int(r["rounds"]))
-        return {n: v / K for n, v in sums.items()}, nnz, rounds
+    grads = park_gradients(torch, wl, n_grads)   # before any timing
+    f = Flat(S, torch, wl, grads, K, W, args.inplace, args.tile_chunks)
+    cap, stream = f.cap, f.stream
 
     if args.calibration_copy:
         n4 = d - d % 4
         for _ in range(3):
-            S.sparsify_calibration_copy(b.acc, grads[0], n4, stream=stream)
+            S.sparsify_calibration_copy(f.b.acc, grads[0], n4, stream=stream)
         torch.cuda.synchronize()
 
-    gk_ms, gk_wall, gk_ev = timed(S.sparsify_gaussiank)
-    gk_stage, gk_nnz, gk_rounds = traced(S.sparsify_gaussiank)
-    tk_ms, tk_wall, tk_ev = timed(S.sparsify_topk)
-    tk_stage, tk_nnz, _ = traced(S.sparsify_topk)
+    gk_ms, gk_wall, gk_ev = f.timed(S.sparsify_gaussiank)
+    gk_stage, gk_nnz, gk_rounds = f.traced(S.sparsify_gaussiank)
+    tk_ms, tk_wall, tk_ev = f.timed(S.sparsify_topk)
+    tk_stage, tk_nnz, _ = f.traced(S.sparsify_topk)
+    gk_spread = tk_spread = None
+    if not args.no_extras:
+        gk_spread = f.spread(S.sparsify_gaussiank, 5)
+        tk_spread = f.spread(S.sparsify_topk, 5)
     dg = None
     if not args.inplace and not args.no_extras:  # the sampling comparator of Sec. 4.3 (1 % sample)
-        dg_ms, _, _ = timed(S.sparsify_dgck)
-        dg_stage, dg_nnz, dg_rounds = traced(S.sparsify_dgck)
+        dg_ms, _, _ = f.timed(S.sparsify_dgck)
+        dg_stage, dg_nnz, dg_rounds = f.traced(S.sparsify_dgck)
         dg = {"ms_per_step": round(dg_ms, 5), "nnz_mean": float(np.mean(dg_nnz)),
               "selections_mean": float(np.mean(dg_rounds)),
               "kernel_ms": {n: round(v, 5) for n, v in dg_stage.items()}}
 
-    def gbps(bytes_per_elem, nnz_mean, ms):
-        return (bytes_per_elem * d + 8.0 * nnz_mean) / (ms * 1e-3) / 1e9
-
     extras = {}
     if not args.no_extras:
         # the same chain with acc aliased to the residual (20 B per element)
-        bi = S.Buffers.allocate(d, cap, 1, True, dev)
-
-        def timed_inplace(fn):
-            bi.residual.zero_()
-            for s in range(W):
-                fn(d, k, grads[s], bi.residual, bi.acc, bi.out_idx, bi.out_val, cap, bi.result,
-                   bi.workspace, bi.workspace_nbytes, stream=stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for s in range(W, W + K):
-                fn(d, k, grads[s], bi.residual, bi.acc, bi.out_idx, bi.out_val, cap, bi.result,
-                   bi.workspace, bi.workspace_nbytes, stream=stream)
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) * 1e3 / K
-        extras["inplace"] = {"gaussiank_ms": round(timed_inplace(S.sparsify_gaussiank), 5),
-                             "topk_ms": round(timed_inplace(S.sparsify_topk), 5),
+        fi = Flat(S, torch, wl, grads, K, W, True)
+        extras["inplace"] = {"gaussiank_ms": round(fi.timed(S.sparsify_gaussiank)[1], 5),
+                             "topk_ms": round(fi.timed(S.sparsify_topk)[1], 5),
                              "note": "acc == residual: 20 B per element for Gaussian_k"}
-        del bi
+        del fi
         # layer-wise call: 54 segments of the same total length, one launch sequence per step
         if wl.d == 25_557_032:
             seg = synth.workload("cfg4_segmented")
@@ -178,7 +285,7 @@ def main() -> int:
                     if s == W:
                         torch.cuda.synchronize()
                         t0 = time.perf_counter()
-                    S.sparsify_segmented(L, d, d_off, d_k, mode, grads[s], bs.residual, bs.acc,
+                    S.sparsify_segmented(L, d, d_off, d_k, mode, grads[s % n_grads], bs.residual, bs.acc,
                                          bs.out_idx, bs.out_val, d_oo, ocap, bs.result, bs.workspace,
                                          bs.workspace_nbytes, stream=stream)
                 torch.cuda.synchronize()
@@ -187,34 +294,41 @@ def main() -> int:
                                       "topk_ms": round(timed_seg(0), 5),
                                       "note": "cfg4 layout (54 segments) on the same gradients"}
             del bs
+        extras["scatter_add"] = scatter_add_bench(S, torch, wl, grads, K, W)
 
     gk_bpe = GK_INPLACE_BYTES_PER_ELEM if args.inplace else GK_BYTES_PER_ELEM
     tk_bpe = TOPK_INPLACE_BYTES_PER_ELEM if args.inplace else TOPK_BYTES_PER_ELEM
-    gk_gbps = gbps(gk_bpe, float(np.mean(gk_nnz)), gk_ms)
-    tk_gbps = gbps(tk_bpe, float(k), tk_ms)
+    gk_gbps = gbps(gk_bpe, d, float(np.mean(gk_nnz)), gk_ms)
+    tk_gbps = gbps(tk_bpe, d, float(k), tk_ms)
+    dom, dom_bytes, dom_gbps = dominant(gk_stage, d)
+    traffic, traffic_source = read_traffic(args.workload, dom)
 
-    dom = max((n for n in gk_stage if KERNEL_BYTES_PER_ELEM.get(n, 0) > 0), key=lambda n: gk_stage[n])
-    dom_bytes = KERNEL_BYTES_PER_ELEM[dom] * d
-    dom_gbps = dom_bytes / (gk_stage[dom] * 1e-3) / 1e9
-    traffic = read_traffic(args.workload, dom)
+    if not args.no_extras and args.workload == "cfg3_resnet50":
+        # the workloads beside the headline: beyond the last-level cache, and below the headline size
+        del f, grads
+        torch.cuda.empty_cache()
+        for name in ("cfg5_lstm", "cfg2_vgg16"):
+            extras[name] = side_workload(S, torch, synth, name, min(K, 8), min(W, 2))
 
     out = {
         "metric": "Gaussian-k sparsify GB/s (algorithmic bytes) at d=25.6M, rho=0.001; exact Top-k beside it",
         "value": round(gk_gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(gk_ms, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: d={d}, k={k}, g~N(0,1e-3) seeded, residual carried",
-                   "acc": "in-place" if args.inplace else "separate", "cap": cap},
+        "config": {"workload": wl.describe() + ", residual carried",
+                   "acc": "in-place" if args.inplace else "separate", "cap": cap,
+                   "gradient_pool": n_grads},
         "elements_per_s": round(d / (gk_ms * 1e-3), 1),
         "pct_hbm_peak": round(100.0 * gk_gbps / HBM_PEAK_GBPS, 2),
         "gaussiank": {"ms_per_step": round(gk_ms, 5), "wall_ms": round(gk_wall, 5),
                       "event_ms": round(gk_ev, 5), "bytes_per_elem": gk_bpe,
                       "nnz_mean": float(np.mean(gk_nnz)), "rounds_mean": float(np.mean(gk_rounds)),
+                      "spread": gk_spread,
                       "kernel_ms": {n: round(v, 5) for n, v in gk_stage.items()}},
         "topk": {"ms_per_step": round(tk_ms, 5), "GBps": round(tk_gbps, 2),
                  "elements_per_s": round(d / (tk_ms * 1e-3), 1),
                  "pct_hbm_peak": round(100.0 * tk_gbps / HBM_PEAK_GBPS, 2),
-                 "bytes_per_elem": tk_bpe,
+                 "bytes_per_elem": tk_bpe, "spread": tk_spread,
                  # context only (Sec. 3.3: a tensor library's topk() on a Tesla V100, same d and k)
                  "paper_v100_ms": 400.0 if (wl.d == 25_557_032 and k == 25_558) else None,
                  "kernel_ms": {n: round(v, 5) for n, v in tk_stage.items()}},
@@ -224,6 +338,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_source": traffic_source,
                      "bytes_per_launch": dom_bytes, "avg_ms": round(gk_stage[dom], 5)},
     }
 
@@ -235,15 +350,23 @@ def main() -> int:
 
 def read_traffic(workload: str, kernel: str):
     """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this
-    workload (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel), or None."""
-    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.txt")
+    workload (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel) and where the figure comes
+    from: it is a profile of the committed kernels, not a counter read during this run.  None when
+    there is no summary, or when the library's sources are newer than it."""
+    rel = os.path.join("profiles", f"bench_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, rel)
     try:
+        csrc = os.path.join(ROOT, "paper_1911_08772_amd", "csrc")
+        newest = max(os.path.getmtime(os.path.join(csrc, f)) for f in os.listdir(csrc))
         for line in open(path):
             if line.startswith(f"traffic kernel={kernel} "):
-                return float(line.split("bytes_per_launch=")[1])
-    except OSError:
+                value = float(line.split("bytes_per_launch=")[1])
+                if os.path.getmtime(path) < newest:
+                    return value, f"{rel} (committed rocprofv3 --pmc summary; older than the kernel sources)"
+                return value, f"{rel} (committed rocprofv3 --pmc summary, not measured in this run)"
+    except (OSError, ValueError):
         pass
-    return None
+    return None, None
 
 
 def cpu_baseline(wl, cap):

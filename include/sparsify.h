@@ -184,12 +184,14 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
  *                and receives its contributions one fp32 addition at a time in worker order
  *                (worker 0 first), so the result is reproducible bit for bit; no workspace, no
  *                floating-point atomics
- *   status       one uint32, out, DEVICE: 0, or bit 0 = some list is not strictly ascending or
- *                holds an index >= d, bit 1 = some count exceeds list_stride (it is cut to
- *                list_stride).  With a bit set the contents of dense are unspecified; nothing
- *                outside dense is written whatever the lists hold.
+ *   status       one uint32, DEVICE, sticky: the call ORs bits into it and never clears it (the
+ *                caller zeroes it once, and again after reading a set bit).  Bit 0 = some list is
+ *                not strictly ascending or holds an index >= d, bit 1 = some count exceeds
+ *                list_stride (it is cut to list_stride).  A call that sets a bit leaves the
+ *                contents of dense unspecified; nothing outside dense is written whatever the
+ *                lists hold.
  * Argument errors (sizes, null or misaligned pointers, dense overlapping an input) return
- * SPARSIFY_E_INVALID before anything is launched.  The call enqueues two kernels and returns. */
+ * SPARSIFY_E_INVALID before anything is launched.  The call enqueues one kernel and returns. */
 int sparsify_scatter_add(int64_t d, int32_t num_lists, const uint32_t* idx, const float* val,
                          int64_t list_stride, const uint32_t* nnz, int64_t nnz_stride_bytes,
                          float scale, float* dense, uint32_t* status, void* stream);

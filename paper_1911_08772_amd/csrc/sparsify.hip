@@ -578,8 +578,6 @@ int sparsify_scatter_add(int64_t d, int32_t num_lists, const uint32_t* idx, cons
   a.span_chunks = (uint32_t)((chunks + 2047) / 2048);
   a.nspans = (uint32_t)((chunks + a.span_chunks - 1) / a.span_chunks);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  k_fill_u32<<<dim3(1), dim3(64), 0, st>>>(status, 1, 0u);
-  if (hipGetLastError() != hipSuccess) return SPARSIFY_E_LAUNCH;
   k_scatter_add<<<dim3(kScatterCheckers + a.nspans), dim3(kBlock),
                   sizeof(uint32_t) * scatter_table_words(num_lists), st>>>(a);
   return hipGetLastError() == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;

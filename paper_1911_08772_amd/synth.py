@@ -90,6 +90,15 @@ class Workload:
     def k(self) -> int:
         return k_of(self.d, self.rho_den)
 
+    def describe(self) -> str:
+        """One line naming the sizes and the gradient recipe (for benchmark records)."""
+        recipe = {"normal": lambda: f"g~N(0, sigma={self.params[0]:g})",
+                  "mixture": lambda: (f"g~N(0, {self.params[0]:g}) w.p. {1 - self.params[2]:g}, "
+                                      f"N(0, {self.params[1]:g}) w.p. {self.params[2]:g} per element"),
+                  "student_t3": lambda: f"g={self.params[0]:g}*Student-t(3)",
+                  "segmented_normal": lambda: "per-segment N(0, sigma_l), sigma_l log-uniform"}
+        return f"{self.name}: d={self.d}, k={self.k}, {recipe[self.dist]()} seeded"
+
     def grad(self, step: int, out: Optional[np.ndarray] = None) -> np.ndarray:
         """Fresh gradient of iteration `step` (stream = step)."""
         if self.dist == "normal":

@@ -32,7 +32,7 @@ def gpu_scatter(d, idx, val, nnz, scale=1.0, guard=64):
     P, stride = idx.shape
     buf = torch.full((d + 2 * guard,), 12345.0, dtype=torch.float32, device=DEV)
     dense = buf[guard:guard + d]
-    status = torch.full((1,), 0x55, dtype=torch.int32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)   # sticky word: the caller clears it
     S.sparsify_scatter_add(d, P, torch.from_numpy(idx.view(np.int32)).to(DEV),
                            torch.from_numpy(val).to(DEV), stride,
                            torch.from_numpy(nnz.view(np.int32)).to(DEV), dense, status, scale=scale)
@@ -48,6 +48,7 @@ def gpu_scatter(d, idx, val, nnz, scale=1.0, guard=64):
     (20_000, 8, 5000),          # thousands of pairs per chunk: several register rounds
     (50_000, 1024, 7),          # the largest number of lists
     (9_000_000, 16, 9000),      # spans of several chunks
+    (9_000_000, 3, 3_000_000),  # spans of several chunks and several register rounds
 ])
 def test_matches_oracle(d, P, per_list):
     rng = np.random.default_rng(d * 31 + P)
@@ -115,8 +116,17 @@ def test_bad_lists_are_flagged_and_nothing_is_written_outside_dense():
     for bad_idx, bad_nnz, want in cases:
         _, status = gpu_scatter(d, bad_idx, val, bad_nnz)   # gpu_scatter checks the guard words
         assert status & want == want and status & ~3 == 0, (status, want)
-    got, status = gpu_scatter(d, idx, val, nnz)             # and the status word is cleared again
+    got, status = gpu_scatter(d, idx, val, nnz)             # good lists again: nothing raised
     assert status == 0 and same_bits(got, O.scatter_add(d, idx, val, nnz))
+    # the word is sticky: a good call after a bad one leaves the bit standing
+    sticky = torch.zeros(1, dtype=torch.int32, device=DEV)
+    dense = torch.empty(d, dtype=torch.float32, device=DEV)
+    for these in (cases[0][0], idx):
+        S.sparsify_scatter_add(d, P, torch.from_numpy(these.view(np.int32)).to(DEV),
+                               torch.from_numpy(val).to(DEV), idx.shape[1],
+                               torch.from_numpy(nnz.view(np.int32)).to(DEV), dense, sticky)
+    torch.cuda.synchronize()
+    assert int(sticky.cpu()[0]) == S.SCATTER_F_BAD_LIST
 
 
 @pytest.mark.parametrize("selector", ["gaussiank", "topk"])
