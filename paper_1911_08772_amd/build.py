@@ -62,6 +62,9 @@ def ensure_synth() -> str:
 def ensure_sparsify() -> str:
     """Path of the built HIP library; (re)builds it when it is missing or older than any of its
     sources, so that a test run never silently exercises the binary of an earlier edit."""
+    other = os.environ.get("SPARSIFY_LIBRARY")  # another build of the same sources (a debug build, say)
+    if other:
+        return other
     if _stale(LIB_SPARSIFY, _sparsify_sources()):
         build_sparsify()
     return LIB_SPARSIFY
