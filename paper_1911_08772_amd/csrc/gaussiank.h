@@ -84,6 +84,43 @@ __device__ inline void accum_moments_chunk(const Args& a, const Tile& t, MomAcc&
   }
 }
 
+// The same for a full chunk in two halves, so that a caller can have the next chunk's loads in
+// flight while it works on this one: `accum_issue` only issues the eight 16-byte loads.
+struct AccIn {
+  float g[kPerThread], e[kPerThread];
+};
+__device__ inline Tile full_chunk_at(int64_t tbase) {
+  Tile t;
+  t.seg = 0;
+  t.tbase = tbase;
+  t.lo = tbase;
+  t.hi = tbase + kChunk;
+  t.full = true;
+  return t;
+}
+__device__ inline void accum_issue(const Args& a, int64_t tbase, AccIn& in) {
+  const Tile t = full_chunk_at(tbase);
+  load_tile<true, true>(a.grad, t, in.g);
+  load_tile<true>(a.resid, t, in.e);
+}
+__device__ inline void accum_finish(const Args& a, int64_t tbase, AccIn& in, MomAcc& m) {
+  const Tile t = full_chunk_at(tbase);
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) in.g[i] = in.g[i] + in.e[i];  // Eq. (2): one fp32 add
+  store_tile<true>(a.acc, t, in.g, 0xFFFFu);
+  if (!m.have_pivot) {  // wave-uniform: the first element the wave meets
+    m.pivot = (double)__shfl(in.g[0], 0, 64);
+    m.have_pivot = true;
+  }
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    const double c = (double)in.g[i] - m.pivot;
+    m.s1 += c;
+    m.s2 = fma(c, c, m.s2);
+  }
+  m.n += (double)kPerThread;
+}
+
 // Combines the four waves' shifted sums around the first wave's pivot (no merge divisions) and
 // stores the workgroup's (n, mean, M2) as partial `slot`.
 __device__ inline void store_moment_partial(const Args& a, const MomAcc& m, uint32_t slot,
@@ -545,12 +582,14 @@ __device__ inline uint32_t compact_values(const Args& a, const Tile& t, float (&
   return run + total;
 }
 
-template <bool FULL, bool NORMS>
+// STREAM: acc is read with the non-temporal hint (its last use in the call); the host picks by
+// the vector length.
+template <bool FULL, bool NORMS, bool STREAM = false>
 __device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr, bool none,
                                          int64_t out0, uint32_t run, uint32_t* lds,
                                          NormAcc& norms) {
   float v[kPerThread];
-  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+  const uint32_t valid = load_tile<FULL, STREAM>(a.acc, t, v);
   return compact_values<FULL, NORMS>(a, t, v, valid, thr, none, out0, run, lds, norms);
 }
 

@@ -38,16 +38,48 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_fused(const Args a) {
     return;
   }
   const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  const uint32_t nfull = (uint32_t)(a.d_total / kChunk);
+  const uint32_t step = a.moment_parts;
   MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
-  for (uint32_t ch = blockIdx.x; ch < nchunks; ch += a.moment_parts) {
+  // Full chunks, two register sets in turn: the loads of the workgroup's next chunk are issued
+  // before this chunk's additions, stores and fp64 sums, so that with one workgroup per compute
+  // unit the memory pipes still have the next 32 KiB on order while this one is worked on.
+  // (No load sits behind a branch inside the loop: where two paths meet, the wait for the
+  // oldest loads is placed for the path with the fewest in flight, and that would drain the
+  // other path's prefetch.)
+  const uint32_t n = blockIdx.x < nfull ? (nfull - blockIdx.x + step - 1) / step : 0u;  // my full chunks
+  auto at = [&](uint32_t k) { return (int64_t)(blockIdx.x + k * step) * kChunk; };
+  if (n > 0) {
+    AccIn x, y;
+    uint32_t k = 0;
+    accum_issue(a, at(0), x);
+    while (k + 2 < n) {
+      accum_issue(a, at(k + 1), y);
+      __builtin_amdgcn_sched_barrier(0);  // nothing of the work below moves above the loads
+      accum_finish(a, at(k), x, m);
+      accum_issue(a, at(k + 2), x);
+      __builtin_amdgcn_sched_barrier(0);
+      accum_finish(a, at(k + 1), y, m);
+      k += 2;
+    }
+    if (n - k == 2) {
+      accum_issue(a, at(k + 1), y);
+      __builtin_amdgcn_sched_barrier(0);
+      accum_finish(a, at(k), x, m);
+      accum_finish(a, at(k + 1), y, m);
+    } else {
+      accum_finish(a, at(k), x, m);
+    }
+  }
+  // the ragged last chunk, if there is one, belongs to the workgroup whose turn it is
+  if (nfull < nchunks && nfull % step == blockIdx.x) {
     Tile t;
     t.seg = 0;
-    t.tbase = (int64_t)ch * kChunk;
+    t.tbase = (int64_t)nfull * kChunk;
     t.lo = t.tbase;
-    t.hi = (t.tbase + kChunk < a.d_total) ? t.tbase + kChunk : a.d_total;
-    t.full = t.tbase + kChunk <= a.d_total;
-    if (t.full) accum_moments_chunk<true>(a, t, m);
-    else accum_moments_chunk<false>(a, t, m);
+    t.hi = a.d_total;
+    t.full = false;
+    accum_moments_chunk<false>(a, t, m);
   }
   store_moment_partial(a, m, blockIdx.x, lds);
 }
@@ -226,7 +258,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
 
 // K5: every workgroup totals the group counts, walks Alg. 1 steps 5-13, finds the first output
 // slot of its tile (groups before its own + tiles before it inside its group), then compacts.
-template <bool NORMS, int GT, int MG>  // tiles per group, groups at most
+template <bool NORMS, int GT, int MG, bool STREAM>  // tiles per group, groups at most, non-temporal reads
 __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   __shared__ uint32_t lds_g[MG * kNumThres];    // group totals [group][threshold]
   __shared__ uint32_t lds_t[GT * kNumThres];    // counts of my group's tiles [threshold][tile]
@@ -300,8 +332,8 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    if (t.full) run = compact_chunk<true, NORMS>(a, t, thr, overflow, out0, run, lds, norms);
-    else run = compact_chunk<false, NORMS>(a, t, thr, overflow, out0, run, lds, norms);
+    if (t.full) run = compact_chunk<true, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
+    else run = compact_chunk<false, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
   }
   if (NORMS) store_norm_partial(a, norms, tile, lds_n);
 }

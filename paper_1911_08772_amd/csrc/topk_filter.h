@@ -284,12 +284,12 @@ struct OrderedSel {
   bool rank_ties, none;
   int64_t out0, cap;
 };
-template <bool FULL, bool NORMS>
+template <bool FULL, bool NORMS, bool STREAM = false>  // STREAM: see compact_chunk
 __device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, const OrderedSel& o,
                                              uint32_t& out_run, uint32_t& tie_run,
                                              uint32_t* lds, NormAcc& norms) {
   float v[kPerThread];
-  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
+  const uint32_t valid = load_tile<FULL, STREAM>(a.acc, t, v);
   const uint32_t T = o.T, take = o.take;
   const bool rank_ties = o.rank_ties;
   uint32_t sel = 0, eq = 0;
@@ -344,7 +344,7 @@ __device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, const
   __syncthreads();  // lds is reused by the next chunk
 }
 
-template <bool NORMS, int GT, int MG>  // tiles per group, groups at most
+template <bool NORMS, int GT, int MG, bool STREAM>  // tiles per group, groups at most, non-temporal reads
 __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ uint32_t lds_base[2];
@@ -388,8 +388,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    if (t.full) ordered_compact_chunk<true, NORMS>(a, t, o, out_run, tie_run, lds, norms);
-    else ordered_compact_chunk<false, NORMS>(a, t, o, out_run, tie_run, lds, norms);
+    if (t.full) ordered_compact_chunk<true, NORMS, STREAM>(a, t, o, out_run, tie_run, lds, norms);
+    else ordered_compact_chunk<false, NORMS, STREAM>(a, t, o, out_run, tie_run, lds, norms);
   }
   if (NORMS) store_norm_partial(a, norms, tile, lds_n);
 }

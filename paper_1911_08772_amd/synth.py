@@ -150,6 +150,8 @@ def workload(name: str) -> Workload:
                         seg_k)
     if name == "cfg5_lstm":
         return Workload(name, 66_034_000, 1000, 100, "student_t3", (1e-3,), BASE_SEED + 5)
+    if name.startswith("normal_d"):  # e.g. normal_d41943040: the d-sweep's vectors as a chain
+        return Workload(name, int(name[len("normal_d"):]), 1000, 20, "normal", (1e-3,), BASE_SEED + 9)
     raise KeyError(name)
 
 
