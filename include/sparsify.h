@@ -19,8 +19,8 @@
  *   Between its first and its last kernel a call may use `residual` (when it is not `acc`)
  *   as scratch: its contents are defined again only when the call's work has completed.
  * Sizes.  1 <= k <= d < 2^31.  Indices are uint32 positions in the flat buffer.
- * Output order.  Gaussian_k pairs come out in ascending index order; Top_k pairs in
- *   unspecified order (treat them as a set).  Entries beyond `nnz` are not written.
+ * Output order.  Every selector writes its pairs in ascending index order (per segment in the
+ *   layer-wise call), the same from run to run.  Entries beyond `nnz` are not written.
  * Errors.  Argument errors that the host can see return a non-zero sparsify_status before
  *   anything is launched and touch no buffer.  Data-dependent conditions are reported in
  *   sparsify_result.flags, never by the return code.
@@ -111,7 +111,7 @@ int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual,
 /* sparsify_gaussiank for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, results and errors as sparsify_gaussiank except that there is no workspace
- * argument: the partial results live in a 4 MiB array built into the library (one copy per GPU,
+ * argument: the partial results live in a 6 MiB array built into the library (one copy per GPU,
  * held until the process ends), which limits d to 2^27 = 134,217,728 elements; a larger d returns
  * SPARSIFY_E_WORKSPACE before anything is launched.  The call allocates nothing and frees
  * nothing.  The array keeps the previous call's contents (the kernels rewrite what they read) and
@@ -173,8 +173,8 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
  *   num_lists    P, 1 <= P <= 1024
  *   idx, val     uint32 / fp32 [P][list_stride], DEVICE: worker p's pairs are entries
  *                p*list_stride + j, j < nnz of worker p.  Every list must be strictly ascending
- *                in index (sparsify_gaussiank, sparsify_dgck and sparsify_topk with a separate
- *                accumulator write their pairs that way) with indices below d.
+ *                in index (every compressor of this library writes its pairs that way) with
+ *                indices below d.
  *   nnz          DEVICE: worker p's pair count is the uint32 at byte offset p*nnz_stride_bytes
  *                (4 for a plain array; sizeof(sparsify_result) to read the counts straight from an
  *                array of result records, whose first field is nnz)

@@ -49,7 +49,6 @@ struct SegCtrl {
   uint32_t k_rem;           // survivors still to take among keys matching the prefix
   uint32_t n_eq;            // number of keys equal to the k-th key
   uint32_t rank_ties;       // 1 if only some of the equal keys are kept (needs index order)
-  uint32_t cursor;          // output slots handed out so far (starts after the ordered part)
   uint32_t sel_prefix[8];   // fused flat paths: prefix and rank left after each digit choice
   uint32_t sel_krem[8];     //   (one slot per choice: a kernel reads one slot and writes the next)
   uint32_t topk_key;        // fused flat paths: the k-th key and the ties to keep
@@ -85,6 +84,7 @@ struct Args {
   double* norm_partial;   // [2][max_tiles]: per-tile sum of acc^2 and of residual'^2
   uint32_t* hist;         // [L][hist_copies][256]
   uint32_t* tie_base;     // [max_tiles]
+  uint32_t* tile_hist;    // [up to 4096 tiles][128]: per-tile histogram of the last digit (Top_k in place)
   uint32_t hist_copies;   // replicas of each segment's histogram (spreads the atomics)
   uint32_t max_tiles;
   uint32_t tile_chunks;   // chunks per tile

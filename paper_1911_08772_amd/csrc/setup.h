@@ -44,7 +44,6 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_flat(const Args a) {
     c.k_rem = (uint32_t)a.flat_k;
     c.n_eq = 0;
     c.rank_ties = 0;
-    c.cursor = 0;
     c.select_none = 0;
     c.bad = 0;
     sparsify_result& r = a.result[0];
@@ -139,7 +138,6 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
       c.k_rem = (uint32_t)k;
       c.n_eq = 0;
       c.rank_ties = 0;
-      c.cursor = 0;
       c.select_none = 0;
       c.t_final = 0.0f;
       sparsify_result& r = a.result[s];

@@ -26,8 +26,8 @@ using namespace sp;
 // One copy per GPU the library runs on, held until the process ends.  In host code the array's
 // name is only a handle for the runtime's symbol lookup: the device address is looked up once per
 // device (static_scratch below) and that pointer is what the kernels receive.
-constexpr size_t kStaticScratchBytes = size_t(4) << 20;
-constexpr int64_t kStaticMaxD = int64_t(1) << 27;  // workspace of 2^27 elements: 3.06 MiB
+constexpr size_t kStaticScratchBytes = size_t(6) << 20;
+constexpr int64_t kStaticMaxD = int64_t(1) << 27;  // workspace of 2^27 elements: 5.06 MiB
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // ---- per-kernel timing (optional) -----------------------------------------------------------
@@ -107,7 +107,7 @@ uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 
 
 struct Carve {
   size_t ctrl, tile_start, partial, folded, tile_counts, tile_base, tie_base, group_counts, seg_groups,
-      norm_partial, hist, total;
+      norm_partial, hist, tile_hist, total;
   uint32_t max_groups;
 };
 Carve carve(int64_t d_total, int32_t L) {
@@ -129,6 +129,9 @@ Carve carve(int64_t d_total, int32_t L) {
   size_t hist_words = (size_t)kDigits * 256 * (size_t)L * hist_copies_of(L);  // [pass][segment][replica]
   if (hist_words < (size_t)kDgcHistWords) hist_words = kDgcHistWords;  // per-pass buffers (flat): 4 or 8
   c.hist = off;        off = align_up(off + sizeof(uint32_t) * hist_words);
+  // per-tile histograms of the last digit: flat Top_k in place, at most kFusedMaxTiles tiles
+  const size_t hist_tiles = mt < (size_t)kFusedMaxTiles ? mt : (size_t)kFusedMaxTiles;
+  c.tile_hist = off;   off = align_up(off + sizeof(uint32_t) * kLastDigitBins * hist_tiles);
   c.total = off;
   return c;
 }
@@ -203,6 +206,7 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.norm_partial = reinterpret_cast<double*>(w + cv.norm_partial);
   a.norms = (opts && opts->error_norms) ? 1 : 0;
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
+  a.tile_hist = reinterpret_cast<uint32_t*>(w + cv.tile_hist);
   a.hist_copies = hist_copies_of(L);
   a.tile_chunks = tile_chunks_of(d_total, false);
   if (opts && opts->tile_chunks != 0) {
@@ -358,12 +362,12 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
     ln.run("topk_hist1", k_topk_hist_fused<false>, pg, blk, a, 1);
     ln.run("topk_hist2", k_topk_hist_fused<false>, pg, blk, a, 2);
     ln.run("topk_hist3", k_topk_hist_fused<true>, pg, blk, a, 3);
-    ln.run("topk_ties", k_topk_ties_fused, pg, blk, a);
+    ln.run("topk_ties", k_topk_ties_fused, dim3((tiles + kWaves - 1) / kWaves), blk, a);
     if (a.norms) {
-      ln.run("topk_compact", k_topk_compact_fused<true>, pg, blk, a);
+      ln.run("topk_compact", k_topk_compact_ordered<true, kGroupTiles, kMaxGroups, false>, pg, blk, a);
       ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
     } else {
-      ln.run("topk_compact", k_topk_compact_fused<false>, pg, blk, a);
+      ln.run("topk_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups, false>, pg, blk, a);
     }
     return;
   }

@@ -2,15 +2,16 @@
 // passes (8, 8, 8, 7 bits, most significant first) with per-wave histograms in LDS, a digit
 // choice after each pass, then compaction of {key > T} plus the lowest-index ties.  This file
 // holds the building blocks (digit layout, histogram flush, the accumulate kernel with the first
-// digit's histogram, tie counting, one chunk of the cursor-based compaction) and the general
-// twelve-launch form with one single-workgroup "select" kernel per segment after each pass; it
-// serves layer-wise calls in place and flat calls whose forced tiling exceeds the fused forms'
-// tables.  The forms normally used are in topk_filter.h (flat), topk_seg.h (layer-wise) and
-// topk_flat.h (flat, in place).
+// digit's histogram, one chunk of the ordered compaction) and the general twelve-launch form with
+// one single-workgroup "select" kernel per segment after each pass, one more pass over acc that
+// counts every tile's survivors and ties once the k-th key T is known, and a per-segment scan of
+// those counts; it serves layer-wise calls in place and flat calls whose forced tiling exceeds
+// the fused forms' tables.  The forms normally used are in topk_filter.h (flat), topk_seg.h
+// (layer-wise) and topk_flat.h (flat, in place).
 // Global atomics on one address cost tens of nanoseconds each on this chip, so the global
-// histogram is replicated and the output slots of the bulk of the survivors come from a scan of
-// per-tile counts; only the few survivors that share the k-th key's leading 24 bits take their
-// slots from an atomic cursor.
+// histogram is replicated, and every survivor's output slot comes from counts (per-tile counts,
+// scanned or totalled per group): no output cursor anywhere, so the pairs of every form come
+// out in ascending index order, the same from run to run.
 #pragma once
 #include "common.h"
 #include "gaussiank.h"
@@ -127,12 +128,10 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(const Args a, int pass) {
 
 // ---- T2: per segment, pick the digit holding the k_rem-th largest key ------------------------
 // One workgroup of kFinBlock threads per segment; the first 256 threads own one bin each, in
-// descending digit order.  After the last pass the same block turns the per-tile counts of
-// sure survivors into their first output slots.
+// descending digit order.
 template <bool SEG>
 __global__ __launch_bounds__(kFinBlock) void k_topk_select(const Args a, int pass) {
   __shared__ uint32_t lds_scan[kFinWaves];
-  __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
   if (SEG && (c.bad || c.select_none)) return;
@@ -171,156 +170,137 @@ __global__ __launch_bounds__(kFinBlock) void k_topk_select(const Args a, int pas
       r.topk_ties_taken = nk;
     }
   }
-  if (pass == kDigits - 1) {
-    const uint32_t tile0 = SEG ? c.tile0 : 0u;
-    const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total, a.tile_chunks);
-    const uint32_t sure = scan_tiles(a.tile_counts + tile0, ntiles, a.tile_base + tile0, stage, lds_scan);
-    if (threadIdx.x == 0) c.cursor = sure;  // the other survivors take slots from here on
-  }
 }
 
-// ---- ties: when only some of the keys equal to T are kept, rank them by index ----------------
+// ---- once T is known: every tile's survivors and keys equal to T ------------------------------
+// One more pass over acc.  A tile's count of survivors (row 0) is what the last digit pass left
+// there (keys whose leading 24 bits exceed T's) plus the keys above T that share those bits, plus
+// the keys equal to T when all of those are kept; when only some are kept (ties are ranked by
+// index) the tile's number of keys equal to T goes to row 1.
 template <bool FULL>
-__device__ inline uint32_t tie_count_chunk(const Args& a, const Tile& t, uint32_t T) {
+__device__ inline void near_count_chunk(const Args& a, const Tile& t, uint32_t T, uint32_t& gt,
+                                        uint32_t& eq) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.acc, t, v);
-  uint32_t n = 0;
 #pragma unroll
-  for (int i = 0; i < kPerThread; ++i)
-    n += ((FULL || ((valid >> i) & 1u)) && mag_key(v[i]) == T) ? 1u : 0u;
-  return n;
+  for (int i = 0; i < kPerThread; ++i) {
+    const uint32_t key = mag_key(v[i]);
+    const bool ok = FULL || ((valid >> i) & 1u);
+    gt += (ok && (key >> 7) == (T >> 7) && key > T) ? 1u : 0u;
+    eq += (ok && key == T) ? 1u : 0u;
+  }
 }
 
 template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_topk_tie_count(const Args a) {
-  __shared__ uint32_t lds[kWaves];
+  __shared__ uint32_t lds[2 * kWaves];
   Span sp_;
   if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
   const SegCtrl& c = a.ctrl[sp_.seg];
-  if ((SEG && (c.bad || c.select_none)) || !c.rank_ties) return;
-  uint32_t n = 0;
+  if (SEG && (c.bad || c.select_none)) return;
+  const uint32_t T = c.prefix;
+  const bool rank_ties = c.rank_ties != 0;
+  uint32_t gt = 0, eq = 0;
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    n += t.full ? tie_count_chunk<true>(a, t, c.prefix) : tie_count_chunk<false>(a, t, c.prefix);
+    if (t.full) near_count_chunk<true>(a, t, T, gt, eq);
+    else near_count_chunk<false>(a, t, T, gt, eq);
   }
-  n = wave_sum(n);
-  if (lane_id() == 0) lds[wave_id()] = n;
+  gt = wave_sum(gt);
+  eq = wave_sum(eq);
+  if (lane_id() == 0) {
+    lds[2 * wave_id()] = gt;
+    lds[2 * wave_id() + 1] = eq;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
-    uint32_t s = 0;
-    for (int w = 0; w < kWaves; ++w) s += lds[w];
-    a.tile_counts[(size_t)a.max_tiles + blockIdx.x] = s;
+    uint32_t g = 0, e = 0;
+    for (int w = 0; w < kWaves; ++w) {
+      g += lds[2 * w];
+      e += lds[2 * w + 1];
+    }
+    a.tile_counts[blockIdx.x] += g + (rank_ties ? 0u : e);
+    if (rank_ties) a.tile_counts[(size_t)a.max_tiles + blockIdx.x] = e;
   }
 }
 
+// Per segment: the tiles' first output slots (and, when ties are ranked, the number of keys equal
+// to T before each tile) by a scan of the counts above.
 template <bool SEG>
 __global__ __launch_bounds__(kFinBlock) void k_topk_tie_scan(const Args a) {
   __shared__ uint32_t lds_scan[kFinWaves];
   __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
   const int s = blockIdx.x;
   const SegCtrl& c = a.ctrl[s];
-  if ((SEG && (c.bad || c.select_none)) || !c.rank_ties) return;
+  if (SEG && (c.bad || c.select_none)) return;
   const uint32_t tile0 = SEG ? c.tile0 : 0u;
   const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total, a.tile_chunks);
-  scan_tiles(a.tile_counts + (size_t)a.max_tiles + tile0, ntiles, a.tie_base + tile0, stage, lds_scan);
+  scan_tiles(a.tile_counts + tile0, ntiles, a.tile_base + tile0, stage, lds_scan);
+  if (c.rank_ties)
+    scan_tiles(a.tile_counts + (size_t)a.max_tiles + tile0, ntiles, a.tie_base + tile0, stage, lds_scan);
 }
 
-// ---- T5: compaction of {key > T} and the kept ties, residual write ---------------------------
-// Survivors whose leading 24 bits exceed T's go, in index order, to the slots the scan assigned
-// to their tile.  Survivors that share T's leading 24 bits (normally a handful in the whole
-// vector) take theirs from the segment's cursor, one reservation per chunk that has any.
-struct TopkSel {
-  uint32_t T, take;       // the k-th key; ties to keep
+// ---- compaction in index order, residual write -------------------------------------------------
+// `out0`, `cap`: first slot and capacity of the output range; `none`: select nothing.
+struct OrderedSel {
+  uint32_t T, take;
   bool rank_ties, none;
   int64_t out0, cap;
-  uint32_t sure_run;      // sure survivors of this tile's earlier chunks
-  uint32_t tie_run;       // ties met so far in index order (this tile's base + earlier chunks)
-  uint32_t tile_sure0;    // first output slot of this tile's sure survivors
 };
-
-template <bool FULL, bool NORMS>
-__device__ inline void topk_compact_chunk(const Args& a, const Tile& t, SegCtrl& c, TopkSel& k,
-                                          uint32_t* lds, uint32_t* lds_base, NormAcc& norms) {
+template <bool FULL, bool NORMS, bool STREAM = false>  // STREAM: see compact_chunk
+__device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, const OrderedSel& o,
+                                             uint32_t& out_run, uint32_t& tie_run,
+                                             uint32_t* lds, NormAcc& norms) {
   float v[kPerThread];
-  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
-  const uint32_t T = k.T;
-  uint32_t sure = 0, near = 0, eq = 0;
+  const uint32_t valid = load_tile<FULL, STREAM>(a.acc, t, v);
+  const uint32_t T = o.T, take = o.take;
+  const bool rank_ties = o.rank_ties;
+  uint32_t sel = 0, eq = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
-    if ((FULL || ((valid >> i) & 1u)) && !k.none) {
+    if ((FULL || ((valid >> i) & 1u)) && !o.none) {
       const uint32_t key = mag_key(v[i]);
-      sure |= ((key >> 7) > (T >> 7) ? 1u : 0u) << i;
-      near |= (((key >> 7) == (T >> 7)) && key > T ? 1u : 0u) << i;
-      eq |= (key == T ? 1u : 0u) << i;
+      sel |= ((key > T || (!rank_ties && key == T)) ? 1u : 0u) << i;
+      eq |= ((rank_ties && key == T) ? 1u : 0u) << i;
     }
   }
   uint32_t first[kSlots];
-  const uint32_t n_sure = tile_rank(sure, lds, first);
+  if (rank_ties && __syncthreads_or(eq != 0)) {
+    // keep a tie only if fewer than `take` ties precede it in index order
+    const uint32_t n_eq = tile_rank(eq, lds, first);
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+      uint32_t r = tie_run + first[j];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if ((eq >> (4 * j + q)) & 1u) {
+          if (r < take) sel |= 1u << (4 * j + q);
+          ++r;
+        }
+      }
+    }
+    tie_run += n_eq;
+    __syncthreads();  // lds is reused below
+  }
+  const uint32_t n_sel = tile_rank(sel, lds, first);
 #pragma unroll
   for (int j = 0; j < kSlots; ++j) {
-    uint32_t r = k.tile_sure0 + k.sure_run + first[j];
+    uint32_t r = out_run + first[j];
     const int64_t i0 = slot_index(t, j);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      if ((sure >> (4 * j + q)) & 1u) {
-        if ((int64_t)r < k.cap) {
-          a.out_idx[k.out0 + r] = (uint32_t)(i0 + q);
-          a.out_val[k.out0 + r] = v[4 * j + q];
+      if ((sel >> (4 * j + q)) & 1u) {
+        if ((int64_t)r < o.cap) {
+          a.out_idx[o.out0 + r] = (uint32_t)(i0 + q);
+          a.out_val[o.out0 + r] = v[4 * j + q];
         }
         ++r;
       }
     }
   }
-  k.sure_run += n_sure;
-  // the rest: same leading bits as T.  Block-uniform early out when the chunk has none.
-  if (__syncthreads_or((near | eq) != 0)) {
-    if (k.rank_ties) {
-      // keep a tie only if fewer than `take` ties precede it in index order
-      const uint32_t n_eq = tile_rank(eq, lds, first);
-      uint32_t kept = 0;
-#pragma unroll
-      for (int j = 0; j < kSlots; ++j) {
-        uint32_t r = k.tie_run + first[j];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if ((eq >> (4 * j + q)) & 1u) {
-            if (r < k.take) kept |= 1u << (4 * j + q);
-            ++r;
-          }
-        }
-      }
-      eq = kept;
-      k.tie_run += n_eq;
-      __syncthreads();
-    }
-    near |= eq;
-    const uint32_t n_near = tile_rank(near, lds, first);
-    if (n_near != 0) {
-      if (threadIdx.x == 0) *lds_base = atomicAdd(&c.cursor, n_near);
-      __syncthreads();
-      const uint32_t base = *lds_base;
-#pragma unroll
-      for (int j = 0; j < kSlots; ++j) {
-        uint32_t r = base + first[j];
-        const int64_t i0 = slot_index(t, j);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if ((near >> (4 * j + q)) & 1u) {
-            if ((int64_t)r < k.cap) {
-              a.out_idx[k.out0 + r] = (uint32_t)(i0 + q);
-              a.out_val[k.out0 + r] = v[4 * j + q];
-            }
-            ++r;
-          }
-        }
-      }
-    }
-  } else {
-    near = 0;
-  }
-  const uint32_t sel = sure | near;
+  out_run += n_sel;
   if (NORMS) norm_accumulate(norms, v, valid, sel);
-  if (a.inplace) {
+  if (a.inplace) {  // acc is the residual: only the selected entries change
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i)
       if ((sel >> i) & 1u) a.resid[slot_index(t, i >> 2) + (i & 3)] = 0.0f;
@@ -330,33 +310,27 @@ __device__ inline void topk_compact_chunk(const Args& a, const Tile& t, SegCtrl&
       if ((sel >> i) & 1u) v[i] = 0.0f;
     store_tile<FULL>(a.resid, t, v, valid);
   }
-  __syncthreads();  // lds and lds_base are reused by the next chunk
+  __syncthreads();  // lds is reused by the next chunk
 }
 
 template <bool SEG, bool NORMS>
 __global__ __launch_bounds__(kBlock) void k_topk_compact(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
-  __shared__ uint32_t lds_base;
   Span sp_;
   if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
-  SegCtrl& c = a.ctrl[sp_.seg];
+  const SegCtrl& c = a.ctrl[sp_.seg];
   if (SEG && c.bad) return;
-  TopkSel k;
-  k.T = c.prefix;
-  k.take = c.k_rem;
-  k.rank_ties = c.rank_ties != 0;
-  k.none = SEG && c.select_none != 0;
-  k.out0 = SEG ? c.out_base : 0;
-  k.cap = SEG ? c.cap : a.flat_cap;
-  k.sure_run = 0;
-  k.tie_run = k.rank_ties ? a.tie_base[blockIdx.x] : 0u;
-  k.tile_sure0 = a.tile_base[blockIdx.x];
+  const OrderedSel o = {c.prefix, c.k_rem, c.rank_ties != 0, SEG && c.select_none != 0,
+                        SEG ? c.out_base : 0, SEG ? c.cap : a.flat_cap};
+  // ties before the tile are capped at the number kept: the lowest indices win
+  uint32_t tie_run = o.rank_ties ? a.tie_base[blockIdx.x] : 0u;
+  uint32_t out_run = a.tile_base[blockIdx.x] + (tie_run < o.take ? tie_run : o.take);
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
-    if (t.full) topk_compact_chunk<true, NORMS>(a, t, c, k, lds, &lds_base, norms);
-    else topk_compact_chunk<false, NORMS>(a, t, c, k, lds, &lds_base, norms);
+    if (t.full) ordered_compact_chunk<true, NORMS>(a, t, o, out_run, tie_run, lds, norms);
+    else ordered_compact_chunk<false, NORMS>(a, t, o, out_run, tie_run, lds, norms);
   }
   if (NORMS) store_norm_partial(a, norms, blockIdx.x, lds_n);
 }

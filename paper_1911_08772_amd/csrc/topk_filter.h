@@ -22,18 +22,6 @@
 
 namespace sp {
 
-// rows of tile_counts used by this path
-constexpr int kRowTake = 0;   // survivors of the tile, ranked ties not included
-constexpr int kRowTies = 1;   // keys equal to T (only when ties are ranked)
-constexpr int kRowCand = 2;   // candidate keys the filter pass wrote for the tile
-constexpr int kRowAbove = 3;  // keys whose exponent byte exceeds the chosen one
-// columns of group_counts used by this path
-constexpr int kColTake = 0;
-constexpr int kColTies = 1;
-
-__device__ inline uint32_t* tile_row(const Args& a, int row) {
-  return a.tile_counts + (size_t)row * a.max_tiles;
-}
 __device__ inline uint32_t* tile_candidates(const Args& a, uint32_t tile) {
   return reinterpret_cast<uint32_t*>(a.resid) + (int64_t)tile * a.tile_chunks * kChunk;
 }
@@ -277,73 +265,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final(const Args a) {
   }
 }
 
-// ---- compaction in index order, residual write -------------------------------------------------
-// `out0`, `cap`: first slot and capacity of the output range; `none`: select nothing.
-struct OrderedSel {
-  uint32_t T, take;
-  bool rank_ties, none;
-  int64_t out0, cap;
-};
-template <bool FULL, bool NORMS, bool STREAM = false>  // STREAM: see compact_chunk
-__device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, const OrderedSel& o,
-                                             uint32_t& out_run, uint32_t& tie_run,
-                                             uint32_t* lds, NormAcc& norms) {
-  float v[kPerThread];
-  const uint32_t valid = load_tile<FULL, STREAM>(a.acc, t, v);
-  const uint32_t T = o.T, take = o.take;
-  const bool rank_ties = o.rank_ties;
-  uint32_t sel = 0, eq = 0;
-#pragma unroll
-  for (int i = 0; i < kPerThread; ++i) {
-    if ((FULL || ((valid >> i) & 1u)) && !o.none) {
-      const uint32_t key = mag_key(v[i]);
-      sel |= ((key > T || (!rank_ties && key == T)) ? 1u : 0u) << i;
-      eq |= ((rank_ties && key == T) ? 1u : 0u) << i;
-    }
-  }
-  uint32_t first[kSlots];
-  if (rank_ties && __syncthreads_or(eq != 0)) {
-    // keep a tie only if fewer than `take` ties precede it in index order
-    const uint32_t n_eq = tile_rank(eq, lds, first);
-#pragma unroll
-    for (int j = 0; j < kSlots; ++j) {
-      uint32_t r = tie_run + first[j];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if ((eq >> (4 * j + q)) & 1u) {
-          if (r < take) sel |= 1u << (4 * j + q);
-          ++r;
-        }
-      }
-    }
-    tie_run += n_eq;
-    __syncthreads();  // lds is reused below
-  }
-  const uint32_t n_sel = tile_rank(sel, lds, first);
-#pragma unroll
-  for (int j = 0; j < kSlots; ++j) {
-    uint32_t r = out_run + first[j];
-    const int64_t i0 = slot_index(t, j);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if ((sel >> (4 * j + q)) & 1u) {
-        if ((int64_t)r < o.cap) {
-          a.out_idx[o.out0 + r] = (uint32_t)(i0 + q);
-          a.out_val[o.out0 + r] = v[4 * j + q];
-        }
-        ++r;
-      }
-    }
-  }
-  out_run += n_sel;
-  if (NORMS) norm_accumulate(norms, v, valid, sel);
-#pragma unroll
-  for (int i = 0; i < kPerThread; ++i)
-    if ((sel >> i) & 1u) v[i] = 0.0f;
-  store_tile<FULL>(a.resid, t, v, valid);
-  __syncthreads();  // lds is reused by the next chunk
-}
-
+// ---- compaction in index order (ordered_compact_chunk of topk.h), residual write ------------------
 template <bool NORMS, int GT, int MG, bool STREAM>  // tiles per group, groups at most, non-temporal reads
 __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];

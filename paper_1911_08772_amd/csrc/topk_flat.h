@@ -1,11 +1,15 @@
 // Exact Top_k, flat vectors, accumulator aliased to the residual (in-place mode): seven launches
 // with three full digit passes.  (With a separate accumulator the candidate-filtering form of
-// topk_filter.h is used instead; it shares this file's initialisation and digit choice.)
+// topk_filter.h is used instead; it shares this file's initialisation and digit choice, and this
+// form ends in that file's ordered compaction.)
 // The per-segment "select" kernels of topk.h are latency-bound single workgroups that each cost a
 // launch; here every workgroup of the next pass chooses the digit itself from the replicated
-// histogram of the previous pass (same arithmetic, same inputs: all agree), each pass has its own
-// histogram buffer (cleared once by the init kernel), and every compact workgroup finds its
-// output base from per-group totals of the sure survivors.
+// histogram of the previous pass (same arithmetic, same inputs: all agree), and each pass has its
+// own histogram buffer (cleared once by the init kernel).  The last pass leaves, per tile, the
+// number of keys whose leading 24 bits already exceed the prefix and the histogram of the last
+// digit among the keys that share the prefix; once the last digit is chosen these give every
+// tile's number of survivors and of keys equal to the k-th key without another look at acc, so
+// every output slot is fixed by counts and the pairs come out in ascending index order.
 //
 // Used when the vector has at most kFusedMaxTiles tiles (always, unless tile_chunks is forced).
 #pragma once
@@ -17,9 +21,23 @@ namespace sp {
 
 constexpr int kTopkCopies = 32;  // replicas of each pass's global histogram
 constexpr int kTopkHistWords = kDigits * kTopkCopies * 256;
+constexpr int kLastDigitBins = 128;  // the last digit has 7 bits
 
 __device__ inline uint32_t* pass_hist(const Args& a, int pass) {
   return a.hist + (size_t)pass * kTopkCopies * 256;
+}
+
+// rows of tile_counts used by the forms with ordered compaction
+constexpr int kRowTake = 0;   // survivors of the tile, ranked ties not included
+constexpr int kRowTies = 1;   // keys equal to T (only when ties are ranked)
+constexpr int kRowCand = 2;   // candidate keys the filter pass wrote for the tile
+constexpr int kRowAbove = 3;  // keys known to exceed the k-th key before its last digits are
+// columns of group_counts used by them
+constexpr int kColTake = 0;
+constexpr int kColTies = 1;
+
+__device__ inline uint32_t* tile_row(const Args& a, int row) {
+  return a.tile_counts + (size_t)row * a.max_tiles;
 }
 
 // Clears `hist_words` words of histograms and the group totals, resets the selection state.
@@ -35,7 +53,6 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_fused(const Args a, uint32
       c.k_rem = (uint32_t)a.flat_k;
       c.n_eq = 0;
       c.rank_ties = 0;
-      c.cursor = 0;
       c.select_none = 0;
       c.bad = 0;
       sparsify_result& r = a.result[0];
@@ -144,112 +161,60 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist_fused(const Args a, int pa
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) v += h[w][bin];
     if (v) atomicAdd(&pass_hist(a, pass)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+    if (LAST && bin < kLastDigitBins) a.tile_hist[(size_t)tile * kLastDigitBins + bin] = v;
   }
   if (LAST && threadIdx.x == 0) {
     uint32_t s = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) s += lds_sure[w];
-    a.tile_counts[tile] = s;
-    if (s) atomicAdd(&a.group_counts[(tile / kGroupTiles) * kNumThres], s);
+    tile_row(a, kRowAbove)[tile] = s;
   }
 }
 
-// After the last pass: every workgroup chooses the last digit (so T, the ties to keep and
-// whether they must be ranked are known); workgroup 0 publishes them with the start of the
-// cursor; if ties must be ranked, each workgroup counts the keys equal to T in its tile.
+// After the last pass: every workgroup chooses the last digit (so T, the ties to keep and whether
+// they must be ranked are known; workgroup 0 publishes them); then one wave per tile turns the
+// tile's last-digit histogram into its number of survivors (keys above T, and keys equal to T
+// when all of those are kept) and, when ties are ranked, its number of keys equal to T; both go
+// to the per-group totals the ordered compaction reads.
 __global__ __launch_bounds__(kBlock) void k_topk_ties_fused(const Args a) {
   __shared__ uint32_t lds_sel[kWaves + 3];
-  __shared__ uint32_t lds[kWaves];
-  const uint32_t tile = blockIdx.x;
-  Span sp_;
-  if (!locate_span<false>(a, tile, &sp_)) return;
   SegCtrl& c = a.ctrl[0];
   const Digit dg = choose_digit(pass_hist(a, 3), 3, c.sel_prefix[2], c.sel_krem[2], lds_sel);
+  const uint32_t T = dg.prefix;
   const bool rank_ties = dg.count > dg.k_rem;
-  if (tile == 0) {
-    uint32_t g = 0;  // total of the sure survivors: one group total per lane
-    if (wave_id() == 0) {
-      const uint32_t ngroups = (gridDim.x + kGroupTiles - 1) / kGroupTiles;
-      g = (uint32_t)lane_id() < ngroups ? a.group_counts[lane_id() * kNumThres] : 0u;
-      g = wave_sum(g);
-    }
-    if (threadIdx.x == 0) {
-      c.topk_key = dg.prefix;
-      c.topk_take = dg.k_rem;
-      c.n_eq = dg.count;
-      c.rank_ties = rank_ties ? 1u : 0u;
-      c.cursor = g;  // the survivors that share T's leading 24 bits take slots from here on
-      sparsify_result& r = a.result[0];
-      r.topk_key = dg.prefix;
-      r.topk_ties_taken = dg.k_rem;
-    }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    c.topk_key = T;
+    c.topk_take = dg.k_rem;
+    c.n_eq = dg.count;
+    c.rank_ties = rank_ties ? 1u : 0u;
+    sparsify_result& r = a.result[0];
+    r.topk_key = T;
+    r.topk_ties_taken = dg.k_rem;
   }
-  if (!rank_ties) return;
-  uint32_t n = 0;
-  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
-    const Tile t = chunk_of(sp_, u);
-    n += t.full ? tie_count_chunk<true>(a, t, dg.prefix) : tie_count_chunk<false>(a, t, dg.prefix);
-  }
-  n = wave_sum(n);
-  if (lane_id() == 0) lds[wave_id()] = n;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t s = 0;
-    for (int w = 0; w < kWaves; ++w) s += lds[w];
-    a.tile_counts[(size_t)a.max_tiles + tile] = s;
-  }
-}
-
-// Compaction.  Prologue: first slot of the tile's sure survivors (groups before its own + tiles
-// before it inside its group) and, when ties are ranked, the number of ties before the tile.
-template <bool NORMS>
-__global__ __launch_bounds__(kBlock) void k_topk_compact_fused(const Args a) {
-  __shared__ uint32_t lds[kSlots * kWaves];
-  __shared__ uint32_t lds_base;
-  __shared__ uint32_t lds_pre[kWaves];
-  __shared__ double lds_n[2 * kWaves];
-  const uint32_t tile = blockIdx.x;
-  Span sp_;
-  if (!locate_span<false>(a, tile, &sp_)) return;
-  SegCtrl& c = a.ctrl[0];
-  TopkSel k;
-  k.T = c.topk_key;
-  k.take = c.topk_take;
-  k.rank_ties = c.rank_ties != 0;
-  k.none = false;
-  k.out0 = 0;
-  k.cap = a.flat_cap;
-  k.sure_run = 0;
-  const uint32_t g = tile / kGroupTiles, g0 = g * kGroupTiles, within = tile - g0;
-  uint32_t x = 0;
-  if (wave_id() == 0) {
-    if ((uint32_t)lane_id() < g) x += a.group_counts[lane_id() * kNumThres];
-    if ((uint32_t)lane_id() < within) x += a.tile_counts[g0 + lane_id()];
-    x = wave_sum(x);
-  }
-  uint32_t ties_before = 0;
-  if (k.rank_ties) {  // rare: sum the tie counts of all earlier tiles
-    const uint32_t* tc = a.tile_counts + a.max_tiles;
-    for (uint32_t i = threadIdx.x; i < tile; i += kBlock) ties_before += tc[i];
-    ties_before = wave_sum(ties_before);
-  }
-  if (lane_id() == 0) {
-    lds_pre[wave_id()] = ties_before;
-    if (wave_id() == 0) lds_base = x;
-  }
-  __syncthreads();
-  k.tile_sure0 = lds_base;
-  k.tie_run = 0;
+  const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  const uint32_t digit = T & (uint32_t)(kLastDigitBins - 1);
+  for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
+    uint32_t gt = 0, eq = 0;
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) k.tie_run += lds_pre[w];
-  __syncthreads();
-  NormAcc norms = {0.0, 0.0};
-  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
-    const Tile t = chunk_of(sp_, u);
-    if (t.full) topk_compact_chunk<true, NORMS>(a, t, c, k, lds, &lds_base, norms);
-    else topk_compact_chunk<false, NORMS>(a, t, c, k, lds, &lds_base, norms);
+    for (int j = 0; j < kLastDigitBins; j += 64) {
+      const uint32_t bin = j + lane_id();
+      const uint32_t v = a.tile_hist[(size_t)tile * kLastDigitBins + bin];
+      gt += bin > digit ? v : 0u;
+      eq += bin == digit ? v : 0u;
+    }
+    gt = wave_sum(gt);
+    eq = wave_sum(eq);
+    if (lane_id() == 0) {
+      const uint32_t taken = tile_row(a, kRowAbove)[tile] + gt + (rank_ties ? 0u : eq);
+      tile_row(a, kRowTake)[tile] = taken;
+      uint32_t* grp = a.group_counts + (tile / kGroupTiles) * kNumThres;
+      if (taken) atomicAdd(&grp[kColTake], taken);
+      if (rank_ties) {
+        tile_row(a, kRowTies)[tile] = eq;
+        if (eq) atomicAdd(&grp[kColTies], eq);
+      }
+    }
   }
-  if (NORMS) store_norm_partial(a, norms, tile, lds_n);
 }
 
 }  // namespace sp

@@ -1,6 +1,6 @@
 """Shared plumbing of the GPU parity tests: run the HIP path through the C ABI on torch-owned
 device buffers, fetch the outputs, and compare them with the CPU oracle's on the same host
-inputs.  Bit-exact for acc, index sets, values and residuals; thresholds within 1e-6 relative
+inputs.  Bit-exact for acc, indices (in ascending order), values and residuals; thresholds within 1e-6 relative
 (their moments are summed in a different order), counts/rounds/flags exactly equal."""
 import math
 import os
@@ -69,9 +69,9 @@ def same_bits(a: np.ndarray, b: np.ndarray) -> bool:
 
 
 def assert_pairs_match(got, idx_o, val_o, what=""):
-    """Index sets and values bit-exact (the GPU order is canonicalised by sorting on index)."""
-    order = np.argsort(got["idx"], kind="stable")
-    gi, gv = got["idx"][order], got["val"][order]
+    """Indices and values bit-exact, in the oracle's order: ascending index, as every selector of
+    the library promises."""
+    gi, gv = got["idx"], got["val"]
     assert gi.size == idx_o.size, (what, gi.size, idx_o.size)
     assert np.array_equal(gi, idx_o), what
     assert same_bits(gv, val_o), what
@@ -191,9 +191,8 @@ def check_segmented(mode: int, gpu: SegGpu, g, eps_in, what="", **kw):
             assert int(res["topk_ties_taken"]) == ro.topk_ties_taken, (w, res, ro)
         o0, o1, n = int(gpu.out_off[l]), int(gpu.out_off[l + 1]), ro.nnz
         gi, gv = got["idx"][o0:o0 + n].view(np.uint32), got["val"][o0:o0 + n]
-        order = np.argsort(gi, kind="stable")
-        assert np.array_equal(gi[order], idx_o[o0:o0 + n]), w
-        assert same_bits(gv[order], val_o[o0:o0 + n]), w
+        assert np.array_equal(gi, idx_o[o0:o0 + n]), w       # ascending index inside the segment
+        assert same_bits(gv, val_o[o0:o0 + n]), w
         assert np.all(got["idx"][o0 + n:o1] == -1), w  # nothing beyond nnz in this range
     assert same_bits(got["eps"], eps_o), what
     return eps_o

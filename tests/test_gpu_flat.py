@@ -159,27 +159,35 @@ def test_cfg1_error_feedback_chain(selector):
 
 
 def test_run_to_run_reproducibility():
-    """Same inputs, repeated calls: identical result records, identical pair lists (Gaussian_k in
-    identical order), identical residuals."""
+    """Same inputs, repeated calls: identical result records, identical pair lists in identical
+    (ascending index) order, identical residuals; every selector, separate accumulator and in
+    place, the usual launch sequences and the general ones a forced fine tiling selects."""
     wl = synth.workload("cfg1_resnet20")
     g = wl.grad(0)
     eps = synth.normal(wl.d, 9, 9, 0.002)
-    for selector in ("gaussiank", "topk"):
-        gpu = FlatGpu(wl.d, cap=4 * wl.k)
+    g[1000:1400] = np.float32(0.25)    # many keys equal to the k-th key: ties ranked by index
+    g[5000:5400:2] = np.float32(-0.25)
+    eps[1000:1400] = 0
+    eps[5000:5400] = 0
+    for selector, inplace, kw in (("gaussiank", False, {}), ("gaussiank", True, {}),
+                                  ("topk", False, {}), ("topk", True, {}), ("dgck", False, {}),
+                                  ("topk", True, {"tile_chunks": 1}), ("topk", False, {"tile_chunks": 1})):
+        d = wl.d if not kw else 20_000_000   # 4883 one-chunk tiles: beyond the fused forms' tables
+        gg = g if not kw else np.resize(g, d)
+        ee = eps if not kw else np.resize(eps, d)
+        k = wl.k if not kw else 20_000
+        gpu = FlatGpu(d, cap=4 * k, inplace=inplace)
         ref = None
-        for rep in range(20):
-            gpu.set_residual(eps)
-            got = gpu.step(selector, g, wl.k)
-            key = (got["res"].tobytes(), got["eps"].tobytes())
-            pairs = (got["idx"].tobytes(), got["val"].tobytes())
-            if selector == "topk":
-                o = np.argsort(got["idx"])
-                pairs = (got["idx"][o].tobytes(), got["val"][o].tobytes())
+        for rep in range(20 if not kw else 4):
+            gpu.set_residual(ee)
+            got = gpu.step(selector, gg, k, **kw)
+            now = (got["res"].tobytes(), got["eps"].tobytes(), got["idx"].tobytes(), got["val"].tobytes())
             if ref is None:
-                ref = (key, pairs)
-            assert (key, pairs) == ref, (selector, rep)
-        if selector == "gaussiank":
-            assert np.all(np.diff(got["idx"].astype(np.int64)) > 0)  # ascending index order
+                ref = now
+            assert now == ref, (selector, inplace, kw, rep)
+        assert np.all(np.diff(got["idx"].astype(np.int64)) > 0), (selector, inplace, kw)
+        if selector == "topk":
+            assert int(got["res"]["topk_ties_taken"]) >= 1
 
 
 def test_stream_argument_and_trace():
