@@ -1,11 +1,9 @@
 // Gaussian_k (Algorithm 1) on gfx950: fused accumulate + fp64 moments, on-device normal
 // quantile, one multi-threshold count pass, on-device threshold walk, ordered compaction with
-// the residual write.  This file holds the building blocks shared by all forms (quantile,
-// moment accumulation, threshold candidates, the walk, count and compact of one chunk) and the
-// five-launch form of a flat call, used only when a forced tiling leaves more tiles than the
-// three-launch form's group tables hold: there a single workgroup combines the per-tile
-// partials in a fixed order between the streaming kernels.  The three-launch flat form is in
-// gaussiank_flat.h, the layer-wise form in gaussiank_seg.h.
+// the residual write.  This file holds the building blocks shared by the forms (quantile,
+// moment accumulation, threshold candidates, the walk, count and compact of one chunk, sums and
+// prefix sums by one large workgroup).  The flat form is in gaussiank_flat.h, the layer-wise form
+// in gaussiank_seg.h.
 #pragma once
 #include "common.h"
 #include "tile_io.h"
@@ -181,27 +179,6 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_seg(const Args a) {
   }
 }
 
-// Flat calls: a resident grid walks the chunks with a grid stride and leaves one partial per
-// workgroup (the moments need no particular partition of the vector).
-__global__ __launch_bounds__(kBlock) void k_accum_moments_flat(const Args a) {
-  __shared__ double lds[4 * kWaves];
-  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
-  MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
-  for (uint32_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
-    Tile t;
-    t.seg = 0;
-    t.tbase = (int64_t)ch * kChunk;
-    t.lo = t.tbase;
-    t.hi = (t.tbase + kChunk < a.d_total) ? t.tbase + kChunk : a.d_total;
-    t.full = t.tbase + kChunk <= a.d_total;
-    if (t.full) accum_moments_chunk<true>(a, t, m);
-    else accum_moments_chunk<false>(a, t, m);
-  }
-  store_moment_partial(a, m, blockIdx.x, lds);
-  if (blockIdx.x == 0 && threadIdx.x == 0)
-    a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
-}
-
 // The ten thresholds reachable from thres0 (Alg. 1 steps 8-11): `na` multiplications by 1.5 in
 // sequence, then halvings (exact), stored in ascending order of their nominal ratio to thres0.
 __device__ inline void candidate_thresholds(double thres0, double (&t64)[kNumThres]) {
@@ -246,9 +223,7 @@ __device__ inline Walk walk_thresholds(const uint32_t (&tot)[kNumThres], int64_t
   return w;
 }
 
-// ---- K2: combine partials -> mean, std, threshold candidates ----------------------------------
-// Two passes over the per-tile partials, no divisions per partial:
-//   N = sum n_i, mean = sum n_i mean_i / N, M2 = sum (M2_i + n_i (mean_i - mean)^2).
+// ---- sums over a workgroup of kFinBlock threads (the per-segment finalising kernels) ----------
 __device__ inline double fin_block_sum(double v, double* lds) {
   v = wave_sum(v);
   __syncthreads();
@@ -261,70 +236,6 @@ __device__ inline double fin_block_sum(double v, double* lds) {
 }
 
 constexpr int kFinBatch = 4;  // partials per thread per round: 4096 tiles per round
-
-__global__ __launch_bounds__(kFinBlock) void k_gk_threshold(const Args a) {
-  __shared__ double lds[kFinWaves];
-  const int s = 0;
-  SegCtrl& c = a.ctrl[s];
-  const uint32_t ntiles = a.moment_parts;  // one partial per accumulate workgroup
-  const int64_t n_seg = a.d_total;
-  const double* pn = a.partial;
-  const double* pm = pn + a.max_tiles;
-  const double* pq = pm + a.max_tiles;
-  const double z = c.z;  // issued early: its latency hides under the partial loads
-  double wsum = 0.0;
-  for (uint32_t base = 0; base < ntiles; base += kFinBlock * kFinBatch) {
-    double n[kFinBatch], mu[kFinBatch];
-#pragma unroll
-    for (int u = 0; u < kFinBatch; ++u) {
-      const uint32_t i = base + u * kFinBlock + threadIdx.x;
-      const bool ok = i < ntiles;
-      n[u] = ok ? pn[i] : 0.0;
-      mu[u] = ok ? pm[i] : 0.0;
-    }
-#pragma unroll
-    for (int u = 0; u < kFinBatch; ++u) wsum = fma(n[u], mu[u], wsum);
-  }
-  const double mean = fin_block_sum(wsum, lds) / (double)n_seg;
-  double dev = 0.0;
-  for (uint32_t base = 0; base < ntiles; base += kFinBlock * kFinBatch) {
-    double n[kFinBatch], mu[kFinBatch], q[kFinBatch];
-#pragma unroll
-    for (int u = 0; u < kFinBatch; ++u) {
-      const uint32_t i = base + u * kFinBlock + threadIdx.x;
-      const bool ok = i < ntiles;
-      n[u] = ok ? pn[i] : 0.0;
-      mu[u] = ok ? pm[i] : mean;
-      q[u] = ok ? pq[i] : 0.0;
-    }
-#pragma unroll
-    for (int u = 0; u < kFinBatch; ++u) {
-      const double dm = mu[u] - mean;
-      dev += fma(n[u] * dm, dm, q[u]);
-    }
-  }
-  const double m2 = fin_block_sum(dev, lds);
-  if (threadIdx.x != 0) return;
-
-  const double sd = (n_seg - a.ddof < 1) ? 0.0 : sqrt(m2 / (double)(n_seg - a.ddof));
-  const double thres0 = mean + sd * z;
-  double t64[kNumThres];
-  candidate_thresholds(thres0, t64);
-#pragma unroll
-  for (int p = 0; p < kNumThres; ++p) {
-    c.t64[p] = t64[p];
-    c.t32[p] = (float)t64[p];
-  }
-  c.sorted_ok = thres0 > 0.0 ? 1u : 0u;
-  uint32_t flags = 0;
-  if (!isfinite(mean) || !isfinite(sd) || !isfinite(thres0)) flags |= SPARSIFY_F_NONFINITE;
-  c.flags = flags;
-  sparsify_result& r = a.result[s];
-  r.mean = mean;
-  r.std = sd;
-  r.z = z;
-  r.thres0 = thres0;
-}
 
 // ---- K3: per tile, count |acc| > t for all ten candidate thresholds --------------------------
 // The thresholds sit in ascending order, so once no element of a wave's slot exceeds one of them
@@ -381,43 +292,9 @@ __device__ inline void count_chunk(const Args& a, const Tile& t, const float (&t
   count_values<FULL>(v, valid, thr, can_skip, cnt);
 }
 
-// The tiles are visited from the last to the first: the end of acc is what the accumulate
-// kernel wrote most recently, so it is the part most likely still to sit in the last-level cache.
-__global__ __launch_bounds__(kBlock) void k_gk_count(const Args a) {
-  __shared__ uint32_t lds[kWaves * kNumThres];
-  Span sp_;
-  const uint32_t tile = gridDim.x - 1u - blockIdx.x;
-  if (!locate_span<false>(a, tile, &sp_)) return;
-  const SegCtrl& c = a.ctrl[0];
-  float thr[kNumThres];
-#pragma unroll
-  for (int p = 0; p < kNumThres; ++p) thr[p] = c.t32[p];
-  const bool can_skip = c.sorted_ok != 0;
-  uint32_t cnt[kNumThres];
-#pragma unroll
-  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
-  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
-    const Tile t = chunk_of(sp_, u);
-    if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
-    else count_chunk<false>(a, t, thr, can_skip, cnt);
-  }
-  if (lane_id() == 0) {
-#pragma unroll
-    for (int p = 0; p < kNumThres; ++p) lds[wave_id() * kNumThres + p] = cnt[p];
-  }
-  __syncthreads();
-  if (threadIdx.x < kNumThres) {
-    uint32_t s = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) s += lds[w * kNumThres + threadIdx.x];
-    a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile] = s;  // [threshold][tile]
-  }
-}
-
-// ---- K4: total the counts, walk Alg. 1 steps 5-13, scan the chosen column ---------------------
+// ---- prefix sums of per-tile counts by one workgroup -------------------------------------------
 constexpr int kScanPer = 4;                        // consecutive tiles per thread per scan round
 constexpr int kScanChunk = kFinBlock * kScanPer;   // 4096 tiles staged in LDS per round
-constexpr int kTotBatch = 2;
 
 // Exclusive prefix sum of col[0..n) into base[0..n) by one workgroup of kFinBlock threads;
 // returns the total.  `stage` holds kFinBlock*(kScanPer+1) words, `lds_scan` kFinWaves words.
@@ -454,86 +331,6 @@ __device__ inline uint32_t scan_tiles(const uint32_t* col, uint32_t ntiles, uint
     __syncthreads();
   }
   return carry;
-}
-
-__global__ __launch_bounds__(kFinBlock) void k_gk_decide(const Args a) {
-  __shared__ uint32_t lds_cnt[kFinWaves * kNumThres];
-  __shared__ uint32_t lds_scan[kFinWaves];
-  __shared__ uint32_t lds_final;
-  __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
-  const int s = 0;
-  SegCtrl& c = a.ctrl[s];
-  const uint32_t tile0 = 0, ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
-  const int64_t k = a.flat_k, cap = a.flat_cap;
-  // thread 0 needs these after the totals; ask for them now so their latency overlaps
-  double t64[kNumThres];
-  uint32_t flags = 0;
-  if (threadIdx.x == 0) {
-#pragma unroll
-    for (int p = 0; p < kNumThres; ++p) t64[p] = c.t64[p];
-    flags = c.flags;  // NONFINITE bit from the threshold kernel
-  }
-  uint32_t cnt[kNumThres];
-#pragma unroll
-  for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
-  const uint32_t* cols = a.tile_counts + tile0;
-  for (uint32_t base = 0; base < ntiles; base += kFinBlock * kTotBatch) {
-    uint32_t x[kTotBatch][kNumThres];
-#pragma unroll
-    for (int u = 0; u < kTotBatch; ++u) {
-      const uint32_t i = base + u * kFinBlock + threadIdx.x;
-#pragma unroll
-      for (int p = 0; p < kNumThres; ++p)
-        x[u][p] = (i < ntiles) ? cols[(size_t)p * a.max_tiles + i] : 0u;
-    }
-#pragma unroll
-    for (int u = 0; u < kTotBatch; ++u)
-#pragma unroll
-      for (int p = 0; p < kNumThres; ++p) cnt[p] += x[u][p];
-  }
-#pragma unroll
-  for (int p = 0; p < kNumThres; ++p) cnt[p] = wave_sum(cnt[p]);
-  if (lane_id() == 0) {
-#pragma unroll
-    for (int p = 0; p < kNumThres; ++p) lds_cnt[wave_id() * kNumThres + p] = cnt[p];
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t tot[kNumThres];
-#pragma unroll
-    for (int p = 0; p < kNumThres; ++p) {
-      tot[p] = 0;
-      for (int w = 0; w < kFinWaves; ++w) tot[p] += lds_cnt[w * kNumThres + p];
-    }
-    sparsify_result& r = a.result[s];
-    const Walk w = walk_thresholds(tot, k);
-    const int p = w.pos;
-    const bool in_band = w.in_band;
-    const uint32_t rounds = w.rounds;
-    const uint32_t* counts = w.counts;
-    if (!in_band) flags |= SPARSIFY_F_EXHAUSTED;
-    const bool overflow = (int64_t)tot[p] > cap;
-    if (overflow) flags |= SPARSIFY_F_OVERFLOW;
-    const double tf = t64[p];
-    r.nnz = overflow ? 0u : tot[p];
-    r.rounds = rounds;
-    r.count[0] = counts[0];
-    r.count[1] = counts[1];
-    r.count[2] = counts[2];
-    r.count[3] = counts[3];
-    r.flags = flags;
-    r.thres = tf;
-    r.thres_f32 = (float)tf;
-    r.topk_key = 0;
-    r.topk_ties_taken = 0;
-    r.acc_sqnorm = 0.0;
-    r.residual_sqnorm = 0.0;
-    c.t_final = (float)tf;
-    c.select_none = overflow ? 1u : 0u;
-    lds_final = (uint32_t)p;
-  }
-  __syncthreads();
-  scan_tiles(cols + (size_t)lds_final * a.max_tiles, ntiles, a.tile_base + tile0, stage, lds_scan);
 }
 
 // ---- K5: compaction in index order + residual (Alg. 1 step 14, Eq. (2)) ----------------------
@@ -591,26 +388,6 @@ __device__ inline uint32_t compact_chunk(const Args& a, const Tile& t, float thr
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL, STREAM>(a.acc, t, v);
   return compact_values<FULL, NORMS>(a, t, v, valid, thr, none, out0, run, lds, norms);
-}
-
-template <bool NORMS>
-__global__ __launch_bounds__(kBlock) void k_gk_compact(const Args a) {
-  __shared__ uint32_t lds[kSlots * kWaves];
-  __shared__ double lds_n[2 * kWaves];
-  Span sp_;
-  if (!locate_span<false>(a, blockIdx.x, &sp_)) return;
-  const SegCtrl& c = a.ctrl[0];
-  const float thr = c.t_final;
-  const bool none = c.select_none != 0;
-  const int64_t out0 = (int64_t)a.tile_base[blockIdx.x];
-  uint32_t run = 0;
-  NormAcc norms = {0.0, 0.0};
-  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
-    const Tile t = chunk_of(sp_, u);
-    if (t.full) run = compact_chunk<true, NORMS>(a, t, thr, none, out0, run, lds, norms);
-    else run = compact_chunk<false, NORMS>(a, t, thr, none, out0, run, lds, norms);
-  }
-  if (NORMS) store_norm_partial(a, norms, blockIdx.x, lds_n);
 }
 
 // ---- optional: ||acc||^2 and ||residual'||^2 from the per-tile sums of the compact kernel ----

@@ -1,11 +1,12 @@
-// Gaussian_k, flat vectors: three launches instead of five.  A launch costs 3-4 us on the
-// stream even when the kernel does nothing, and a single workgroup that combines per-tile
-// partials is latency-bound; here every workgroup of the count kernel derives the thresholds
-// from the (few) moment partials itself, and every workgroup of the compact kernel walks
-// Algorithm 1 and finds its own output base from per-group totals.  All workgroups run the same
-// arithmetic on the same inputs in the same order, so they agree bit for bit.
+// Gaussian_k, flat vectors: three launches.  A launch costs 3-4 us on the stream even when the
+// kernel does nothing, and a single workgroup that combines per-tile partials is latency-bound;
+// here every workgroup of the count kernel derives the thresholds from the (few) moment partials
+// itself, and every workgroup of the compact kernel walks Algorithm 1 and finds its own output
+// base from per-group totals.  All workgroups run the same arithmetic on the same inputs in the
+// same order, so they agree bit for bit.
 //
-// Used when the vector has at most kFusedMaxTiles tiles (always, unless tile_chunks is forced).
+// The group tables hold kFusedMaxTiles tiles (kBigMaxTiles for long vectors); the host chooses
+// the tile length accordingly and refuses a forced tile length that would need more.
 #pragma once
 #include "common.h"
 #include "gaussiank.h"
@@ -24,7 +25,8 @@ constexpr int kBigMaxGroups = 256;
 constexpr int kBigMaxTiles = kBigGroupTiles * kBigMaxGroups;     // 65536
 constexpr int kMaxMomentParts = 1024;                             // accumulate workgroups at most
 
-// K1: the accumulate kernel of gaussiank.h (k_accum_moments_flat) on `moment_parts` workgroups,
+// K1: a resident grid of `moment_parts` workgroups walks the chunks with a grid stride and leaves
+// one moment partial per workgroup (the moments need no particular partition of the vector),
 // plus one more workgroup that streams nothing: it clears the group totals the count kernel adds
 // into and computes the normal quantile (a few microseconds of dependent fp64 arithmetic in one
 // thread, which would otherwise stick out at the end of a workgroup that also streams).
@@ -164,7 +166,9 @@ template <int GT>  // tiles per group
 __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
   __shared__ double lds_m[2 * kWaves];
   __shared__ uint32_t lds[kWaves * kNumThres];
-  const uint32_t tile = gridDim.x - 1u - blockIdx.x;  // backwards: see k_gk_count
+  // The tiles are visited from the last to the first: the end of acc is what the accumulate
+  // kernel wrote most recently, so it is the part most likely still to sit in the last-level cache.
+  const uint32_t tile = gridDim.x - 1u - blockIdx.x;
   Span sp_;
   if (!locate_span<false>(a, tile, &sp_)) return;
   SegCtrl& c = a.ctrl[0];

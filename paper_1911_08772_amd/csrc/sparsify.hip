@@ -249,8 +249,7 @@ void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
   }
 }
 
-// Flat Gaussian_k: three launches (gaussiank_flat.h); five when a forced tiling leaves more
-// tiles than the fused kernels' group tables hold.
+// Flat Gaussian_k: three launches (gaussiank_flat.h), four for long vectors.
 void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   // The streaming grid of the accumulate kernel: one workgroup per compute unit (measured on 256
@@ -263,7 +262,7 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   if (want > a.max_tiles) want = a.max_tiles;
   if (want < 1) want = 1;
   a.moment_parts = want;
-  if (nchunks > kChunkGridFrom && tiles <= (uint32_t)kBigMaxTiles) {
+  if (nchunks > kChunkGridFrom) {  // (flat_call has checked that the group tables hold `tiles`)
     // long vector: one chunk per workgroup and a fold of the partials, then short tiles in
     // groups of kBigGroupTiles
     a.moment_parts = nchunks < (uint32_t)kMaxMomentParts ? nchunks : (uint32_t)kMaxMomentParts;
@@ -279,7 +278,7 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
     }
     return;
   }
-  if (nchunks <= kChunkGridFrom && tiles <= (uint32_t)kFusedMaxTiles) {
+  {
     ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
     ln.run("gk_count", k_gk_count_fused<kGroupTiles>, dim3(tiles), blk, a);
     if (a.norms) {
@@ -290,17 +289,6 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
       if (stream_acc(a)) ln.run("gk_compact", k_gk_compact_fused<false, kGroupTiles, kMaxGroups, true>, dim3(tiles), blk, a);
       else ln.run("gk_compact", k_gk_compact_fused<false, kGroupTiles, kMaxGroups, false>, dim3(tiles), blk, a);
     }
-    return;
-  }
-  ln.run("accum_moments", k_accum_moments_flat, dim3(want), blk, a);
-  ln.run("gk_threshold", k_gk_threshold, dim3(1), dim3(kFinBlock), a);
-  ln.run("gk_count", k_gk_count, dim3(tiles), blk, a);
-  ln.run("gk_decide", k_gk_decide, dim3(1), dim3(kFinBlock), a);
-  if (a.norms) {
-    ln.run("gk_compact", k_gk_compact<true>, dim3(tiles), blk, a);
-    ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
-  } else {
-    ln.run("gk_compact", k_gk_compact<false>, dim3(tiles), blk, a);
   }
 }
 
@@ -447,6 +435,11 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (!(opts && opts->tile_chunks != 0))
     a.tile_chunks = tile_chunks_of(d, selector == kSelGaussian || (selector == kSelTopk && !a.inplace));
   const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
+  if (selector == kSelGaussian) {
+    // a forced tile length must leave no more tiles than the group tables hold
+    const bool big = (d + kChunk - 1) / kChunk > (int64_t)kChunkGridFrom;
+    if (tiles > (uint32_t)(big ? kBigMaxTiles : kFusedMaxTiles)) return SPARSIFY_E_INVALID;
+  }
   if (selector == kSelDgc) {
     // the per-tile key lists live in the residual buffer and the list kernels use one lane per
     // group of tiles: separate acc and at most kFusedMaxTiles tiles

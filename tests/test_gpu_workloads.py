@@ -9,6 +9,7 @@ import torch
 from gpu_harness import (FlatGpu, assert_dgck_result, assert_gaussiank_result, assert_pairs_match,
                          assert_topk_result, progress, same_bits)
 from oracle import oracle as O
+from paper_1911_08772_amd import sparsify as S
 from paper_1911_08772_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -96,11 +97,18 @@ def test_cfg3_resnet50_sized(selector, wl):
     chain(wl, selector)
 
 
-def test_cfg3_one_chunk_per_tile():
-    """6240 tiles: beyond what the three-launch flat Gaussian_k path handles, so this runs the
-    five-launch path on a flat vector."""
-    chain("cfg3_resnet50", "gaussiank", steps=3, tile_chunks=1)
+def test_cfg3_forced_tile_lengths():
+    """Forced fine tilings at the headline size: 3120 two-chunk tiles for Gaussian_k (its group
+    tables hold 4096; a one-chunk tiling would need 6240 and is refused), 6240 one-chunk tiles for
+    Top_k, which then runs the general twelve-launch form on a flat vector."""
+    chain("cfg3_resnet50", "gaussiank", steps=3, tile_chunks=2)
     chain("cfg3_resnet50", "topk", steps=3, tile_chunks=1)
+    wl = synth.workload("cfg3_resnet50")
+    gpu = FlatGpu(wl.d, 1024)
+    b = gpu.b
+    rc = S.sparsify_gaussiank(wl.d, wl.k, gpu.grad, b.residual, b.acc, b.out_idx, b.out_val, 1024,
+                              b.result, b.workspace, b.workspace_nbytes, tile_chunks=1, check=False)
+    assert rc == S.E_INVALID
 
 
 def test_cfg3_inplace_mode():

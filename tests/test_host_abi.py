@@ -147,3 +147,13 @@ def test_scatter_add_rejects_bad_arguments_before_any_launch():
     assert rc(dense=BASE + 64) == S.E_INVALID                     # dense overlaps the index lists
     assert rc(dense=BASE + (1 << 32)) == S.E_INVALID              # dense is the value buffer
     assert rc(status=BASE + (3 << 32) + 400) == S.E_INVALID       # status inside dense
+
+
+def test_gaussiank_refuses_a_forced_tile_length_its_tables_cannot_hold():
+    a, _ = flat_args(d=25_557_032, k=25_558, cap=1024)
+    def rc(tc):
+        return S.sparsify_gaussiank(a["d"], a["k"], a["grad"], a["residual"], a["acc"], a["out_idx"],
+                                    a["out_val"], a["cap"], a["result"], a["workspace"],
+                                    a["workspace_nbytes"], stream=0, check=False, tile_chunks=tc)
+    assert rc(1) == S.E_INVALID          # 6240 one-chunk tiles, the group tables hold 4096
+    assert rc(-1) == S.E_INVALID
