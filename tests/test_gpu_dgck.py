@@ -91,3 +91,13 @@ def test_cfg2_chain_of_five_steps():
     for step in range(5):
         wl.grad(step, out=g)
         eps = check_flat("dgck", gpu, g, eps, wl.k, what=f"cfg2 dgck step {step}", sample_seed=100 + step)
+
+
+def test_lstm_sized_heavy_tails_three_steps():
+    """The sampling comparator at the LSTM-sized length (66 M elements, Student-t(3) gradients):
+    three error-feedback steps, bit-exact record, pairs, accumulator and residual."""
+    wl = synth.workload("cfg5_lstm")
+    gpu = FlatGpu(wl.d, cap=wl.k)
+    eps = np.zeros(wl.d, np.float32)
+    for step in range(3):
+        eps = check_flat("dgck", gpu, wl.grad(step), eps, wl.k, what=f"cfg5 dgck step {step}")
