@@ -278,10 +278,34 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   const uint32_t ngroups = (ntiles + GT - 1) / GT;
   const uint32_t g = tile / GT, g0 = g * GT, within = tile - g0;
 
-  for (uint32_t i = threadIdx.x; i < ngroups * kNumThres; i += kBlock) lds_g[i] = a.group_counts[i];
-  for (uint32_t i = threadIdx.x; i < (uint32_t)(GT * kNumThres); i += kBlock) {
-    const uint32_t p = i / GT, j = i % GT;
-    lds_t[i] = (j < within) ? a.tile_counts[(size_t)p * a.max_tiles + g0 + j] : 0u;
+  // Both tables go to LDS in rounds of four loads per thread, every load issued before the first
+  // is waited for and none behind a branch (an index beyond the table re-reads a valid entry).
+  for (uint32_t i0 = 0; i0 < ngroups * kNumThres; i0 += 4 * kBlock) {
+    uint32_t v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * kBlock + threadIdx.x;
+      v[u] = a.group_counts[i < ngroups * kNumThres ? i : 0u];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * kBlock + threadIdx.x;
+      if (i < ngroups * kNumThres) lds_g[i] = v[u];
+    }
+  }
+  for (uint32_t i0 = 0; i0 < (uint32_t)(GT * kNumThres); i0 += 4 * kBlock) {
+    uint32_t v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * kBlock + threadIdx.x;
+      const uint32_t p = i < (uint32_t)(GT * kNumThres) ? i / GT : 0u, j = i % GT;
+      v[u] = a.tile_counts[(size_t)p * a.max_tiles + g0 + (j < within ? j : within)];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * kBlock + threadIdx.x;
+      if (i < (uint32_t)(GT * kNumThres)) lds_t[i] = (i % GT < within) ? v[u] : 0u;
+    }
   }
   double t64[kNumThres];
 #pragma unroll

@@ -281,21 +281,23 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   const uint32_t g = tile / GT, g0 = g * GT, within = tile - g0;
   if (wave_id() == 0) {  // survivors and ties before this tile: whole groups, then tiles of its own
     uint32_t x = 0, y = 0;
+    // (no load behind a branch, so that all of them are on their way before the first is
+    // waited for: a lane with nothing to add re-reads entry 0 and drops the value)
 #pragma unroll
     for (int j0 = 0; j0 < MG; j0 += 64) {
-      const uint32_t j = j0 + lane_id();
-      if (j < g) {
-        x += a.group_counts[j * kNumThres + kColTake];
-        if (rank_ties) y += a.group_counts[j * kNumThres + kColTies];
-      }
+      const uint32_t j = j0 + lane_id(), jc = j < g ? j : 0u;
+      const uint32_t vx = a.group_counts[jc * kNumThres + kColTake];
+      const uint32_t vy = a.group_counts[jc * kNumThres + kColTies];
+      x += j < g ? vx : 0u;
+      y += (j < g && rank_ties) ? vy : 0u;
     }
 #pragma unroll
     for (int j0 = 0; j0 < GT; j0 += 64) {
-      const uint32_t j = j0 + lane_id();
-      if (j < within) {
-        x += tile_row(a, kRowTake)[g0 + j];
-        if (rank_ties) y += tile_row(a, kRowTies)[g0 + j];
-      }
+      const uint32_t j = j0 + lane_id(), jc = j < within ? j : 0u;
+      const uint32_t vx = tile_row(a, kRowTake)[g0 + jc];
+      const uint32_t vy = tile_row(a, kRowTies)[g0 + jc];
+      x += j < within ? vx : 0u;
+      y += (j < within && rank_ties) ? vy : 0u;
     }
     x = wave_sum(x);
     y = wave_sum(y);
