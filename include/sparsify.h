@@ -79,9 +79,10 @@ typedef struct {
                       Alg. 1 step 3.  Must be >= 1. */
   int32_t ddof;    /* 1 (default): sample standard deviation; 0: population */
   int32_t tile_chunks; /* 0 (default): automatic.  Otherwise the number of 4096-element chunks one
-                      workgroup processes; a tuning knob, results do not depend on it.  Gaussian_k
-                      and DGC_k refuse (SPARSIFY_E_INVALID) a value that leaves more than 4096
-                      tiles (65536 for Gaussian_k beyond 123 M elements) */
+                      workgroup processes; a tuning knob, results do not depend on it.  The flat
+                      calls refuse (SPARSIFY_E_INVALID) a value that leaves more than 4096 tiles
+                      (65536 beyond 123 M elements for Gaussian_k and for Top_k with a separate
+                      acc) */
   void* trace;     /* NULL, or a sparsify_trace* to record per-kernel timings of this call */
   int32_t error_norms; /* 0 (default).  1: also reduce ||acc||^2 and ||residual'||^2 (fp64) into the
                       result record; the sums ride on the compaction pass, one small launch more */

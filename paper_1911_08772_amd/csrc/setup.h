@@ -35,23 +35,6 @@ __global__ __launch_bounds__(kBlock) void k_calibration_copy(float* dst, const f
     d4[i] = s4[i];
 }
 
-// Flat Top_k: reset the selection state and the histogram (one block of 256 threads).
-__global__ __launch_bounds__(kBlock) void k_topk_init_flat(const Args a) {
-  for (uint32_t r = 0; r < a.hist_copies; ++r) a.hist[r * 256 + threadIdx.x] = 0;
-  if (threadIdx.x == 0) {
-    SegCtrl& c = a.ctrl[0];
-    c.prefix = 0;
-    c.k_rem = (uint32_t)a.flat_k;
-    c.n_eq = 0;
-    c.rank_ties = 0;
-    c.select_none = 0;
-    c.bad = 0;
-    sparsify_result& r = a.result[0];
-    clear_result(r);
-    r.nnz = (uint32_t)a.flat_k;
-  }
-}
-
 // Segmented calls: one block walks the segments in chunks of kBlock, numbers their tiles and
 // their groups of kSegGroupTiles tiles, and clears the group totals.
 // mode 0 = Top_k, 1 = Gaussian_k.

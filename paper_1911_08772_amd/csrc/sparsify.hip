@@ -292,24 +292,23 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   }
 }
 
-template <bool SEG>
-void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
+// Flat Top_k.  Separate acc: seven launches with candidate filtering (topk_filter.h); in place:
+// seven launches with three more digit passes over acc (topk_flat.h).  flat_call has checked
+// that the group tables hold `tiles`.
+void launch_topk_flat(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   const dim3 pg(tiles);
-  const uint32_t nchunks_flat = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
-  const bool big = nchunks_flat > kChunkGridFrom;  // long vector: larger group tables
-  if (!SEG && !a.inplace && tiles <= (uint32_t)(big ? kBigMaxTiles : kFusedMaxTiles)) {  // see topk_filter.h
+  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  static const uint32_t cus = compute_units();
+  if (!a.inplace) {
+    const bool big = nchunks > kChunkGridFrom;  // long vector: larger group tables
     // one wave per tile's candidate list, several lists per wave when there are many tiles
     uint32_t lists = (tiles + kWaves - 1) / kWaves;
     if (lists > 4096) lists = 4096;
     const dim3 cg(lists);
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
-    if (big) {
-      ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks_flat), blk, a);
-    } else {
-      static const uint32_t cus = compute_units();
-      ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks_flat ? cus : nchunks_flat), blk, a);
-    }
+    if (big) ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks), blk, a);
+    else ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
     ln.run("topk_filter", k_topk_filter, pg, blk, a);
     ln.run("topk_cand2", k_topk_cand_hist, cg, blk, a, 2);
     ln.run("topk_cand3", k_topk_cand_hist, cg, blk, a, 3);
@@ -323,60 +322,49 @@ void launch_topk(Launcher& ln, const Args& a, uint32_t tiles) {
       else if (stream_acc(a)) ln.run("topk_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups, true>, pg, blk, a);
       else ln.run("topk_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups, false>, pg, blk, a);
     }
-    if (a.norms) ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
-    return;
-  }
-  if (SEG && !a.inplace) {  // layer-wise with candidate filtering: see topk_seg.h
-    ln.run("topk_accum_hist", k_topk_accum_hist<true>, pg, blk, a);
-    ln.run("topk_filter", k_topk_filter_seg, pg, blk, a);
-    ln.run("topk_cand2", k_topk_cand_hist_seg, pg, blk, a, 2);
-    ln.run("topk_cand3", k_topk_cand_hist_seg, pg, blk, a, 3);
-    ln.run("topk_final", k_topk_cand_final_seg, pg, blk, a);
-    if (a.norms) {
-      ln.run("topk_compact", k_topk_compact_ordered_seg<true>, pg, blk, a);
-      ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
-    } else {
-      ln.run("topk_compact", k_topk_compact_ordered_seg<false>, pg, blk, a);
-    }
-    return;
-  }
-  if (!SEG && tiles <= (uint32_t)kFusedMaxTiles) {  // seven launches: see topk_flat.h
+  } else {
     ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
-    {
-      static const uint32_t cus = compute_units();
-      const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
-      ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
-    }
+    ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
     ln.run("topk_hist1", k_topk_hist_fused<false>, pg, blk, a, 1);
     ln.run("topk_hist2", k_topk_hist_fused<false>, pg, blk, a, 2);
     ln.run("topk_hist3", k_topk_hist_fused<true>, pg, blk, a, 3);
     ln.run("topk_ties", k_topk_ties_fused, dim3((tiles + kWaves - 1) / kWaves), blk, a);
-    if (a.norms) {
-      ln.run("topk_compact", k_topk_compact_ordered<true, kGroupTiles, kMaxGroups, false>, pg, blk, a);
-      ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
-    } else {
-      ln.run("topk_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups, false>, pg, blk, a);
-    }
-    return;
+    if (a.norms) ln.run("topk_compact", k_topk_compact_ordered<true, kGroupTiles, kMaxGroups, false>, pg, blk, a);
+    else ln.run("topk_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups, false>, pg, blk, a);
   }
-  if (!SEG) ln.run("topk_init", k_topk_init_flat, dim3(1), blk, a);
-  ln.run("topk_accum_hist", k_topk_accum_hist<SEG>, pg, blk, a);
-  const dim3 fin(kFinBlock);
-  ln.run("topk_select0", k_topk_select<SEG>, dim3(a.L), fin, a, 0);
-  ln.run("topk_hist1", k_topk_hist<SEG, false>, pg, blk, a, 1);
-  ln.run("topk_select1", k_topk_select<SEG>, dim3(a.L), fin, a, 1);
-  ln.run("topk_hist2", k_topk_hist<SEG, false>, pg, blk, a, 2);
-  ln.run("topk_select2", k_topk_select<SEG>, dim3(a.L), fin, a, 2);
-  ln.run("topk_hist3", k_topk_hist<SEG, true>, pg, blk, a, 3);
-  ln.run("topk_select3", k_topk_select<SEG>, dim3(a.L), fin, a, 3);
-  ln.run("topk_tie_count", k_topk_tie_count<SEG>, dim3(tiles), blk, a);
-  ln.run("topk_tie_scan", k_topk_tie_scan<SEG>, dim3(a.L), fin, a);
-  if (a.norms) {
-    ln.run("topk_compact", k_topk_compact<SEG, true>, dim3(tiles), blk, a);
-    ln.run("norms", k_norms_finalize<SEG>, dim3(a.L), dim3(kFinBlock), a);
+  if (a.norms) ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
+}
+
+// Layer-wise Top_k (after k_seg_setup).  Separate acc: six launches with candidate filtering
+// (topk_seg.h); in place: twelve launches, a single-workgroup digit choice per segment after
+// every pass (topk.h).
+void launch_topk_seg(Launcher& ln, const Args& a, uint32_t tiles) {
+  const dim3 blk(kBlock);
+  const dim3 pg(tiles);
+  if (!a.inplace) {
+    ln.run("topk_accum_hist", k_topk_accum_hist, pg, blk, a);
+    ln.run("topk_filter", k_topk_filter_seg, pg, blk, a);
+    ln.run("topk_cand2", k_topk_cand_hist_seg, pg, blk, a, 2);
+    ln.run("topk_cand3", k_topk_cand_hist_seg, pg, blk, a, 3);
+    ln.run("topk_final", k_topk_cand_final_seg, pg, blk, a);
+    if (a.norms) ln.run("topk_compact", k_topk_compact_ordered_seg<true>, pg, blk, a);
+    else ln.run("topk_compact", k_topk_compact_ordered_seg<false>, pg, blk, a);
   } else {
-    ln.run("topk_compact", k_topk_compact<SEG, false>, dim3(tiles), blk, a);
+    const dim3 fin(kFinBlock);
+    ln.run("topk_accum_hist", k_topk_accum_hist, pg, blk, a);
+    ln.run("topk_select0", k_topk_select, dim3(a.L), fin, a, 0);
+    ln.run("topk_hist1", k_topk_hist<false>, pg, blk, a, 1);
+    ln.run("topk_select1", k_topk_select, dim3(a.L), fin, a, 1);
+    ln.run("topk_hist2", k_topk_hist<false>, pg, blk, a, 2);
+    ln.run("topk_select2", k_topk_select, dim3(a.L), fin, a, 2);
+    ln.run("topk_hist3", k_topk_hist<true>, pg, blk, a, 3);
+    ln.run("topk_select3", k_topk_select, dim3(a.L), fin, a, 3);
+    ln.run("topk_tie_count", k_topk_tie_count, dim3(tiles), blk, a);
+    ln.run("topk_tie_scan", k_topk_tie_scan, dim3(a.L), fin, a);
+    if (a.norms) ln.run("topk_compact", k_topk_compact<true>, dim3(tiles), blk, a);
+    else ln.run("topk_compact", k_topk_compact<false>, dim3(tiles), blk, a);
   }
+  if (a.norms) ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
 }
 
 // DGC_k: eleven launches (dgck.h).
@@ -435,9 +423,11 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (!(opts && opts->tile_chunks != 0))
     a.tile_chunks = tile_chunks_of(d, selector == kSelGaussian || (selector == kSelTopk && !a.inplace));
   const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
-  if (selector == kSelGaussian) {
-    // a forced tile length must leave no more tiles than the group tables hold
-    const bool big = (d + kChunk - 1) / kChunk > (int64_t)kChunkGridFrom;
+  if (selector == kSelGaussian || selector == kSelTopk) {
+    // a forced tile length must leave no more tiles than the group tables hold (the larger
+    // tables serve long vectors, except Top_k in place)
+    const bool big = (d + kChunk - 1) / kChunk > (int64_t)kChunkGridFrom &&
+                     !(selector == kSelTopk && a.inplace);
     if (tiles > (uint32_t)(big ? kBigMaxTiles : kFusedMaxTiles)) return SPARSIFY_E_INVALID;
   }
   if (selector == kSelDgc) {
@@ -458,7 +448,7 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (selector == kSelGaussian) {
     launch_gaussiank_flat(ln, a, tiles);
   } else if (selector == kSelTopk) {
-    launch_topk<false>(ln, a, tiles);
+    launch_topk_flat(ln, a, tiles);
   } else {
     launch_dgck(ln, a, tiles);
   }
@@ -543,7 +533,7 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
     const size_t n = (size_t)kDigits * 256 * (size_t)num_segments * a.hist_copies;
     ln.run("hist_zero", k_fill_u32, dim3((unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024)),
            dim3(256), a.hist, n, 0u);
-    launch_topk<true>(ln, a, tiles);
+    launch_topk_seg(ln, a, tiles);
   }
   if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);
   return ln.err == hipSuccess ? SPARSIFY_OK : SPARSIFY_E_LAUNCH;

@@ -2,12 +2,11 @@
 // passes (8, 8, 8, 7 bits, most significant first) with per-wave histograms in LDS, a digit
 // choice after each pass, then compaction of {key > T} plus the lowest-index ties.  This file
 // holds the building blocks (digit layout, histogram flush, the accumulate kernel with the first
-// digit's histogram, one chunk of the ordered compaction) and the general twelve-launch form with
-// one single-workgroup "select" kernel per segment after each pass, one more pass over acc that
-// counts every tile's survivors and ties once the k-th key T is known, and a per-segment scan of
-// those counts; it serves layer-wise calls in place and flat calls whose forced tiling exceeds
-// the fused forms' tables.  The forms normally used are in topk_filter.h (flat), topk_seg.h
-// (layer-wise) and topk_flat.h (flat, in place).
+// digit's histogram, one chunk of the ordered compaction) and the twelve-launch form of the
+// layer-wise calls in place: one single-workgroup "select" kernel per segment after each pass,
+// one more pass over acc that counts every tile's survivors and ties once the k-th key T is
+// known, and a per-segment scan of those counts.  The other forms are in topk_filter.h (flat),
+// topk_seg.h (layer-wise, separate acc) and topk_flat.h (flat, in place).
 // Global atomics on one address cost tens of nanoseconds each on this chip, so the global
 // histogram is replicated, and every survivor's output slot comes from counts (per-tile counts,
 // scanned or totalled per group): no output cursor anywhere, so the pairs of every form come
@@ -53,15 +52,14 @@ __device__ inline void accum_hist_tile(const Args& a, const Tile& t, uint32_t* h
     if (FULL || ((valid >> i) & 1u)) atomicAdd(&h[mag_key(g[i]) >> 23], 1u);
 }
 
-template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_topk_accum_hist(const Args a) {
   __shared__ uint32_t h[kWaves][256];
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   __syncthreads();
   Span sp_;
-  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
-  if (SEG && a.ctrl[sp_.seg].bad) return;
+  if (!locate_span<true>(a, blockIdx.x, &sp_)) return;
+  if (a.ctrl[sp_.seg].bad) return;
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);
     if (t.full) accum_hist_tile<true>(a, t, h[wave_id()]);
@@ -92,7 +90,7 @@ __device__ inline uint32_t hist_tile(const Args& a, const Tile& t, int pass, uin
   return sure;
 }
 
-template <bool SEG, bool LAST>
+template <bool LAST>
 __global__ __launch_bounds__(kBlock) void k_topk_hist(const Args a, int pass) {
   __shared__ uint32_t h[kWaves][256];
   __shared__ uint32_t lds_sure[kWaves];
@@ -103,9 +101,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(const Args a, int pass) {
   // odd passes walk the tiles backwards: each pass starts where the previous one ended, on the
   // part of acc most likely still to sit in the last-level cache
   const uint32_t tile = (pass & 1) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
-  if (!locate_span<SEG>(a, tile, &sp_)) return;
+  if (!locate_span<true>(a, tile, &sp_)) return;
   const SegCtrl& c = a.ctrl[sp_.seg];
-  if (SEG && (c.bad || c.select_none)) return;
+  if (c.bad || c.select_none) return;
   const uint32_t prefix = c.prefix;
   uint32_t sure = 0;
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
@@ -129,12 +127,11 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(const Args a, int pass) {
 // ---- T2: per segment, pick the digit holding the k_rem-th largest key ------------------------
 // One workgroup of kFinBlock threads per segment; the first 256 threads own one bin each, in
 // descending digit order.
-template <bool SEG>
 __global__ __launch_bounds__(kFinBlock) void k_topk_select(const Args a, int pass) {
   __shared__ uint32_t lds_scan[kFinWaves];
   const int s = blockIdx.x;
   SegCtrl& c = a.ctrl[s];
-  if (SEG && (c.bad || c.select_none)) return;
+  if (c.bad || c.select_none) return;
   const uint32_t nbins = 1u << digit_bits(pass);
   const bool owner = threadIdx.x < 256;
   const uint32_t bin = 255u - (threadIdx.x & 255u);
@@ -191,13 +188,12 @@ __device__ inline void near_count_chunk(const Args& a, const Tile& t, uint32_t T
   }
 }
 
-template <bool SEG>
 __global__ __launch_bounds__(kBlock) void k_topk_tie_count(const Args a) {
   __shared__ uint32_t lds[2 * kWaves];
   Span sp_;
-  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
+  if (!locate_span<true>(a, blockIdx.x, &sp_)) return;
   const SegCtrl& c = a.ctrl[sp_.seg];
-  if (SEG && (c.bad || c.select_none)) return;
+  if (c.bad || c.select_none) return;
   const uint32_t T = c.prefix;
   const bool rank_ties = c.rank_ties != 0;
   uint32_t gt = 0, eq = 0;
@@ -226,15 +222,13 @@ __global__ __launch_bounds__(kBlock) void k_topk_tie_count(const Args a) {
 
 // Per segment: the tiles' first output slots (and, when ties are ranked, the number of keys equal
 // to T before each tile) by a scan of the counts above.
-template <bool SEG>
 __global__ __launch_bounds__(kFinBlock) void k_topk_tie_scan(const Args a) {
   __shared__ uint32_t lds_scan[kFinWaves];
   __shared__ uint32_t stage[kFinBlock * (kScanPer + 1)];
   const int s = blockIdx.x;
   const SegCtrl& c = a.ctrl[s];
-  if (SEG && (c.bad || c.select_none)) return;
-  const uint32_t tile0 = SEG ? c.tile0 : 0u;
-  const uint32_t ntiles = SEG ? c.ntiles : seg_ntiles(0, a.d_total, a.tile_chunks);
+  if (c.bad || c.select_none) return;
+  const uint32_t tile0 = c.tile0, ntiles = c.ntiles;
   scan_tiles(a.tile_counts + tile0, ntiles, a.tile_base + tile0, stage, lds_scan);
   if (c.rank_ties)
     scan_tiles(a.tile_counts + (size_t)a.max_tiles + tile0, ntiles, a.tie_base + tile0, stage, lds_scan);
@@ -313,16 +307,15 @@ __device__ inline void ordered_compact_chunk(const Args& a, const Tile& t, const
   __syncthreads();  // lds is reused by the next chunk
 }
 
-template <bool SEG, bool NORMS>
+template <bool NORMS>
 __global__ __launch_bounds__(kBlock) void k_topk_compact(const Args a) {
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
   Span sp_;
-  if (!locate_span<SEG>(a, blockIdx.x, &sp_)) return;
+  if (!locate_span<true>(a, blockIdx.x, &sp_)) return;
   const SegCtrl& c = a.ctrl[sp_.seg];
-  if (SEG && c.bad) return;
-  const OrderedSel o = {c.prefix, c.k_rem, c.rank_ties != 0, SEG && c.select_none != 0,
-                        SEG ? c.out_base : 0, SEG ? c.cap : a.flat_cap};
+  if (c.bad) return;
+  const OrderedSel o = {c.prefix, c.k_rem, c.rank_ties != 0, c.select_none != 0, c.out_base, c.cap};
   // ties before the tile are capped at the number kept: the lowest indices win
   uint32_t tie_run = o.rank_ties ? a.tie_base[blockIdx.x] : 0u;
   uint32_t out_run = a.tile_base[blockIdx.x] + (tie_run < o.take ? tie_run : o.take);

@@ -98,17 +98,18 @@ def test_cfg3_resnet50_sized(selector, wl):
 
 
 def test_cfg3_forced_tile_lengths():
-    """Forced fine tilings at the headline size: 3120 two-chunk tiles for Gaussian_k (its group
-    tables hold 4096; a one-chunk tiling would need 6240 and is refused), 6240 one-chunk tiles for
-    Top_k, which then runs the general twelve-launch form on a flat vector."""
+    """Forced fine tilings at the headline size: 3120 two-chunk tiles (the group tables hold
+    4096); a one-chunk tiling would need 6240 and is refused by every flat call."""
     chain("cfg3_resnet50", "gaussiank", steps=3, tile_chunks=2)
-    chain("cfg3_resnet50", "topk", steps=3, tile_chunks=1)
+    chain("cfg3_resnet50", "topk", steps=3, tile_chunks=2)
+    chain("cfg3_resnet50", "topk", steps=2, tile_chunks=2, inplace=True)
     wl = synth.workload("cfg3_resnet50")
-    gpu = FlatGpu(wl.d, 1024)
+    gpu = FlatGpu(wl.d, wl.k)
     b = gpu.b
-    rc = S.sparsify_gaussiank(wl.d, wl.k, gpu.grad, b.residual, b.acc, b.out_idx, b.out_val, 1024,
-                              b.result, b.workspace, b.workspace_nbytes, tile_chunks=1, check=False)
-    assert rc == S.E_INVALID
+    for fn in (S.sparsify_gaussiank, S.sparsify_topk, S.sparsify_dgck):
+        rc = fn(wl.d, wl.k, gpu.grad, b.residual, b.acc, b.out_idx, b.out_val, wl.k, b.result,
+                b.workspace, b.workspace_nbytes, tile_chunks=1, check=False)
+        assert rc == S.E_INVALID, fn
 
 
 def test_cfg3_inplace_mode():

@@ -149,11 +149,22 @@ def test_scatter_add_rejects_bad_arguments_before_any_launch():
     assert rc(status=BASE + (3 << 32) + 400) == S.E_INVALID       # status inside dense
 
 
-def test_gaussiank_refuses_a_forced_tile_length_its_tables_cannot_hold():
-    a, _ = flat_args(d=25_557_032, k=25_558, cap=1024)
-    def rc(tc):
-        return S.sparsify_gaussiank(a["d"], a["k"], a["grad"], a["residual"], a["acc"], a["out_idx"],
-                                    a["out_val"], a["cap"], a["result"], a["workspace"],
-                                    a["workspace_nbytes"], stream=0, check=False, tile_chunks=tc)
-    assert rc(1) == S.E_INVALID          # 6240 one-chunk tiles, the group tables hold 4096
-    assert rc(-1) == S.E_INVALID
+def test_flat_calls_refuse_a_forced_tile_length_their_tables_cannot_hold():
+    a, _ = flat_args(d=25_557_032, k=25_558, cap=25_558)
+    def rc(fn, tc, inplace=False):
+        acc = a["residual"] if inplace else a["acc"]
+        return fn(a["d"], a["k"], a["grad"], a["residual"], acc, a["out_idx"], a["out_val"], a["cap"],
+                  a["result"], a["workspace"], a["workspace_nbytes"], stream=0, check=False,
+                  tile_chunks=tc)
+    for fn in (S.sparsify_gaussiank, S.sparsify_topk, S.sparsify_dgck):
+        assert rc(fn, 1) == S.E_INVALID      # 6240 one-chunk tiles, the group tables hold 4096
+        assert rc(fn, -1) == S.E_INVALID
+    assert rc(S.sparsify_gaussiank, 1, inplace=True) == S.E_INVALID
+    assert rc(S.sparsify_topk, 1, inplace=True) == S.E_INVALID
+    # beyond 123 M elements the tables of Gaussian_k and of Top_k with a separate acc hold 65536
+    # tiles; those of Top_k in place still 4096
+    big, _ = flat_args(d=200_000_000, k=200_000, cap=200_000)
+    rc_big = S.sparsify_topk(big["d"], big["k"], big["grad"], big["residual"], big["residual"],
+                             big["out_idx"], big["out_val"], big["cap"], big["result"], big["workspace"],
+                             big["workspace_nbytes"], stream=0, check=False, tile_chunks=1)
+    assert rc_big == S.E_INVALID         # 48829 one-chunk tiles
