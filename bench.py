@@ -133,7 +133,8 @@ def dominant(stage, d):
 
 
 def side_workload(S, torch, synth, name, K, W):
-    """Gaussian_k and Top_k on another workload: a shorter chain, one fresh gradient per step."""
+    """Gaussian_k and Top_k on another workload: the same K steps after W warm-up steps, one
+    fresh gradient per step."""
     import numpy as np
     wl = synth.workload(name)
     pool = K + W
@@ -326,7 +327,7 @@ def main() -> int:
         del f, grads
         torch.cuda.empty_cache()
         for name in ("cfg5_lstm", "cfg2_vgg16"):
-            extras[name] = side_workload(S, torch, synth, name, min(K, 8), min(W, 2))
+            extras[name] = side_workload(S, torch, synth, name, K, W)
 
     out = {
         "metric": ("Gaussian-k sparsify GB/s (algorithmic bytes) at d=25.6M, rho=0.001; exact Top-k beside it"
