@@ -46,8 +46,9 @@ class Flat:
     """One flat compressor instance on a pool of gradients resident in HBM (step s uses gradient
     s modulo the pool size): timed chains and traced chains of W warm-up + K steps."""
 
-    def __init__(self, S, torch, wl, grads, K, W, inplace=False, tile_chunks=0):
+    def __init__(self, S, torch, wl, grads, K, W, inplace=False, tile_chunks=0, short_list=0):
         self.S, self.torch, self.wl, self.grads, self.K, self.W = S, torch, wl, grads, K, W
+        self.short_list = short_list
         self.d, self.k = wl.d, wl.k
         self.cap = max(4 * wl.k, 1024)
         self.tile_chunks = tile_chunks
@@ -56,9 +57,10 @@ class Flat:
 
     def run(self, fn, s, trace=None, result=None):
         b = self.b
+        kw = {"short_list": self.short_list} if fn is self.S.sparsify_topk else {}
         fn(self.d, self.k, self.grads[s % len(self.grads)], b.residual, b.acc, b.out_idx, b.out_val,
            self.cap, b.result if result is None else result, b.workspace, b.workspace_nbytes,
-           trace=trace, stream=self.stream, tile_chunks=self.tile_chunks)
+           trace=trace, stream=self.stream, tile_chunks=self.tile_chunks, **kw)
 
     def timed(self, fn):
         """W warm-up steps then exactly K timed steps, bracketed by synchronisations; returns
@@ -216,6 +218,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3_resnet50")
     ap.add_argument("--inplace", action="store_true", help="acc aliases residual")
+    ap.add_argument("--short-list", type=int, default=0,
+                    help="-1: Top_k never builds the short lists in its accumulate pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip everything reported under `also` (other workloads, in place, layer-wise, "
@@ -254,7 +258,7 @@ def main() -> int:
                           "scatter_add": scatter_add_bench(S, torch, wl, grads, K, W)}), flush=True)
         return 0
     grads = park_gradients(torch, wl, n_grads)   # before any timing
-    f = Flat(S, torch, wl, grads, K, W, args.inplace, args.tile_chunks)
+    f = Flat(S, torch, wl, grads, K, W, args.inplace, args.tile_chunks, args.short_list)
     cap, stream = f.cap, f.stream
 
     if args.calibration_copy:

@@ -47,9 +47,14 @@ enum {
   SPARSIFY_F_OVERFLOW = 1u,  /* more survivors than `cap`: nothing selected, residual' = acc */
   SPARSIFY_F_NONFINITE = 2u, /* mean, std or threshold not finite */
   SPARSIFY_F_EXHAUSTED = 4u, /* four count evaluations used, last one still outside the band */
-  SPARSIFY_F_BADSEGMENT = 8u /* segmented call: this segment's offsets, k or output range are
+  SPARSIFY_F_BADSEGMENT = 8u, /* segmented call: this segment's offsets, k or output range are
                                 invalid (or its start lies before an earlier offset); no kernel
                                 touches its stretch of acc, residual or the output */
+  /* The next two say which way a flat Top_k call took, not what it computed (the results are the
+     same either way); neither is set when the call built no short lists to begin with. */
+  SPARSIFY_F_SHORTLIST = 16u,     /* the digit passes and the pairs were taken from the short lists */
+  SPARSIFY_F_SHORTLIST_MISS = 32u /* the lists were built but held fewer than k entries (or ran
+                                     out of room): the passes over acc ran after all */
 };
 
 /* Written on the stream; valid once the stream has been synchronised. */
@@ -89,11 +94,25 @@ typedef struct {
   int32_t sample_stride; /* DGC_k only.  0 (default): 100, a 1 % sample (Sec. 4.3).  Otherwise the
                       stratum length S >= 1: one sampled position per S consecutive elements */
   uint64_t sample_seed;  /* DGC_k only: seed of the counter-based choice of those positions */
+  int32_t short_list;    /* Top_k, flat call only.  0 (default): the library decides.  -1: never
+                      build the short lists (below).  Results do not depend on it. */
 } sparsify_opts;
 
-/* Bytes of `workspace` needed for a vector of d_total elements in num_segments segments
- * (1 for the flat calls).  Returns 0 for invalid arguments. */
+/* Bytes of `workspace` for a vector of d_total elements in num_segments segments (1 for the
+ * flat calls).  Returns 0 for invalid arguments.
+ *   sparsify_workspace_bytes      the size to allocate.  For flat vectors of 2 M to 123 M elements
+ *                                 it includes room for Top_k's short lists (0.8 bytes per
+ *                                 element): the accumulate pass then also writes the residual and
+ *                                 lists the entries above a key guessed from a sample of acc,
+ *                                 a fraction of a per cent of the vector; if the lists turn out
+ *                                 to hold at least k entries, the digit passes and the compaction
+ *                                 read them instead of acc (16 bytes per element instead of 24,
+ *                                 12 instead of 28 in place); if not, or if k > d / 80, the
+ *                                 passes over acc run as they do without the lists.
+ *   sparsify_workspace_bytes_min  the smallest size any call accepts; with less than the size
+ *                                 above, Top_k never builds the lists. */
 size_t sparsify_workspace_bytes(int64_t d_total, int32_t num_segments);
+size_t sparsify_workspace_bytes_min(int64_t d_total, int32_t num_segments);
 
 /* Gaussian_k compressor (Algorithm 1; accumulate and residual of Eq. (2)).
  *   d, k      vector length and target number of survivors

@@ -53,6 +53,8 @@ struct SegCtrl {
   uint32_t sel_krem[8];     //   (one slot per choice: a kernel reads one slot and writes the next)
   uint32_t topk_key;        // fused flat paths: the k-th key and the ties to keep
   uint32_t topk_take;
+  uint32_t tau_key;         // short-list form (topk_list.h): entries with a larger key are listed
+  uint32_t list_mode;       //   1 once the kernel after the accumulate kernel found the lists usable
 };
 
 struct Args {
@@ -96,6 +98,13 @@ struct Args {
   int64_t sample_m;       // number of strata = sample size
   int64_t sample_k;       // rank of the threshold inside the sample
   uint64_t sample_seed;
+  // Top_k, short-list form (topk_list.h); `list` is null when the call does not use it
+  uint2* list;            // (index, bits of acc): every wave appends to its own stretch
+  uint2* run_table;       // [chunks * 16]: (first entry, entries) of each 256-element run
+  uint32_t* worker_info;  // [list_workers]: entries the wave listed, or kListOverflow
+  uint32_t list_workers;  // waves of the accumulate kernel
+  uint32_t list_cap;      // entries per wave
+  uint32_t list_last;     // index of the buffer's last entry
 };
 
 // Tile j of a segment covers the absolute range [base + j*E, base + (j+1)*E) cut to

@@ -105,12 +105,25 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
 // replicas of each segment's global histogram: spreads same-address atomics of the flat call
 uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
 
+// Short-list Top_k (topk_list.h): flat vectors long enough for the passes saved to matter, short
+// enough for the resident accumulate kernel.  The list buffer holds kListShare of the vector's
+// length in entries (the lists are expected to take max(4 k, 0.4 % of d)), split evenly among the
+// accumulate kernel's waves.
+constexpr int64_t kListFrom = 2'000'000;
+constexpr double kListShare = 0.10;
+constexpr uint32_t kListMaxWorkers = kWaves * kMaxMomentParts;
+bool list_sized(int64_t d_total, int32_t L) {
+  return L == 1 && d_total >= kListFrom && (d_total + kChunk - 1) / kChunk <= (int64_t)kChunkGridFrom;
+}
+size_t list_entries(int64_t d_total) { return (size_t)(kListShare * (double)d_total) + 64 * (size_t)kListMaxWorkers; }
+
 struct Carve {
   size_t ctrl, tile_start, partial, folded, tile_counts, tile_base, tie_base, group_counts, seg_groups,
       norm_partial, hist, tile_hist, total;
+  size_t list, run_table, worker_info;  // with lists only
   uint32_t max_groups;
 };
-Carve carve(int64_t d_total, int32_t L) {
+Carve carve(int64_t d_total, int32_t L, bool lists = false) {
   const size_t mt = max_tiles_of(d_total, L, 1);
   Carve c;
   size_t off = 0;
@@ -132,6 +145,13 @@ Carve carve(int64_t d_total, int32_t L) {
   // per-tile histograms of the last digit: flat Top_k in place, at most kFusedMaxTiles tiles
   const size_t hist_tiles = mt < (size_t)kFusedMaxTiles ? mt : (size_t)kFusedMaxTiles;
   c.tile_hist = off;   off = align_up(off + sizeof(uint32_t) * kLastDigitBins * hist_tiles);
+  c.list = c.run_table = c.worker_info = 0;
+  if (lists) {  // appended, so that the layout above does not depend on them
+    const size_t chunks = (size_t)((d_total + kChunk - 1) / kChunk);
+    c.worker_info = off; off = align_up(off + sizeof(uint32_t) * kListMaxWorkers);
+    c.run_table = off;   off = align_up(off + sizeof(uint2) * chunks * kRunsPerChunk);
+    c.list = off;        off = align_up(off + sizeof(uint2) * list_entries(d_total));
+  }
   c.total = off;
   return c;
 }
@@ -164,9 +184,17 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
     if (!(tail_div >= 1.0) || !(tail_div <= 1e300) || (ddof != 0 && ddof != 1))
       return SPARSIFY_E_INVALID;
   }
-  const Carve cv = carve(d_total, L);
+  Carve cv = carve(d_total, L);
   if (!workspace || misaligned(workspace, kAlign) || workspace_bytes < cv.total)
     return SPARSIFY_E_WORKSPACE;
+  bool lists = false;
+  if (list_sized(d_total, L)) {  // the larger layout extends the smaller one
+    const Carve big = carve(d_total, L, true);
+    if (workspace_bytes >= big.total) {
+      cv = big;
+      lists = true;
+    }
+  }
 
   const size_t vec = sizeof(float) * (size_t)d_total;
   const Range rg = range_of(grad, vec), rr = range_of(residual, vec), ra = range_of(acc, vec);
@@ -208,6 +236,11 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
   a.tile_hist = reinterpret_cast<uint32_t*>(w + cv.tile_hist);
   a.hist_copies = hist_copies_of(L);
+  if (lists) {
+    a.list = reinterpret_cast<uint2*>(w + cv.list);
+    a.run_table = reinterpret_cast<uint2*>(w + cv.run_table);
+    a.worker_info = reinterpret_cast<uint32_t*>(w + cv.worker_info);
+  }
   a.tile_chunks = tile_chunks_of(d_total, false);
   if (opts && opts->tile_chunks != 0) {
     if (opts->tile_chunks < 0 || opts->tile_chunks > (1 << 20)) return SPARSIFY_E_INVALID;
@@ -292,23 +325,40 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   }
 }
 
+void launch_topk_flat_rest(Launcher& ln, const Args& a, uint32_t tiles, uint32_t nchunks, uint32_t resident);
+
 // Flat Top_k.  Separate acc: seven launches with candidate filtering (topk_filter.h); in place:
 // seven launches with three more digit passes over acc (topk_flat.h).  flat_call has checked
 // that the group tables hold `tiles`.
 void launch_topk_flat(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
-  const dim3 pg(tiles);
   const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
   static const uint32_t cus = compute_units();
+  const uint32_t resident = cus < nchunks ? cus : nchunks;
+  Args al = a;  // short-list form (topk_list.h): the first two launches differ, the rest is shared
+  if (a.list) {
+    al.list_workers = resident * kWaves;
+    al.list_cap = (uint32_t)(list_entries(a.d_total) / al.list_workers);
+    al.list_last = (uint32_t)(list_entries(a.d_total) - 1);
+    ln.run("topk_init", k_topk_init_list, dim3(32), blk, al, (uint32_t)kTopkHistWords);
+    ln.run("topk_accum_hist", k_topk_accum_list, dim3(resident), blk, al);
+  }
+  launch_topk_flat_rest(ln, al, tiles, nchunks, resident);
+}
+void launch_topk_flat_rest(Launcher& ln, const Args& a, uint32_t tiles, uint32_t nchunks, uint32_t resident) {
+  const dim3 blk(kBlock);
+  const dim3 pg(tiles);
   if (!a.inplace) {
     const bool big = nchunks > kChunkGridFrom;  // long vector: larger group tables
     // one wave per tile's candidate list, several lists per wave when there are many tiles
     uint32_t lists = (tiles + kWaves - 1) / kWaves;
     if (lists > 4096) lists = 4096;
     const dim3 cg(lists);
-    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
-    if (big) ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks), blk, a);
-    else ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
+    if (!a.list) {
+      ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
+      if (big) ln.run("topk_accum_hist", k_topk_accum_hist_chunks, dim3(nchunks), blk, a);
+      else ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(resident), blk, a);
+    }
     ln.run("topk_filter", k_topk_filter, pg, blk, a);
     ln.run("topk_cand2", k_topk_cand_hist, cg, blk, a, 2);
     ln.run("topk_cand3", k_topk_cand_hist, cg, blk, a, 3);
@@ -323,8 +373,10 @@ void launch_topk_flat(Launcher& ln, const Args& a, uint32_t tiles) {
       else ln.run("topk_compact", k_topk_compact_ordered<false, kGroupTiles, kMaxGroups, false>, pg, blk, a);
     }
   } else {
-    ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
-    ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(cus < nchunks ? cus : nchunks), blk, a);
+    if (!a.list) {
+      ln.run("topk_init", k_topk_init_fused, dim3(32), blk, a, (uint32_t)kTopkHistWords);
+      ln.run("topk_accum_hist", k_topk_accum_hist_resident, dim3(resident), blk, a);
+    }
     ln.run("topk_hist1", k_topk_hist_fused<false>, pg, blk, a, 1);
     ln.run("topk_hist2", k_topk_hist_fused<false>, pg, blk, a, 2);
     ln.run("topk_hist3", k_topk_hist_fused<true>, pg, blk, a, 3);
@@ -420,6 +472,11 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
+  // the short-list form: Top_k without the norms, k small enough for the lists' share of the
+  // workspace, where the workspace has room at all (prepare)
+  if (selector != kSelTopk || a.norms || (opts && opts->short_list < 0) ||
+      2.0 * kListAim * (double)k > kListShare * (double)d)
+    a.list = nullptr;
   if (!(opts && opts->tile_chunks != 0))
     a.tile_chunks = tile_chunks_of(d, selector == kSelGaussian || (selector == kSelTopk && !a.inplace));
   const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);
@@ -462,10 +519,16 @@ extern "C" {
 
 const char* sparsify_version(void) { return "sparsify 0.1 (gfx950)"; }
 
-size_t sparsify_workspace_bytes(int64_t d_total, int32_t num_segments) {
+size_t sparsify_workspace_bytes_min(int64_t d_total, int32_t num_segments) {
   if (d_total < 1 || d_total >= (int64_t(1) << 31) || num_segments < 1 || num_segments > (1 << 20))
     return 0;
   return carve(d_total, num_segments).total;
+}
+
+size_t sparsify_workspace_bytes(int64_t d_total, int32_t num_segments) {
+  if (d_total < 1 || d_total >= (int64_t(1) << 31) || num_segments < 1 || num_segments > (1 << 20))
+    return 0;
+  return carve(d_total, num_segments, list_sized(d_total, num_segments)).total;
 }
 
 int sparsify_gaussiank(int64_t d, int64_t k, const float* grad, float* residual, float* acc,

@@ -131,6 +131,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_filter(const Args a) {
   __shared__ uint32_t h[kWaves][256];
   __shared__ uint32_t lds_sel[kWaves + 3];
   __shared__ uint32_t lds_above[kWaves];
+  __shared__ uint32_t lds_lists[2 * kWaves];
   __shared__ uint32_t lds_cursor;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
@@ -143,6 +144,19 @@ __global__ __launch_bounds__(kBlock) void k_topk_filter(const Args a) {
   if (tile == 0 && threadIdx.x == 0) {
     c.sel_prefix[0] = dg.prefix;
     c.sel_krem[0] = dg.k_rem;
+  }
+  if (a.list) {  // short-list form (topk_list.h): if the lists serve, the second digit's histogram from them
+    const bool usable = lists_usable(a, lds_lists);
+    if (tile == 0 && threadIdx.x == 0) c.list_mode = usable ? 1u : 0u;
+    if (usable) {
+      list_digit_pass(a, 1, dg.prefix, h[wave_id()]);
+      __syncthreads();
+      uint32_t v = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) v += h[w][threadIdx.x];
+      if (v) atomicAdd(&pass_hist(a, 1)[(blockIdx.x % kTopkCopies) * 256 + threadIdx.x], v);
+      return;
+    }
   }
   uint32_t* cand = tile_candidates(a, tile);
   uint32_t above = 0;
@@ -210,11 +224,15 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const Args a, int pas
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
   uint32_t* hw = h[wave_id()];
-  // one wave per list; with more lists than waves in the grid a wave takes several
-  for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
-    for_each_candidate(a, tile, ntiles, [&](uint32_t key, bool valid) {
-      wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
-    });
+  if (c.list_mode) {  // short-list form: the accumulate kernel's lists instead of the filter's
+    list_digit_pass(a, pass, dg.prefix, hw);
+  } else {
+    // one wave per list; with more lists than waves in the grid a wave takes several
+    for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
+      for_each_candidate(a, tile, ntiles, [&](uint32_t key, bool valid) {
+        wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
+      });
+    }
   }
   __syncthreads();
   const int bin = threadIdx.x;
@@ -242,6 +260,11 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final(const Args a) {
     sparsify_result& r = a.result[0];
     r.topk_key = T;
     r.topk_ties_taken = dg.k_rem;
+    if (a.list) r.flags = c.list_mode ? SPARSIFY_F_SHORTLIST : SPARSIFY_F_SHORTLIST_MISS;  // which way, no result
+  }
+  if (c.list_mode) {  // short-list form
+    list_tile_counts<GT>(a, T, rank_ties);
+    return;
   }
   const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
   for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
@@ -309,6 +332,10 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered(const Args a) {
   __syncthreads();
   uint32_t tie_run = lds_base[1];
   uint32_t out_run = lds_base[0] + (tie_run < take ? tie_run : take);
+  if (c.list_mode) {  // short-list form: the tile's pairs from the lists, by one wave
+    if (wave_id() == 0) list_compact_tile(a, tile, o.T, take, rank_ties, out_run, tie_run);
+    return;
+  }
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
     const Tile t = chunk_of(sp_, u);

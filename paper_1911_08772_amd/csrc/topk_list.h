@@ -1,0 +1,439 @@
+// Exact Top_k, flat vectors, the short-list form.  Before the accumulate pass one workgroup
+// takes a sample of acc and sets a listing key tau a little below where the k-th key is expected
+// (the sample's quantile for about four times k entries).  The accumulate kernel then, besides
+// acc and the first digit's histogram, writes the residual (as if nothing were selected) and a
+// list of every entry whose key exceeds tau.  If the lists hold at least k entries they hold the
+// k largest (every key >= the k-th key exceeds tau), and everything that follows reads the lists,
+// a fraction of a per cent of the vector, instead of acc: the three remaining digit passes, the
+// per-tile counts, and the compaction, which only clears the selected entries of the residual.
+// 16 bytes per element instead of 24 (12 instead of 28 in place).
+//
+// The guess cannot make the result wrong.  Whether the lists are used is decided from their
+// exact length; if they are too short (a sample that misleads: a constant vector, say) or a
+// list ran out of room, every later kernel of the call takes its other body, the form without
+// lists (topk_filter.h, or topk_flat.h in place), which overwrites whatever the accumulate
+// kernel put into the residual.  The launch sequence is the same either way.
+//
+// Lists are kept per wave of the accumulate kernel: a wave appends the entries of each
+// 256-element run it streams (one wave instruction's worth of a chunk, in index order) to its
+// own stretch of the list buffer and records (first entry, entries) per run, so that later
+// kernels find the entries of a tile in index order.
+#pragma once
+#include "common.h"
+#include "tile_io.h"
+#include "gaussiank.h"
+#include "topk.h"
+#include "topk_select.h"
+
+namespace sp {
+
+constexpr int kRun = 256;                         // elements per run: 64 lanes x 4
+constexpr int kRunsPerChunk = kChunk / kRun;      // 16
+constexpr uint32_t kListOverflow = 0xFFFFFFFFu;   // worker_info: the wave's stretch ran out
+constexpr int kListSample = 16 * kBlock;          // entries of acc the init kernel looks at
+constexpr int kListAim = 4;                       // the lists should hold about this many times k
+
+// ---- the listing key (one workgroup, inside the init kernel) -------------------------------------
+// 4096 entries of acc, four consecutive ones every d/1024 elements; tau is the lower edge of the
+// 16-bit key bin (sign dropped: exponent and eight mantissa bits) that holds the sample's r-th
+// largest key, r = the sample's share of kListAim * k entries, at least 16.  `lds_h` holds 256
+// words, `lds_sel` kWaves + 3.
+__device__ inline uint32_t sample_listing_key(const Args& a, uint32_t* lds_h, uint32_t* lds_sel) {
+  const int64_t stride4 = (a.d_total / 4) / (kListSample / 4);  // >= 1: the host asks for d >= 4 * kListSample
+  uint32_t key[16];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = (int64_t)(u * kBlock + (int)threadIdx.x) * stride4 * 4;
+    const f32x4 g = *reinterpret_cast<const f32x4*>(a.grad + i);
+    const f32x4 e = *reinterpret_cast<const f32x4*>(a.resid + i);
+    key[4 * u + 0] = mag_key(g.x + e.x);
+    key[4 * u + 1] = mag_key(g.y + e.y);
+    key[4 * u + 2] = mag_key(g.z + e.z);
+    key[4 * u + 3] = mag_key(g.w + e.w);
+  }
+  uint64_t want = ((uint64_t)kListAim * (uint64_t)a.flat_k * kListSample + (uint64_t)a.d_total - 1) / (uint64_t)a.d_total;
+  if (want < 16) want = 16;
+  if (want > kListSample) want = kListSample;
+  uint32_t prefix = 0, rank = (uint32_t)want;
+#pragma unroll 1
+  for (int pass = 0; pass < 2; ++pass) {
+    lds_h[threadIdx.x] = 0;
+    __syncthreads();
+    const int shift = digit_shift(pass), hi_shift = digit_shift(pass - 1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (pass == 0 || (key[i] >> hi_shift) == prefix) atomicAdd(&lds_h[(key[i] >> shift) & 255u], 1u);
+    __syncthreads();
+    const Digit dg = digit_from_bins(lds_h[255u - threadIdx.x], pass, prefix, rank, lds_sel);  // barriers
+    prefix = dg.prefix;
+    rank = dg.k_rem;
+  }
+  return prefix << digit_shift(1);
+}
+
+// Clears the histograms and the group totals, resets the selection state (k_topk_init_fused) and
+// sets the listing key.
+__global__ __launch_bounds__(kBlock) void k_topk_init_list(const Args a, uint32_t hist_words) {
+  __shared__ uint32_t lds_h[256];
+  __shared__ uint32_t lds_sel[kWaves + 3];
+  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < hist_words; i += gridDim.x * kBlock)
+    a.hist[i] = 0;
+  if (blockIdx.x != 0) return;
+  for (uint32_t i = threadIdx.x; i < (uint32_t)(kBigMaxGroups * kNumThres); i += kBlock)
+    a.group_counts[i] = 0;
+  const uint32_t tau = sample_listing_key(a, lds_h, lds_sel);
+  if (threadIdx.x == 0) {
+    SegCtrl& c = a.ctrl[0];
+    c.prefix = 0;
+    c.k_rem = (uint32_t)a.flat_k;
+    c.n_eq = 0;
+    c.rank_ties = 0;
+    c.select_none = 0;
+    c.bad = 0;
+    c.tau_key = tau;
+    c.list_mode = 0;
+    sparsify_result& r = a.result[0];
+    clear_result(r);
+    r.nnz = (uint32_t)a.flat_k;
+  }
+}
+
+// ---- the accumulate kernel with lists -------------------------------------------------------------
+// A wave's position in its stretch of the list buffer (wave-uniform).
+struct ListCursor {
+  uint32_t cur, end;
+  bool over;
+};
+
+// Appends the entries of this wave's four runs of a chunk and records the runs.  `v` holds acc.
+template <bool FULL>
+__device__ inline void list_chunk(const Args& a, int64_t tbase, const float (&v)[kPerThread],
+                                  uint32_t valid, uint32_t tau, ListCursor& lc) {
+  uint32_t off[kSlots], cnt[kSlots];
+#pragma unroll
+  for (int j = 0; j < kSlots; ++j) {
+    bool in[4];
+    uint32_t tot = 0, mine = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bool ok = FULL || ((valid >> (4 * j + q)) & 1u);
+      in[q] = ok && (mag_key(v[4 * j + q]) > tau);
+      const uint64_t m = __ballot(in[q]);
+      tot += (uint32_t)__builtin_popcountll(m);
+      mine += lanes_below(m);
+    }
+    if (tot > lc.end - lc.cur) lc.over = true;  // sticky: nothing more is appended
+    off[j] = lc.cur;
+    cnt[j] = lc.over ? 0u : tot;
+    if (!lc.over && tot != 0) {
+      uint32_t pos = lc.cur + mine;
+      const uint32_t i0 = (uint32_t)(tbase + (int64_t)(j * kBlock + (int)threadIdx.x) * 4);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (in[q]) {
+          a.list[pos] = make_uint2(i0 + q, __float_as_uint(v[4 * j + q]));
+          ++pos;
+        }
+      }
+      lc.cur += tot;
+    }
+  }
+  if (lane_id() < kSlots) {  // run (chunk, slot j, wave w) covers elements [256 r, 256 r + 256)
+    const int j = lane_id();
+    const uint32_t o = j == 0 ? off[0] : j == 1 ? off[1] : j == 2 ? off[2] : off[3];
+    const uint32_t c = j == 0 ? cnt[0] : j == 1 ? cnt[1] : j == 2 ? cnt[2] : cnt[3];
+    a.run_table[(tbase / kRun) + j * kWaves + wave_id()] = make_uint2(o, c);
+  }
+}
+
+template <bool FULL>
+__device__ inline void accum_hist_list_chunk(const Args& a, const Tile& t, uint32_t* h, uint32_t tau,
+                                             ListCursor& lc) {
+  float g[kPerThread], e[kPerThread];
+  const uint32_t valid = load_tile<FULL>(a.grad, t, g);
+  load_tile<FULL>(a.resid, t, e);
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) g[i] = g[i] + e[i];  // Eq. (2): one fp32 add
+  if (!a.inplace) store_tile<FULL>(a.acc, t, g, valid);
+  store_tile<FULL>(a.resid, t, g, valid);  // the residual if nothing of this chunk is selected
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i)
+    if (FULL || ((valid >> i) & 1u)) atomicAdd(&h[mag_key(g[i]) >> 23], 1u);
+  list_chunk<FULL>(a, t.tbase, g, valid, tau, lc);
+}
+
+// A full chunk whose loads were issued earlier (accum_issue of gaussiank.h).
+__device__ inline void accum_hist_list_finish(const Args& a, int64_t tbase, AccIn& in, uint32_t* h,
+                                              uint32_t tau, ListCursor& lc) {
+  const Tile t = full_chunk_at(tbase);
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) in.g[i] = in.g[i] + in.e[i];  // Eq. (2): one fp32 add
+  if (!a.inplace) store_tile<true>(a.acc, t, in.g, 0xFFFFu);
+  store_tile<true>(a.resid, t, in.g, 0xFFFFu);
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) atomicAdd(&h[mag_key(in.g[i]) >> 23], 1u);
+  list_chunk<true>(a, tbase, in.g, 0xFFFFu, tau, lc);
+}
+
+// The resident accumulate kernel of topk_filter.h plus the residual write and the lists, with
+// the next chunk's loads in flight while this one is worked on (two register sets in turn, no
+// load behind a branch inside the loop: see k_accum_moments_fused).
+__global__ __launch_bounds__(kBlock) void k_topk_accum_list(const Args a) {
+  __shared__ uint32_t h[kWaves][256];
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t tau = a.ctrl[0].tau_key;
+  const uint32_t worker = blockIdx.x * kWaves + wave_id();
+  ListCursor lc;
+  lc.cur = worker * a.list_cap;
+  lc.end = lc.cur + a.list_cap;
+  lc.over = false;
+  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  const uint32_t nfull = (uint32_t)(a.d_total / kChunk);
+  const uint32_t step = gridDim.x;
+  const uint32_t n = blockIdx.x < nfull ? (nfull - blockIdx.x + step - 1) / step : 0u;  // my full chunks
+  auto at = [&](uint32_t k) { return (int64_t)(blockIdx.x + k * step) * kChunk; };
+  uint32_t* hw = h[wave_id()];
+  if (n > 0) {
+    AccIn x, y;
+    uint32_t k = 0;
+    accum_issue(a, at(0), x);
+    while (k + 2 < n) {
+      accum_issue(a, at(k + 1), y);
+      __builtin_amdgcn_sched_barrier(0);
+      accum_hist_list_finish(a, at(k), x, hw, tau, lc);
+      accum_issue(a, at(k + 2), x);
+      __builtin_amdgcn_sched_barrier(0);
+      accum_hist_list_finish(a, at(k + 1), y, hw, tau, lc);
+      k += 2;
+    }
+    if (n - k == 2) {
+      accum_issue(a, at(k + 1), y);
+      __builtin_amdgcn_sched_barrier(0);
+      accum_hist_list_finish(a, at(k), x, hw, tau, lc);
+      accum_hist_list_finish(a, at(k + 1), y, hw, tau, lc);
+    } else {
+      accum_hist_list_finish(a, at(k), x, hw, tau, lc);
+    }
+  }
+  if (nfull < nchunks && nfull % step == blockIdx.x) {  // the ragged last chunk
+    Tile t;
+    t.seg = 0;
+    t.tbase = (int64_t)nfull * kChunk;
+    t.lo = t.tbase;
+    t.hi = a.d_total;
+    t.full = false;
+    accum_hist_list_chunk<false>(a, t, hw, tau, lc);
+  }
+  if (lane_id() == 0) a.worker_info[worker] = lc.over ? kListOverflow : lc.cur - worker * a.list_cap;
+  __syncthreads();
+  const int bin = threadIdx.x;
+  uint32_t v = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) v += h[w][bin];
+  if (v) atomicAdd(&pass_hist(a, 0)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+}
+
+// ---- reading the lists -----------------------------------------------------------------------------
+// Whether the lists can serve the call: no stretch ran out and they hold at least k entries.
+// Computed the same way by every workgroup of the kernel that follows the accumulate kernel
+// (`lds` holds 2 * kWaves words; one barrier); the first tile's workgroup publishes it.
+__device__ inline bool lists_usable(const Args& a, uint32_t* lds) {
+  const uint32_t nworkers = a.list_workers;
+  uint32_t over = 0, total = 0;
+  for (uint32_t i0 = 0; i0 < nworkers; i0 += 4 * kBlock) {
+    uint32_t w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // all loads first, none behind a branch
+      const uint32_t i = i0 + u * kBlock + threadIdx.x;
+      w[u] = a.worker_info[i < nworkers ? i : nworkers - 1u];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool mine = i0 + u * kBlock + threadIdx.x < nworkers;
+      over |= (mine && w[u] == kListOverflow) ? 1u : 0u;
+      total += (mine && w[u] != kListOverflow) ? w[u] : 0u;
+    }
+  }
+  total = wave_sum(total);
+  const uint64_t any_over = __ballot(over != 0);
+  if (lane_id() == 0) {
+    lds[2 * wave_id()] = total;
+    lds[2 * wave_id() + 1] = any_over != 0 ? 1u : 0u;
+  }
+  __syncthreads();
+  uint32_t t = 0, o = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    t += lds[2 * w];
+    o |= lds[2 * w + 1];
+  }
+  return o == 0 && (int64_t)t >= a.flat_k;
+}
+
+// the runs of a tile (every chunk has kRunsPerChunk records, empty ones beyond the vector's end)
+__device__ inline void tile_runs(const Args& a, uint32_t tile, uint32_t* r0, uint32_t* r1) {
+  const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+  const uint32_t c0 = tile * a.tile_chunks;
+  const uint32_t c1 = c0 + a.tile_chunks < nchunks ? c0 + a.tile_chunks : nchunks;
+  *r0 = c0 * kRunsPerChunk;
+  *r1 = c1 * kRunsPerChunk;
+}
+
+__device__ inline uint32_t wave_max(uint32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t o = __shfl_xor(v, off, 64);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+// One lane per run of the tile, 64 runs at a time: the lanes fetch their runs' records, then
+// their runs' entries four at a time.  No load sits behind a branch (a wave would wait for each
+// before it issues the next): a lane past the end of its run re-reads the run's last entry (an
+// empty run the entry at its offset), kept inside the buffer, and reports it as not valid.
+// fn(entry, valid) is called by the whole wave; the order of the calls is not the index order.
+constexpr int kListBatch = 4;
+template <typename F>
+__device__ inline void for_each_list_entry(const Args& a, uint32_t tile, F fn) {
+  uint32_t r0, r1;
+  tile_runs(a, tile, &r0, &r1);
+  for (uint32_t rb = r0; rb < r1; rb += 64) {
+    const uint32_t r = rb + lane_id();
+    const uint2 rec = a.run_table[r < r1 ? r : r1 - 1u];
+    const uint32_t n = r < r1 ? rec.y : 0u, off = rec.x;
+    const uint32_t last = n ? n - 1u : 0u;
+    const uint32_t nmax = wave_max(n);
+    for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
+      uint2 e[kListBatch];
+#pragma unroll
+      for (int u = 0; u < kListBatch; ++u) {
+        uint32_t i = off + (i0 + u < last ? i0 + u : last);
+        i = i < a.list_last ? i : a.list_last;
+        e[u] = a.list[i];
+      }
+#pragma unroll
+      for (int u = 0; u < kListBatch; ++u)
+        if (i0 + u < nmax) fn(e[u], i0 + u < n);  // wave-uniform condition
+    }
+  }
+}
+
+// A digit pass over the lists: the histogram of digit `pass` among the listed keys whose higher
+// digits equal `prefix`, one wave per tile (any grid), into the wave's LDS histogram `hw`.
+__device__ inline void list_digit_pass(const Args& a, int pass, uint32_t prefix, uint32_t* hw) {
+  const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  const int hi_shift = digit_shift(pass - 1);
+  const int shift = digit_shift(pass);
+  const uint32_t mask = (1u << digit_bits(pass)) - 1u;
+  for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
+    for_each_list_entry(a, tile, [&](uint2 e, bool valid) {
+      const uint32_t key = e.y & 0x7FFFFFFFu;
+      wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == prefix);
+    });
+  }
+}
+
+// Per tile, from the lists: the survivors (keys above T, plus the keys equal to T when all of
+// those are kept) and, when ties are ranked, the keys equal to T; per-group totals by atomics.
+// One wave per tile (any grid).
+template <int GT>
+__device__ inline void list_tile_counts(const Args& a, uint32_t T, bool rank_ties) {
+  const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {
+    uint32_t gt = 0, eq = 0;
+    for_each_list_entry(a, tile, [&](uint2 e, bool valid) {
+      const uint32_t key = e.y & 0x7FFFFFFFu;
+      gt += (valid && key > T) ? 1u : 0u;
+      eq += (valid && key == T) ? 1u : 0u;
+    });
+    gt = wave_sum(gt);
+    eq = wave_sum(eq);
+    if (lane_id() == 0) {
+      const uint32_t taken = gt + (rank_ties ? 0u : eq);
+      tile_row(a, kRowTake)[tile] = taken;
+      uint32_t* grp = a.group_counts + (tile / GT) * kNumThres;
+      if (taken) atomicAdd(&grp[kColTake], taken);
+      if (rank_ties) {
+        tile_row(a, kRowTies)[tile] = eq;
+        if (eq) atomicAdd(&grp[kColTies], eq);
+      }
+    }
+  }
+}
+
+// The pairs of one tile from its lists, in index order, by one wave: `out_run` survivors and
+// `tie_run` keys equal to T precede the tile (ties before it capped by the caller).  A lane owns
+// a run; the lanes' counts are scanned across the wave, then every lane writes its run's
+// survivors one after the other and clears them in the residual.
+__device__ inline void list_compact_tile(const Args& a, uint32_t tile, uint32_t T, uint32_t take,
+                                         bool rank_ties, uint32_t out_run, uint32_t tie_run) {
+  uint32_t r0, r1;
+  tile_runs(a, tile, &r0, &r1);
+  for (uint32_t rb = r0; rb < r1; rb += 64) {
+    const uint32_t r = rb + lane_id();
+    const uint2 rec = a.run_table[r < r1 ? r : r1 - 1u];
+    const uint32_t n = r < r1 ? rec.y : 0u, off = rec.x;
+    const uint32_t last = n ? n - 1u : 0u;
+    const uint32_t nmax = wave_max(n);
+    uint32_t csel = 0, ceq = 0;
+    for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
+      uint2 e[kListBatch];
+#pragma unroll
+      for (int u = 0; u < kListBatch; ++u) {
+        uint32_t i = off + (i0 + u < last ? i0 + u : last);
+        i = i < a.list_last ? i : a.list_last;
+        e[u] = a.list[i];
+      }
+#pragma unroll
+      for (int u = 0; u < kListBatch; ++u) {
+        const uint32_t key = e[u].y & 0x7FFFFFFFu;
+        const bool valid = i0 + u < n;
+        csel += (valid && (key > T || (!rank_ties && key == T))) ? 1u : 0u;
+        ceq += (valid && rank_ties && key == T) ? 1u : 0u;
+      }
+    }
+    // ties in index order: this lane's come after those of the lanes below
+    const uint32_t ties_inc = wave_inclusive_scan(ceq);
+    const uint32_t ties_before = tie_run + ties_inc - ceq;
+    const uint32_t room = take > ties_before ? take - ties_before : 0u;
+    const uint32_t kept_ties = ceq < room ? ceq : room;
+    const uint32_t mine = csel + kept_ties;
+    const uint32_t inc = wave_inclusive_scan(mine);
+    uint32_t pos = out_run + inc - mine;
+    uint32_t tie_pos = ties_before;
+    for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
+      uint2 e[kListBatch];
+#pragma unroll
+      for (int u = 0; u < kListBatch; ++u) {
+        uint32_t i = off + (i0 + u < last ? i0 + u : last);
+        i = i < a.list_last ? i : a.list_last;
+        e[u] = a.list[i];
+      }
+#pragma unroll
+      for (int u = 0; u < kListBatch; ++u) {
+        const uint32_t key = e[u].y & 0x7FFFFFFFu;
+        const bool valid = i0 + u < n;
+        bool sel = valid && (key > T || (!rank_ties && key == T));
+        if (valid && rank_ties && key == T) {
+          sel = tie_pos < take;
+          ++tie_pos;
+        }
+        if (sel) {
+          if ((int64_t)pos < a.flat_cap) {
+            a.out_idx[pos] = e[u].x;
+            a.out_val[pos] = __uint_as_float(e[u].y);
+          }
+          a.resid[e[u].x] = 0.0f;
+          ++pos;
+        }
+      }
+    }
+    out_run += __shfl(inc, 63, 64);
+    tie_run += __shfl(ties_inc, 63, 64);
+  }
+}
+
+}  // namespace sp

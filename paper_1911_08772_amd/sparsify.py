@@ -15,6 +15,8 @@ from . import build as _build
 
 OK, E_INVALID, E_WORKSPACE, E_LAUNCH = 0, 1, 2, 3
 F_OVERFLOW, F_NONFINITE, F_EXHAUSTED, F_BADSEGMENT = 1, 2, 4, 8
+F_SHORTLIST, F_SHORTLIST_MISS = 16, 32      # which way a flat Top_k call took, not a result
+F_WAY = F_SHORTLIST | F_SHORTLIST_MISS
 
 RESULT_DTYPE = np.dtype([("nnz", "<u4"), ("rounds", "<u4"), ("count", "<u4", (4,)),
                          ("flags", "<u4"), ("thres_f32", "<f4"), ("mean", "<f8"), ("std", "<f8"),
@@ -27,7 +29,7 @@ RESULT_BYTES = RESULT_DTYPE.itemsize  # 96
 class Opts(C.Structure):
     _fields_ = [("tail_div", C.c_double), ("ddof", C.c_int32), ("tile_chunks", C.c_int32),
                 ("trace", C.c_void_p), ("error_norms", C.c_int32), ("sample_stride", C.c_int32),
-                ("sample_seed", C.c_uint64)]
+                ("sample_seed", C.c_uint64), ("short_list", C.c_int32)]
 
 
 _p = C.c_void_p
@@ -35,6 +37,8 @@ lib = C.CDLL(_build.ensure_sparsify())
 lib.sparsify_version.restype = C.c_char_p
 lib.sparsify_workspace_bytes.argtypes = [C.c_int64, C.c_int32]
 lib.sparsify_workspace_bytes.restype = C.c_size_t
+lib.sparsify_workspace_bytes_min.argtypes = [C.c_int64, C.c_int32]
+lib.sparsify_workspace_bytes_min.restype = C.c_size_t
 _flat = [C.c_int64, C.c_int64, _p, _p, _p, _p, _p, C.c_int64, _p, _p, C.c_size_t,
          C.POINTER(Opts), _p]
 lib.sparsify_gaussiank.argtypes = _flat
@@ -55,7 +59,7 @@ lib.sparsify_trace_stage_name.argtypes = [_p, C.c_int32]
 lib.sparsify_trace_stage_name.restype = C.c_char_p
 lib.sparsify_trace_stage_ms.argtypes = [_p, C.c_int32, C.POINTER(C.c_float)]
 
-EXPORTS = ["sparsify_version", "sparsify_workspace_bytes", "sparsify_gaussiank", "sparsify_topk",
+EXPORTS = ["sparsify_version", "sparsify_workspace_bytes", "sparsify_workspace_bytes_min", "sparsify_gaussiank", "sparsify_topk",
            "sparsify_dgck", "sparsify_gaussiank_static", "sparsify_scatter_add",
            "sparsify_segmented", "sparsify_calibration_copy", "sparsify_trace_create", "sparsify_trace_destroy",
            "sparsify_trace_num_stages", "sparsify_trace_stage_name", "sparsify_trace_stage_ms"]
@@ -87,10 +91,10 @@ def _stream(stream) -> int:
 
 
 def _opts(tail_div: float, ddof: int, trace, tile_chunks: int = 0, error_norms: bool = False,
-          sample_stride: int = 0, sample_seed: int = 0) -> Opts:
+          sample_stride: int = 0, sample_seed: int = 0, short_list: int = 0) -> Opts:
     return Opts(float(tail_div), int(ddof), int(tile_chunks),
                 trace.handle if trace is not None else None, 1 if error_norms else 0,
-                int(sample_stride), int(sample_seed))
+                int(sample_stride), int(sample_seed), int(short_list))
 
 
 def version() -> str:
@@ -99,6 +103,10 @@ def version() -> str:
 
 def workspace_bytes(d_total: int, num_segments: int = 1) -> int:
     return int(lib.sparsify_workspace_bytes(d_total, num_segments))
+
+
+def workspace_bytes_min(d_total: int, num_segments: int = 1) -> int:
+    return int(lib.sparsify_workspace_bytes_min(d_total, num_segments))
 
 
 class Trace:
@@ -168,8 +176,8 @@ def sparsify_dgck(d, k, grad, residual, acc, out_idx, out_val, cap, result, work
 
 def sparsify_topk(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                   workspace_nbytes, trace=None, stream=None, check=True, tile_chunks=0,
-                  error_norms=False) -> int:
-    o = _opts(2.0, 1, trace, tile_chunks, error_norms)
+                  error_norms=False, short_list=0) -> int:
+    o = _opts(2.0, 1, trace, tile_chunks, error_norms, short_list=short_list)
     rc = lib.sparsify_topk(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                            _ptr(out_val), cap, _ptr(result), _ptr(workspace), workspace_nbytes,
                            C.byref(o), _stream(stream))

@@ -31,16 +31,24 @@ def test_result_record_layout_matches_header():
     assert S.RESULT_BYTES == 96
     assert S.RESULT_DTYPE.fields["mean"][1] == 32 and S.RESULT_DTYPE.fields["topk_key"][1] == 72
     assert S.RESULT_DTYPE.fields["acc_sqnorm"][1] == 80
-    assert C.sizeof(S.Opts) == 40 and S.Opts.sample_seed.offset == 32
+    assert C.sizeof(S.Opts) == 48 and S.Opts.sample_seed.offset == 32 and S.Opts.short_list.offset == 40
 
 
 def test_workspace_bytes():
     assert S.workspace_bytes(0, 1) == 0 and S.workspace_bytes(10, 0) == 0
     assert S.workspace_bytes(1 << 31, 1) == 0
-    small, big = S.workspace_bytes(1000, 1), S.workspace_bytes(66_034_000, 1)
+    assert S.workspace_bytes_min(0, 1) == 0 and S.workspace_bytes_min(1 << 31, 1) == 0
+    small, big = S.workspace_bytes_min(1000, 1), S.workspace_bytes_min(66_034_000, 1)
     assert 0 < small < big < 4 * 1024 * 1024
-    assert S.workspace_bytes(25_557_032, 54) > S.workspace_bytes(25_557_032, 1)
+    assert S.workspace_bytes_min(25_557_032, 54) > S.workspace_bytes_min(25_557_032, 1)
     assert small % 256 == 0 and big % 256 == 0
+    # the size to allocate adds Top_k's short lists for flat vectors of 2 M to 123 M elements:
+    # 0.1 entries of 8 bytes per element and the per-run records (8 bytes per 256 elements)
+    for d, L in ((1000, 1), (1_999_999, 1), (200_000_000, 1), (25_557_032, 54)):
+        assert S.workspace_bytes(d, L) == S.workspace_bytes_min(d, L)
+    for d in (2_000_000, 25_557_032, 66_034_000):
+        extra = S.workspace_bytes(d, 1) - S.workspace_bytes_min(d, 1)
+        assert 0.8 * d < extra < 0.9 * d + (3 << 20) and S.workspace_bytes(d, 1) % 256 == 0
 
 
 BASE = 0x7000_0000_0000  # fake, 256-byte aligned "device" addresses; never dereferenced
@@ -126,7 +134,7 @@ def test_static_workspace_call_rejects_long_vectors_before_anything_else():
                                      a["out_idx"], a["out_val"], a["cap"], a["result"], stream=0,
                                      check=False)
     assert rc == S.E_WORKSPACE
-    assert S.workspace_bytes(S.STATIC_MAX_D, 1) <= 6 << 20 < S.workspace_bytes(2 * S.STATIC_MAX_D, 1)
+    assert S.workspace_bytes_min(S.STATIC_MAX_D, 1) <= 6 << 20 < S.workspace_bytes_min(2 * S.STATIC_MAX_D, 1)
 
 
 def test_scatter_add_rejects_bad_arguments_before_any_launch():
