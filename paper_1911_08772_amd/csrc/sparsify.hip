@@ -109,7 +109,7 @@ uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 
 // enough for the resident accumulate kernel.  The list buffer holds kListShare of the vector's
 // length in entries (the lists are expected to take max(4 k, 0.4 % of d)), split evenly among the
 // accumulate kernel's waves.
-constexpr int64_t kListFrom = 2'000'000;
+constexpr int64_t kListFrom = 6'000'000;
 constexpr double kListShare = 0.10;
 constexpr uint32_t kListMaxWorkers = kWaves * kMaxMomentParts;
 bool list_sized(int64_t d_total, int32_t L) {

@@ -58,18 +58,21 @@ __device__ inline uint32_t load_tile(const float* __restrict__ p, const Tile& t,
   return valid;
 }
 
-template <bool FULL>
+// STREAM: data nobody reads again soon (non-temporal stores; full chunks only).
+template <bool FULL, bool STREAM = false>
 __device__ inline void store_tile(float* p, const Tile& t, const float (&v)[kPerThread],
                                   uint32_t valid) {
   if (FULL) {
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) {
-      float4 q;
+      f32x4 q;
       q.x = v[4 * j + 0];
       q.y = v[4 * j + 1];
       q.z = v[4 * j + 2];
       q.w = v[4 * j + 3];
-      *reinterpret_cast<float4*>(p + slot_index(t, j)) = q;
+      f32x4* dst = reinterpret_cast<f32x4*>(p + slot_index(t, j));
+      if (STREAM) __builtin_nontemporal_store(q, dst);
+      else *dst = q;
     }
     return;
   }

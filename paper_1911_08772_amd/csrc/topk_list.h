@@ -168,7 +168,10 @@ __device__ inline void accum_hist_list_finish(const Args& a, int64_t tbase, AccI
   const Tile t = full_chunk_at(tbase);
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) in.g[i] = in.g[i] + in.e[i];  // Eq. (2): one fp32 add
-  if (!a.inplace) store_tile<true>(a.acc, t, in.g, 0xFFFFu);
+  // (acc is not read again by this call when the lists serve, nor by the next call: its
+  // stores are marked non-temporal so that it does not displace the residual, which the next
+  // call reads first)
+  if (!a.inplace) store_tile<true, true>(a.acc, t, in.g, 0xFFFFu);
   store_tile<true>(a.resid, t, in.g, 0xFFFFu);
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) atomicAdd(&h[mag_key(in.g[i]) >> 23], 1u);

@@ -1,5 +1,5 @@
 """GPU parity of flat Top_k where the library builds short lists in the accumulate pass (vectors
-of 2 M elements and more, k up to d/80): the results must not depend on whether the lists end
+of 6 M elements and more, k up to d/80): the results must not depend on whether the lists end
 up being used, so every case is compared with the CPU oracle bit for bit, and the way the call
 took (reported in two informational flag bits) is checked against what the input was built to
 provoke: typical vectors take the lists; vectors that defeat the guess the lists are built on
@@ -15,7 +15,7 @@ from paper_1911_08772_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-D0 = 2_000_000  # the shortest vector that gets lists
+D0 = 6_000_000  # the shortest vector that gets lists
 
 
 def way(gpu):
@@ -23,7 +23,7 @@ def way(gpu):
 
 
 @pytest.mark.parametrize("inplace", [False, True])
-@pytest.mark.parametrize("d", [D0, 4_194_304, 4_194_304 + 1, 6_000_000 + 4095, 9_000_017])
+@pytest.mark.parametrize("d", [D0, 8_388_608, 8_388_608 + 1, 6_000_000 + 4095, 9_000_017])
 def test_typical_vectors_take_the_lists(d, inplace):
     gpu = FlatGpu(d, cap=d // 100 + 16, inplace=inplace)
     eps = np.zeros(d, np.float32)
@@ -36,7 +36,7 @@ def test_typical_vectors_take_the_lists(d, inplace):
 
 @pytest.mark.parametrize("inplace", [False, True])
 def test_heavy_tails_and_ranked_ties_from_the_lists(inplace):
-    d, k = 5_000_003, 5000
+    d, k = 7_000_003, 7000
     gpu = FlatGpu(d, cap=k, inplace=inplace)
     zero = np.zeros(d, np.float32)
     x = synth.student_t3(d, 55, 0, 1e-3)
@@ -46,7 +46,7 @@ def test_heavy_tails_and_ranked_ties_from_the_lists(inplace):
     # alone): only the lowest-index ones are kept, and those come from the lists in index order
     rng = np.random.default_rng(11)
     y = synth.normal(d, 56, 0, 0.01)
-    where = np.unique(np.concatenate([rng.integers(0, d, 6000), np.arange(1_234_000, 1_236_000)]))
+    where = np.unique(np.concatenate([rng.integers(0, d, 8000), np.arange(1_234_000, 1_237_000)]))
     y[where] = np.float32(0.0625)
     y[where[::3]] = np.float32(-0.0625)
     y[rng.integers(0, d, 300)] = np.float32(0.5)      # a few entries above the ties
@@ -73,28 +73,35 @@ def defeating_vectors(d, rng):
     n = rng.standard_normal(d).astype(np.float32)
     n[rng.integers(0, d, 3)] = np.float32(np.nan)     # NaN keys rank above Inf: they are the top
     out["nans"] = n
+    # one stretch a hundred times larger than the rest (a layer of another scale): every survivor
+    # sits there, and the few waves that stream it may or may not have room for their lists
+    w = rng.standard_normal(d).astype(np.float32)
+    w[1_000_000:1_200_000] *= np.float32(100.0)
+    out["one_loud_stretch"] = w
     return out
 
 
 @pytest.mark.parametrize("inplace", [False, True])
 def test_vectors_that_defeat_the_guess(inplace):
-    d, k = 2_300_000 + 77, 2300
+    d, k = 6_300_000 + 77, 6300
     rng = np.random.default_rng(77)
     zero = np.zeros(d, np.float32)
     gpu = FlatGpu(d, cap=k, inplace=inplace)
     expected = {"zeros": S.F_SHORTLIST_MISS, "constant": S.F_SHORTLIST_MISS,
                 "small_ints": S.F_SHORTLIST_MISS, "sample_sees_zeros": S.F_SHORTLIST_MISS,
-                "nans": S.F_SHORTLIST}
+                "nans": S.F_SHORTLIST, "one_loud_stretch": None}
     for name, acc in defeating_vectors(d, rng).items():
         gpu.set_residual(zero)
         check_flat("topk", gpu, acc, zero, k, what=f"{name} inplace={inplace}")
-        assert way(gpu) == expected[name], (name, inplace)
+        assert way(gpu) in (S.F_SHORTLIST, S.F_SHORTLIST_MISS)
+        if expected[name] is not None:
+            assert way(gpu) == expected[name], (name, inplace)
 
 
 def test_the_lists_can_be_declined():
     """short_list = -1, the error norms, k beyond d/80 and a workspace of the smaller size all
     take the passes over acc from the start: same results, no way reported."""
-    d, k = 2_100_000, 2100
+    d, k = 6_100_000, 6100
     g = synth.normal(d, 41, 0, 0.01)
     eps = synth.normal(d, 42, 0, 0.003)
     gpu = FlatGpu(d, cap=d // 50)
