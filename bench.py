@@ -31,6 +31,11 @@ GK_BYTES_PER_ELEM = 24   # r g, r eps, w acc | r acc (one count pass) | r acc, w
 # r g, r eps, w acc (+digit 1) | r acc (filter: candidates written out) | r acc, w eps'; the
 # candidate lists the three later digit passes read are data dependent and not counted
 TOPK_BYTES_PER_ELEM = 24
+# Top_k with short lists built in the accumulate pass (from 6 M elements, when the lists serve:
+# the result record says so): r g, r eps, w acc, w eps'; the lists, a fraction of a per cent of
+# the vector, are not counted.  In place: r g, r eps, w acc.
+TOPK_LIST_BYTES_PER_ELEM = 16
+TOPK_LIST_INPLACE_BYTES_PER_ELEM = 12
 GK_INPLACE_BYTES_PER_ELEM = 20   # the compaction pass only reads acc (and zeroes the survivors)
 TOPK_INPLACE_BYTES_PER_ELEM = 28  # no room for candidates: 12 + 3 full digit passes + r acc
 
@@ -40,6 +45,7 @@ class StageMeans(dict):
     interval between two events also contains whatever kept the host from enqueueing the next
     launch in time, so a single late step can lift an average)."""
     median = {}
+    listed = 0.0
 
 
 class Flat:
@@ -93,15 +99,17 @@ class Flat:
         for i in range(K):
             self.run(fn, W + i, trace=traces[i], result=records[i])
         self.stream.synchronize()
-        per, nnz, rounds = {}, [], []
+        per, nnz, rounds, listed = {}, [], [], 0
         for i in range(K):
             for name, ms in traces[i].stages():
                 per.setdefault(name, []).append(ms)
             r = S.decode_results(records[i])[0]
             nnz.append(int(r["nnz"]))
             rounds.append(int(r["rounds"]))
+            listed += 1 if int(r["flags"]) & S.F_SHORTLIST else 0
         stage = StageMeans({n: sum(v) / len(v) for n, v in per.items()})
         stage.median = {n: statistics.median(v) for n, v in per.items()}
+        stage.listed = listed / K   # share of the steps whose Top_k pairs came from the short lists
         return stage, nnz, rounds
 
     def spread(self, fn, repeats):
@@ -127,6 +135,14 @@ def gbps(bytes_per_elem, d, nnz_mean, ms):
     return (bytes_per_elem * d + 8.0 * nnz_mean) / (ms * 1e-3) / 1e9
 
 
+def topk_bytes_per_elem(listed, inplace):
+    """Algorithmic bytes per element of the Top_k path as run: `listed` of the steps took the
+    short-list way (16 B, 12 in place), the others the passes over acc (24 B, 28 in place)."""
+    a = TOPK_LIST_INPLACE_BYTES_PER_ELEM if inplace else TOPK_LIST_BYTES_PER_ELEM
+    b = TOPK_INPLACE_BYTES_PER_ELEM if inplace else TOPK_BYTES_PER_ELEM
+    return round(listed * a + (1.0 - listed) * b, 3)
+
+
 def dominant(stage, d):
     """The streaming kernel with the longest average duration and its algorithmic GB/s."""
     dom = max((n for n in stage if KERNEL_BYTES_PER_ELEM.get(n, 0) > 0), key=lambda n: stage[n])
@@ -148,7 +164,8 @@ def side_workload(S, torch, synth, name, K, W):
     tk_stage, _, _ = f.traced(S.sparsify_topk)
     dom, nbytes, dom_gbps = dominant(gk_stage, wl.d)
     g = gbps(GK_BYTES_PER_ELEM, wl.d, float(np.mean(gk_nnz)), gk_ms)
-    t = gbps(TOPK_BYTES_PER_ELEM, wl.d, float(wl.k), tk_ms)
+    tk_bpe = topk_bytes_per_elem(tk_stage.listed, False)
+    t = gbps(tk_bpe, wl.d, float(wl.k), tk_ms)
     out = {"workload": wl.describe(), "gradient_pool": pool, "steps": K, "warmup": W,
            "working_set_MB": round(12 * wl.d / 1e6, 1),
            "gaussiank": {"ms_per_step": round(gk_ms, 5), "GBps": round(g, 2),
@@ -158,6 +175,7 @@ def side_workload(S, torch, synth, name, K, W):
                          "kernel_ms_median": {n: round(v, 5) for n, v in gk_stage.median.items()}},
            "topk": {"ms_per_step": round(tk_ms, 5), "GBps": round(t, 2),
                     "pct_hbm_peak": round(100.0 * t / HBM_PEAK_GBPS, 2),
+                    "bytes_per_elem": tk_bpe, "steps_from_short_lists": tk_stage.listed,
                     "kernel_ms": {n: round(v, 5) for n, v in tk_stage.items()},
                     "kernel_ms_median": {n: round(v, 5) for n, v in tk_stage.median.items()}},
            "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 2),
@@ -289,7 +307,7 @@ def main() -> int:
         fi = Flat(S, torch, wl, grads, K, W, True)
         extras["inplace"] = {"gaussiank_ms": round(fi.timed(S.sparsify_gaussiank)[1], 5),
                              "topk_ms": round(fi.timed(S.sparsify_topk)[1], 5),
-                             "note": "acc == residual: 20 B per element for Gaussian_k"}
+                             "note": "acc == residual: 20 B per element for Gaussian_k, 12 for Top_k when its short lists serve (28 otherwise)"}
         del fi
         # layer-wise call: 54 segments of the same total length, one launch sequence per step
         if wl.d == 25_557_032:
@@ -320,7 +338,7 @@ def main() -> int:
         extras["scatter_add"] = scatter_add_bench(S, torch, wl, grads, K, W)
 
     gk_bpe = GK_INPLACE_BYTES_PER_ELEM if args.inplace else GK_BYTES_PER_ELEM
-    tk_bpe = TOPK_INPLACE_BYTES_PER_ELEM if args.inplace else TOPK_BYTES_PER_ELEM
+    tk_bpe = topk_bytes_per_elem(tk_stage.listed, args.inplace)
     gk_gbps = gbps(gk_bpe, d, float(np.mean(gk_nnz)), gk_ms)
     tk_gbps = gbps(tk_bpe, d, float(k), tk_ms)
     dom, dom_bytes, dom_gbps = dominant(gk_stage, d)
@@ -354,7 +372,8 @@ def main() -> int:
         "topk": {"ms_per_step": round(tk_ms, 5), "GBps": round(tk_gbps, 2),
                  "elements_per_s": round(d / (tk_ms * 1e-3), 1),
                  "pct_hbm_peak": round(100.0 * tk_gbps / HBM_PEAK_GBPS, 2),
-                 "bytes_per_elem": tk_bpe, "spread": tk_spread,
+                 "bytes_per_elem": tk_bpe, "steps_from_short_lists": tk_stage.listed,
+                 "spread": tk_spread,
                  # context only (Sec. 3.3: a tensor library's topk() on a Tesla V100, same d and k)
                  "paper_v100_ms": 400.0 if (wl.d == 25_557_032 and k == 25_558) else None,
                  "kernel_ms": {n: round(v, 5) for n, v in tk_stage.items()},

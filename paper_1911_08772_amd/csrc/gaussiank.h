@@ -101,11 +101,12 @@ __device__ inline void accum_issue(const Args& a, int64_t tbase, AccIn& in) {
   load_tile<true, true>(a.grad, t, in.g);
   load_tile<true>(a.resid, t, in.e);
 }
+template <bool STREAM = false>
 __device__ inline void accum_finish(const Args& a, int64_t tbase, AccIn& in, MomAcc& m) {
   const Tile t = full_chunk_at(tbase);
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) in.g[i] = in.g[i] + in.e[i];  // Eq. (2): one fp32 add
-  store_tile<true>(a.acc, t, in.g, 0xFFFFu);
+  store_tile<true, STREAM>(a.acc, t, in.g, 0xFFFFu);
   if (!m.have_pivot) {  // wave-uniform: the first element the wave meets
     m.pivot = (double)__shfl(in.g[0], 0, 64);
     m.have_pivot = true;

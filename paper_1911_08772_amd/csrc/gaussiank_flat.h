@@ -30,6 +30,7 @@ constexpr int kMaxMomentParts = 1024;                             // accumulate 
 // plus one more workgroup that streams nothing: it clears the group totals the count kernel adds
 // into and computes the normal quantile (a few microseconds of dependent fp64 arithmetic in one
 // thread, which would otherwise stick out at the end of a workgroup that also streams).
+template <bool STREAM>  // acc is stored with the non-temporal hint (the host picks by the vector length)
 __global__ __launch_bounds__(kBlock) void k_accum_moments_fused(const Args a) {
   __shared__ double lds[4 * kWaves];
   if (blockIdx.x == a.moment_parts) {
@@ -58,19 +59,19 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_fused(const Args a) {
     while (k + 2 < n) {
       accum_issue(a, at(k + 1), y);
       __builtin_amdgcn_sched_barrier(0);  // nothing of the work below moves above the loads
-      accum_finish(a, at(k), x, m);
+      accum_finish<STREAM>(a, at(k), x, m);
       accum_issue(a, at(k + 2), x);
       __builtin_amdgcn_sched_barrier(0);
-      accum_finish(a, at(k + 1), y, m);
+      accum_finish<STREAM>(a, at(k + 1), y, m);
       k += 2;
     }
     if (n - k == 2) {
       accum_issue(a, at(k + 1), y);
       __builtin_amdgcn_sched_barrier(0);
-      accum_finish(a, at(k), x, m);
-      accum_finish(a, at(k + 1), y, m);
+      accum_finish<STREAM>(a, at(k), x, m);
+      accum_finish<STREAM>(a, at(k + 1), y, m);
     } else {
-      accum_finish(a, at(k), x, m);
+      accum_finish<STREAM>(a, at(k), x, m);
     }
   }
   // the ragged last chunk, if there is one, belongs to the workgroup whose turn it is

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -266,6 +267,10 @@ uint32_t compute_units() {
 // do not: acc then no longer displaces the new residual, which the next call's accumulate kernel
 // reads first.  Measured over chains of calls: 8 % faster per call at 42 M elements, 7 % at 50 M,
 // 1 % at 67 M; no difference at 25.6 M and 33.5 M; 2 % slower at 100 M.
+// In the same range the Gaussian_k accumulate kernel (separate acc) stores acc with that hint:
+// the count kernel then finds less of acc in the cache and slows down, the accumulate kernel gains
+// more (per call: 2 % faster at 50 M elements, 4 % at 59 M, 5 % at 66 M; no difference at 42 M;
+// 3-5 % slower at 84 M and 100 M, and slightly slower at 25.6 M, where it is not used).
 constexpr int64_t kStreamAccFrom = 40'000'000, kStreamAccBelow = 80'000'000;
 bool stream_acc(const Args& a) { return a.d_total >= kStreamAccFrom && a.d_total < kStreamAccBelow; }
 
@@ -312,7 +317,8 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
     return;
   }
   {
-    ln.run("accum_moments", k_accum_moments_fused, dim3(want + 1), blk, a);
+    if (stream_acc(a) && !a.inplace) ln.run("accum_moments", k_accum_moments_fused<true>, dim3(want + 1), blk, a);
+    else ln.run("accum_moments", k_accum_moments_fused<false>, dim3(want + 1), blk, a);
     ln.run("gk_count", k_gk_count_fused<kGroupTiles>, dim3(tiles), blk, a);
     if (a.norms) {
       if (stream_acc(a)) ln.run("gk_compact", k_gk_compact_fused<true, kGroupTiles, kMaxGroups, true>, dim3(tiles), blk, a);
