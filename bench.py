@@ -4,7 +4,8 @@ gradient vector (d = 25,557,032, rho = 0.001) on one MI355X.
 One step = one pass of the whole hot path on a fresh synthetic gradient already resident in
 HBM: accumulate, select (Algorithm 1), compact, residual, with the residual carried from step
 to step as in Eq. (2).  `value` is algorithmic GB/s of the Gaussian_k path (24 B per element +
-8 B per survivor); the exact Top_k path, timed the same way, is reported beside it, and under
+8 B per survivor); the exact Top_k path, timed the same way, is reported beside it (16 B per
+element when its short lists serve, which the result records say; 24 otherwise), and under
 `also`: the same two selectors on the workloads that do not fit the last-level cache (LSTM-sized,
 66 M elements) or sit below the headline (VGG-16-sized), in place, layer-wise, the sampling
 comparator DGC_k, and the aggregation of 16 workers' lists (sparsify_scatter_add).

@@ -10,6 +10,10 @@
 // every key of the tile if it must.  (With acc == residual there is no such room; that case
 // keeps the unfiltered passes of topk_flat.h.)
 //
+// From 6 M elements the accumulate pass also builds short lists (topk_list.h); when they hold at
+// least k entries, which the workgroups of k_topk_filter find out, the kernels of this file take
+// their list bodies instead of the ones described here.  Same launches, same results.
+//
 // Every survivor's output slot is fixed by counts: per tile, the keys above the k-th key T and
 // the keys equal to it are counted from the candidates, the compaction kernel turns group and
 // tile totals into its first slot, and ties are kept lowest index first.  The pairs come out in

@@ -11,7 +11,9 @@
 // tile's number of survivors and of keys equal to the k-th key without another look at acc, so
 // every output slot is fixed by counts and the pairs come out in ascending index order.
 //
-// Used when the vector has at most kFusedMaxTiles tiles (always, unless tile_chunks is forced).
+// From 6 M elements the accumulate pass also builds short lists (topk_list.h); when they hold at
+// least k entries, which the workgroups of the first k_topk_hist_fused find out, the kernels of
+// this file take their list bodies instead of the ones described here.
 #pragma once
 #include "common.h"
 #include "gaussiank_flat.h"
