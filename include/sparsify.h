@@ -100,7 +100,7 @@ typedef struct {
 
 /* Bytes of `workspace` for a vector of d_total elements in num_segments segments (1 for the
  * flat calls).  Returns 0 for invalid arguments.
- *   sparsify_workspace_bytes      the size to allocate.  For flat vectors of 6 M to 123 M elements
+ *   sparsify_workspace_bytes      the size to allocate.  For flat vectors of 6 M elements and more
  *                                 it includes room for Top_k's short lists (0.8 bytes per
  *                                 element): the accumulate pass then also writes the residual and
  *                                 lists the entries above a key guessed from a sample of acc,

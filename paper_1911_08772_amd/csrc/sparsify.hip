@@ -106,15 +106,14 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
 // replicas of each segment's global histogram: spreads same-address atomics of the flat call
 uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
 
-// Short-list Top_k (topk_list.h): flat vectors long enough for the passes saved to matter, short
-// enough for the resident accumulate kernel.  The list buffer holds kListShare of the vector's
-// length in entries (the lists are expected to take max(4 k, 0.4 % of d)), split evenly among the
-// accumulate kernel's waves.
+// Short-list Top_k (topk_list.h): flat vectors long enough for the passes saved to matter.  The
+// list buffer holds kListShare of the vector's length in entries (the lists are expected to take
+// max(4 k, 0.4 % of d)), split evenly among the accumulate kernel's waves.
 constexpr int64_t kListFrom = 6'000'000;
 constexpr double kListShare = 0.10;
 constexpr uint32_t kListMaxWorkers = kWaves * kMaxMomentParts;
 bool list_sized(int64_t d_total, int32_t L) {
-  return L == 1 && d_total >= kListFrom && (d_total + kChunk - 1) / kChunk <= (int64_t)kChunkGridFrom;
+  return L == 1 && d_total >= kListFrom;
 }
 size_t list_entries(int64_t d_total) { return (size_t)(kListShare * (double)d_total) + 64 * (size_t)kListMaxWorkers; }
 
