@@ -101,9 +101,8 @@ struct Args {
   // Top_k, short-list form (topk_list.h); `list` is null when the call does not use it
   uint2* list;            // (index, bits of acc): every wave appends to its own stretch
   uint2* run_table;       // [chunks * 16]: (first entry, entries) of each 256-element run
-  uint32_t* worker_info;  // [list_workers]: entries the wave listed, or kListOverflow
-  uint32_t list_workers;  // waves of the accumulate kernel
-  uint32_t list_cap;      // entries per wave
+  uint32_t* list_stats;   // [2][kListStatCopies]: entries listed (replicated sums), stretches that ran out
+  uint32_t list_cap;      // entries per wave of the accumulate kernel
   uint32_t list_last;     // index of the buffer's last entry
 };
 

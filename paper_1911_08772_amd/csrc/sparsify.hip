@@ -111,16 +111,15 @@ uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 
 // max(4 k, 0.4 % of d)), split evenly among the accumulate kernel's waves.
 constexpr int64_t kListFrom = 6'000'000;
 constexpr double kListShare = 0.10;
-constexpr uint32_t kListMaxWorkers = kWaves * kMaxMomentParts;
 bool list_sized(int64_t d_total, int32_t L) {
   return L == 1 && d_total >= kListFrom;
 }
-size_t list_entries(int64_t d_total) { return (size_t)(kListShare * (double)d_total) + 64 * (size_t)kListMaxWorkers; }
+size_t list_entries(int64_t d_total) { return (size_t)(kListShare * (double)d_total) + 64 * (size_t)kWaves * kMaxMomentParts; }
 
 struct Carve {
   size_t ctrl, tile_start, partial, folded, tile_counts, tile_base, tie_base, group_counts, seg_groups,
       norm_partial, hist, tile_hist, total;
-  size_t list, run_table, worker_info;  // with lists only
+  size_t list, run_table, list_stats;  // with lists only
   uint32_t max_groups;
 };
 Carve carve(int64_t d_total, int32_t L, bool lists = false) {
@@ -145,10 +144,10 @@ Carve carve(int64_t d_total, int32_t L, bool lists = false) {
   // per-tile histograms of the last digit: flat Top_k in place, at most kFusedMaxTiles tiles
   const size_t hist_tiles = mt < (size_t)kFusedMaxTiles ? mt : (size_t)kFusedMaxTiles;
   c.tile_hist = off;   off = align_up(off + sizeof(uint32_t) * kLastDigitBins * hist_tiles);
-  c.list = c.run_table = c.worker_info = 0;
+  c.list = c.run_table = c.list_stats = 0;
   if (lists) {  // appended, so that the layout above does not depend on them
     const size_t chunks = (size_t)((d_total + kChunk - 1) / kChunk);
-    c.worker_info = off; off = align_up(off + sizeof(uint32_t) * kListMaxWorkers);
+    c.list_stats = off;  off = align_up(off + sizeof(uint32_t) * 2 * kListStatCopies);
     c.run_table = off;   off = align_up(off + sizeof(uint2) * chunks * kRunsPerChunk);
     c.list = off;        off = align_up(off + sizeof(uint2) * list_entries(d_total));
   }
@@ -239,7 +238,7 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   if (lists) {
     a.list = reinterpret_cast<uint2*>(w + cv.list);
     a.run_table = reinterpret_cast<uint2*>(w + cv.run_table);
-    a.worker_info = reinterpret_cast<uint32_t*>(w + cv.worker_info);
+    a.list_stats = reinterpret_cast<uint32_t*>(w + cv.list_stats);
   }
   a.tile_chunks = tile_chunks_of(d_total, false);
   if (opts && opts->tile_chunks != 0) {
@@ -342,8 +341,9 @@ void launch_topk_flat(Launcher& ln, const Args& a, uint32_t tiles) {
   const uint32_t resident = cus < nchunks ? cus : nchunks;
   Args al = a;  // short-list form (topk_list.h): the first two launches differ, the rest is shared
   if (a.list) {
-    al.list_workers = resident * kWaves;
-    al.list_cap = (uint32_t)(list_entries(a.d_total) / al.list_workers);
+    // (the resident grid at every length: one chunk per workgroup in dispatch order, which the
+    // accumulate kernels without lists use beyond 123 M elements, measured 6 % slower here)
+    al.list_cap = (uint32_t)(list_entries(a.d_total) / ((size_t)resident * kWaves));
     al.list_last = (uint32_t)(list_entries(a.d_total) - 1);
     ln.run("topk_init", k_topk_init_list, dim3(32), blk, al, (uint32_t)kTopkHistWords);
     ln.run("topk_accum_hist", k_topk_accum_list, dim3(resident), blk, al);

@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_filter(const Args a) {
   __shared__ uint32_t h[kWaves][256];
   __shared__ uint32_t lds_sel[kWaves + 3];
   __shared__ uint32_t lds_above[kWaves];
-  __shared__ uint32_t lds_lists[2 * kWaves];
+  __shared__ uint32_t lds_lists[2];
   __shared__ uint32_t lds_cursor;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist_fused(const Args a, int pa
   __shared__ uint32_t h[kWaves][256];
   __shared__ uint32_t lds_sel[kWaves + 3];
   __shared__ uint32_t lds_sure[kWaves];
-  __shared__ uint32_t lds_lists[2 * kWaves];
+  __shared__ uint32_t lds_lists[2];
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   // odd passes walk the tiles backwards (see k_topk_hist)

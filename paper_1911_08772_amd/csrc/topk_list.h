@@ -29,7 +29,7 @@ namespace sp {
 
 constexpr int kRun = 256;                         // elements per run: 64 lanes x 4
 constexpr int kRunsPerChunk = kChunk / kRun;      // 16
-constexpr uint32_t kListOverflow = 0xFFFFFFFFu;   // worker_info: the wave's stretch ran out
+constexpr int kListStatCopies = 32;               // replicas of the lists' length and overflow words
 constexpr int kListSample = 16 * kBlock;          // entries of acc the init kernel looks at
 constexpr int kListAim = 4;                       // the lists should hold about this many times k
 
@@ -81,6 +81,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_list(const Args a, uint32_
   if (blockIdx.x != 0) return;
   for (uint32_t i = threadIdx.x; i < (uint32_t)(kBigMaxGroups * kNumThres); i += kBlock)
     a.group_counts[i] = 0;
+  if (threadIdx.x < 2 * kListStatCopies) a.list_stats[threadIdx.x] = 0;
   const uint32_t tau = sample_listing_key(a, lds_h, lds_sel);
   if (threadIdx.x == 0) {
     SegCtrl& c = a.ctrl[0];
@@ -178,11 +179,40 @@ __device__ inline void accum_hist_list_finish(const Args& a, int64_t tbase, AccI
   list_chunk<true>(a, tbase, in.g, 0xFFFFu, tau, lc);
 }
 
+// End of an accumulate kernel with lists: the workgroup's histogram into one replica of the
+// global one, the entries its waves listed (and whether a stretch ran out) into one replica of
+// the lists' statistics.  `lds_stat` holds 2 * kWaves words.
+__device__ inline void finish_accum_list(const Args& a, uint32_t (*h)[256], const ListCursor& lc,
+                                         uint32_t worker, uint32_t* lds_stat) {
+  if (lane_id() == 0) {
+    lds_stat[2 * wave_id()] = lc.cur - worker * a.list_cap;
+    lds_stat[2 * wave_id() + 1] = lc.over ? 1u : 0u;
+  }
+  __syncthreads();
+  const int bin = threadIdx.x;
+  uint32_t v = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) v += h[w][bin];
+  if (v) atomicAdd(&pass_hist(a, 0)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+  if (threadIdx.x == 0) {
+    uint32_t n = 0, over = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      n += lds_stat[2 * w];
+      over |= lds_stat[2 * w + 1];
+    }
+    const uint32_t copy = blockIdx.x % kListStatCopies;
+    if (n) atomicAdd(&a.list_stats[copy], n);
+    if (over) atomicOr(&a.list_stats[kListStatCopies + copy], 1u);
+  }
+}
+
 // The resident accumulate kernel of topk_filter.h plus the residual write and the lists, with
 // the next chunk's loads in flight while this one is worked on (two register sets in turn, no
 // load behind a branch inside the loop: see k_accum_moments_fused).
 __global__ __launch_bounds__(kBlock) void k_topk_accum_list(const Args a) {
   __shared__ uint32_t h[kWaves][256];
+  __shared__ uint32_t lds_stat[2 * kWaves];
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   __syncthreads();
@@ -229,50 +259,26 @@ __global__ __launch_bounds__(kBlock) void k_topk_accum_list(const Args a) {
     t.full = false;
     accum_hist_list_chunk<false>(a, t, hw, tau, lc);
   }
-  if (lane_id() == 0) a.worker_info[worker] = lc.over ? kListOverflow : lc.cur - worker * a.list_cap;
-  __syncthreads();
-  const int bin = threadIdx.x;
-  uint32_t v = 0;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) v += h[w][bin];
-  if (v) atomicAdd(&pass_hist(a, 0)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+  finish_accum_list(a, h, lc, worker, lds_stat);
 }
 
 // ---- reading the lists -----------------------------------------------------------------------------
 // Whether the lists can serve the call: no stretch ran out and they hold at least k entries.
 // Computed the same way by every workgroup of the kernel that follows the accumulate kernel
-// (`lds` holds 2 * kWaves words; one barrier); the first tile's workgroup publishes it.
+// (`lds` holds 2 words; one barrier); the first tile's workgroup publishes it.
 __device__ inline bool lists_usable(const Args& a, uint32_t* lds) {
-  const uint32_t nworkers = a.list_workers;
-  uint32_t over = 0, total = 0;
-  for (uint32_t i0 = 0; i0 < nworkers; i0 += 4 * kBlock) {
-    uint32_t w[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {  // all loads first, none behind a branch
-      const uint32_t i = i0 + u * kBlock + threadIdx.x;
-      w[u] = a.worker_info[i < nworkers ? i : nworkers - 1u];
+  if (wave_id() == 0) {
+    static_assert(2 * kListStatCopies == 64, "one lane per word");
+    const uint32_t w = a.list_stats[lane_id()];
+    const uint32_t total = wave_sum(lane_id() < kListStatCopies ? w : 0u);
+    const uint64_t over = __ballot(lane_id() >= kListStatCopies && w != 0);
+    if (lane_id() == 0) {
+      lds[0] = total;
+      lds[1] = over != 0 ? 1u : 0u;
     }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const bool mine = i0 + u * kBlock + threadIdx.x < nworkers;
-      over |= (mine && w[u] == kListOverflow) ? 1u : 0u;
-      total += (mine && w[u] != kListOverflow) ? w[u] : 0u;
-    }
-  }
-  total = wave_sum(total);
-  const uint64_t any_over = __ballot(over != 0);
-  if (lane_id() == 0) {
-    lds[2 * wave_id()] = total;
-    lds[2 * wave_id() + 1] = any_over != 0 ? 1u : 0u;
   }
   __syncthreads();
-  uint32_t t = 0, o = 0;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) {
-    t += lds[2 * w];
-    o |= lds[2 * w + 1];
-  }
-  return o == 0 && (int64_t)t >= a.flat_k;
+  return lds[1] == 0 && (int64_t)lds[0] >= a.flat_k;
 }
 
 // the runs of a tile (every chunk has kRunsPerChunk records, empty ones beyond the vector's end)
