@@ -122,3 +122,45 @@ def test_the_lists_can_be_declined():
     gpu.set_residual(eps)
     check_flat("topk", gpu, g, eps, k, what="small workspace")
     assert way(gpu) == 0
+
+
+def test_a_call_with_lists_can_be_captured_in_a_hip_graph():
+    """The way a call takes is decided on the device, so a captured call replays with or without
+    the lists as each replay's data asks: typical gradients take them, an all-zero one does not."""
+    from gpu_harness import same_bits
+    from oracle import oracle as O
+    d, k = 6_100_000, 6100
+    b = S.Buffers.allocate(d, k)
+    grad = torch.zeros(d, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # warm-up outside capture (first-call queries of the runtime)
+        S.sparsify_topk(d, k, grad, b.residual, b.acc, b.out_idx, b.out_val, k, b.result, b.workspace,
+                        b.workspace_nbytes)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        S.sparsify_topk(d, k, grad, b.residual, b.acc, b.out_idx, b.out_val, k, b.result, b.workspace,
+                        b.workspace_nbytes)
+    b.residual.zero_()
+    eps = np.zeros(d, np.float32)
+    for step in range(5):
+        g = np.zeros(d, np.float32) if step == 2 else synth.normal(d, 77, step, 0.01)
+        if step == 2:
+            eps = np.zeros(d, np.float32)   # with a zero residual acc is all zero: no key above tau
+            b.residual.zero_()
+        grad.copy_(torch.from_numpy(g))
+        b.out_idx.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        acc_o = O.accumulate(g, eps)
+        idx_o, val_o, eps, ro = O.topk(acc_o, k)
+        res = S.decode_results(b.result)[0]
+        assert int(res["nnz"]) == k and int(res["topk_key"]) == ro.topk_key, step
+        assert (int(res["flags"]) & S.F_WAY) == (S.F_SHORTLIST_MISS if step == 2 else S.F_SHORTLIST), step
+        assert np.array_equal(b.out_idx[:k].cpu().numpy().view(np.uint32), idx_o), step
+        assert same_bits(b.out_val[:k].cpu().numpy(), val_o), step
+        assert same_bits(b.residual.cpu().numpy(), eps), step
+        assert same_bits(b.acc.cpu().numpy(), acc_o), step
+        _ = (b.acc * 2).sum().item()   # unrelated eager work between replays
