@@ -11,6 +11,14 @@
 // by the keys >= Ts; three more list passes and the final kernel find the k-th key among those
 // (when they are more than k); the ordered compaction of topk_filter.h writes pairs and residual.
 // Eight histogram buffers: 0-3 for the sample's digits, 4-7 for the kept keys'.
+//
+// From 6 M elements (where the workspace holds the list buffers of topk_list.h) the sample is
+// drawn first, straight from g and eps, so that Ts is known when the accumulate pass runs: that
+// pass then also writes the residual and lists every entry that reaches Ts, and what follows
+// (the digits of the kept keys, the per-tile counts, the compaction) reads those lists, about k
+// entries, instead of acc: twelve launches, one pass over the vector.  Should a list run out of
+// room (Ts = 0, a sample that sat on the small entries) the later kernels take the bodies
+// described above; the launches are the same either way.
 #pragma once
 #include "common.h"
 #include "topk_filter.h"
@@ -76,6 +84,43 @@ __global__ __launch_bounds__(kBlock) void k_dgck_accum_sample(const Args a) {
   if (threadIdx.x == 0) tile_row(a, kRowCand)[tile] = lds_cursor;
 }
 
+// ---- the sample on its own (the form with lists) ------------------------------------------------
+// acc[p] = g[p] + eps[p] at the sampled positions (the accumulate pass makes the same fp32 add),
+// keys to the head of the list buffer, which is idle until that pass, in stratum order.
+constexpr int kSampleBatch = 2;
+__device__ inline uint32_t* sample_keys(const Args& a) { return reinterpret_cast<uint32_t*>(a.list); }
+
+__global__ __launch_bounds__(kBlock) void k_dgck_sample(const Args a) {
+  __shared__ uint32_t h[256];
+  h[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t j0 = (int64_t)blockIdx.x * (kBlock * kSampleBatch) + threadIdx.x;
+  int64_t p[kSampleBatch];
+  float g[kSampleBatch], e[kSampleBatch];
+#pragma unroll
+  for (int u = 0; u < kSampleBatch; ++u) {
+    const int64_t j = j0 + u * kBlock;
+    p[u] = sample_position(a, j < a.sample_m ? j : a.sample_m - 1);  // (no load behind a branch)
+  }
+#pragma unroll
+  for (int u = 0; u < kSampleBatch; ++u) g[u] = a.grad[p[u]];
+#pragma unroll
+  for (int u = 0; u < kSampleBatch; ++u) e[u] = a.resid[p[u]];
+  uint32_t* keys = sample_keys(a);
+#pragma unroll
+  for (int u = 0; u < kSampleBatch; ++u) {
+    const int64_t j = j0 + u * kBlock;
+    if (j < a.sample_m) {
+      const uint32_t key = mag_key(g[u] + e[u]);  // Eq. (2): one fp32 add
+      keys[j] = key;
+      atomicAdd(&h[key >> 23], 1u);
+    }
+  }
+  __syncthreads();
+  const uint32_t v = h[threadIdx.x];
+  if (v) atomicAdd(&pass_hist(a, 0)[(blockIdx.x % kTopkCopies) * 256 + threadIdx.x], v);
+}
+
 // ---- one digit pass over the per-tile lists ----------------------------------------------------
 // stage 1..3: digits 1..3 of the sample (rank sample_k); stage 5..7: digits 1..3 of the kept keys
 // (rank k).  Prologue: the previous digit, from histogram buffer stage-1; the choice goes to
@@ -100,9 +145,31 @@ __global__ __launch_bounds__(kBlock) void k_dgck_lists_hist(const Args a, int st
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
   uint32_t* hw = h[wave_id()];
-  for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key, bool valid) {
-    wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
-  });
+  if (a.list && !(stage & 4)) {
+    // the sample as one array (k_dgck_sample): every workgroup takes stretches of it
+    const uint32_t* keys = sample_keys(a);
+    const int64_t span = (int64_t)kBlock * kCandBatch;
+    for (int64_t b = (int64_t)blockIdx.x * span; b < a.sample_m; b += (int64_t)gridDim.x * span) {
+      uint32_t key[kCandBatch];
+#pragma unroll
+      for (int u = 0; u < kCandBatch; ++u) {
+        const int64_t i = b + u * kBlock + threadIdx.x;
+        key[u] = keys[i < a.sample_m ? i : a.sample_m - 1];
+      }
+#pragma unroll
+      for (int u = 0; u < kCandBatch; ++u) {
+        const bool valid = b + u * kBlock + threadIdx.x < a.sample_m;
+        wave_hist_add(hw, (key[u] >> shift) & mask, valid && (key[u] >> hi_shift) == dg.prefix);
+      }
+    }
+  } else if (a.list && c.list_mode) {
+    // the kept keys from the accumulate pass's lists; nothing to find when all of them are taken
+    if (c.list_mode == 1) list_digit_pass(a, pass, dg.prefix, hw);
+  } else {
+    for_each_candidate(a, blockIdx.x * kWaves + wave_id(), ntiles, [&](uint32_t key, bool valid) {
+      wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == dg.prefix);
+    });
+  }
   __syncthreads();
   const int bin = threadIdx.x;
   uint32_t v = 0;
@@ -152,6 +219,7 @@ __global__ __launch_bounds__(kBlock) void k_dgck_filter(const Args a) {
   __shared__ uint32_t h[kWaves][256];
   __shared__ uint32_t lds_sel[kWaves + 3];
   __shared__ uint32_t lds_cursor;
+  __shared__ uint32_t lds_lists[2];
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   if (threadIdx.x == 0) lds_cursor = 0;
@@ -164,6 +232,23 @@ __global__ __launch_bounds__(kBlock) void k_dgck_filter(const Args a) {
   if (tile == 0 && threadIdx.x == 0) {
     c.sel_prefix[3] = Ts;
     c.sel_krem[3] = dg.k_rem;
+  }
+  if (a.list) {
+    // the accumulate pass listed the keys that reach Ts.  If no stretch ran out the lists are
+    // the kept entries: more than k of them, a second selection follows (way 1: the first
+    // digit's histogram from the lists); otherwise all of them are the result (way 2).
+    list_totals(a, lds_lists);
+    const uint32_t way = lds_lists[1] != 0 ? 0u : (int64_t)lds_lists[0] > a.flat_k ? 1u : 2u;
+    if (tile == 0 && threadIdx.x == 0) c.list_mode = way;
+    if (way == 1) {
+      list_digit_pass(a, 0, 0u, h[wave_id()]);
+      __syncthreads();
+      uint32_t v = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) v += h[w][threadIdx.x];
+      if (v) atomicAdd(&pass_hist(a, 4)[(blockIdx.x % kTopkCopies) * 256 + threadIdx.x], v);
+    }
+    if (way != 0) return;
   }
   uint32_t* list = tile_candidates(a, tile);
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
@@ -192,9 +277,14 @@ __global__ __launch_bounds__(kBlock) void k_dgck_filter(const Args a) {
 __global__ __launch_bounds__(kBlock) void k_dgck_final(const Args a) {
   __shared__ uint32_t lds_sel[kWaves + 3];
   __shared__ uint32_t lds_n;
+  __shared__ uint32_t lds_lists[2];
   SegCtrl& c = a.ctrl[0];
   const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
-  if (wave_id() == 0) {
+  const bool listed = a.list && c.list_mode != 0;
+  if (listed) {
+    list_totals(a, lds_lists);  // barrier
+    if (threadIdx.x == 0) lds_n = lds_lists[0];
+  } else if (wave_id() == 0) {
     const uint32_t ngroups = (ntiles + kGroupTiles - 1) / kGroupTiles;
     uint32_t g = (uint32_t)lane_id() < ngroups ? a.group_counts[lane_id() * kNumThres + kColCand] : 0u;
     g = wave_sum(g);
@@ -221,6 +311,11 @@ __global__ __launch_bounds__(kBlock) void k_dgck_final(const Args a) {
     r.thres = (double)__uint_as_float(Ts);
     r.topk_key = T;
     r.topk_ties_taken = second ? dg.k_rem : 0u;
+    if (a.list) r.flags = listed ? SPARSIFY_F_SHORTLIST : SPARSIFY_F_SHORTLIST_MISS;  // which way, no result
+  }
+  if (listed) {
+    list_tile_counts<kGroupTiles>(a, T, rank_ties);
+    return;
   }
   const uint32_t tile = blockIdx.x * kWaves + wave_id();
   uint32_t gt = 0, eq = 0;

@@ -346,7 +346,7 @@ void launch_topk_flat(Launcher& ln, const Args& a, uint32_t tiles) {
     al.list_cap = (uint32_t)(list_entries(a.d_total) / ((size_t)resident * kWaves));
     al.list_last = (uint32_t)(list_entries(a.d_total) - 1);
     ln.run("topk_init", k_topk_init_list, dim3(32), blk, al, (uint32_t)kTopkHistWords);
-    ln.run("topk_accum_hist", k_topk_accum_list, dim3(resident), blk, al);
+    ln.run("topk_accum_hist", k_topk_accum_list<false>, dim3(resident), blk, al);
   }
   launch_topk_flat_rest(ln, al, tiles, nchunks, resident);
 }
@@ -424,14 +424,31 @@ void launch_topk_seg(Launcher& ln, const Args& a, uint32_t tiles) {
   if (a.norms) ln.run("norms", k_norms_finalize<true>, dim3(a.L), dim3(kFinBlock), a);
 }
 
-// DGC_k: eleven launches (dgck.h).
-void launch_dgck(Launcher& ln, const Args& a, uint32_t tiles) {
+// DGC_k: eleven launches; twelve with the lists, where the sample comes first and the accumulate
+// pass already knows the sample's threshold (dgck.h).
+void launch_dgck(Launcher& ln, const Args& a0, uint32_t tiles) {
   const dim3 blk(kBlock), pg(tiles), cg((tiles + kWaves - 1) / kWaves);
+  Args a = a0;
   ln.run("dgck_init", k_topk_init_fused, dim3(64), blk, a, (uint32_t)kDgcHistWords);
-  ln.run("dgck_accum_sample", k_dgck_accum_sample, pg, blk, a);
+  if (a.list) {
+    const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+    static const uint32_t cus = compute_units();
+    const uint32_t resident = cus < nchunks ? cus : nchunks;
+    a.list_cap = (uint32_t)(list_entries(a.d_total) / ((size_t)resident * kWaves));
+    a.list_last = (uint32_t)(list_entries(a.d_total) - 1);
+    const int64_t per_wg = (int64_t)kBlock * kSampleBatch;
+    ln.run("dgck_sample", k_dgck_sample, dim3((uint32_t)((a.sample_m + per_wg - 1) / per_wg)), blk, a);
+  } else {
+    ln.run("dgck_accum_sample", k_dgck_accum_sample, pg, blk, a);
+  }
   ln.run("dgck_sample1", k_dgck_lists_hist, cg, blk, a, 1);
   ln.run("dgck_sample2", k_dgck_lists_hist, cg, blk, a, 2);
   ln.run("dgck_sample3", k_dgck_lists_hist, cg, blk, a, 3);
+  if (a.list) {
+    const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
+    static const uint32_t cus = compute_units();
+    ln.run("dgck_accum_list", k_topk_accum_list<true>, dim3(cus < nchunks ? cus : nchunks), blk, a);
+  }
   ln.run("dgck_filter", k_dgck_filter, pg, blk, a);
   ln.run("dgck_kept1", k_dgck_lists_hist, cg, blk, a, 5);
   ln.run("dgck_kept2", k_dgck_lists_hist, cg, blk, a, 6);
@@ -477,9 +494,9 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
-  // the short-list form: Top_k without the norms, k small enough for the lists' share of the
-  // workspace, where the workspace has room at all (prepare)
-  if (selector != kSelTopk || a.norms || (opts && opts->short_list < 0) ||
+  // the short-list forms: Top_k and DGC_k without the norms, k small enough for the lists' share
+  // of the workspace, where the workspace has room at all (prepare)
+  if (selector == kSelGaussian || a.norms || (opts && opts->short_list < 0) ||
       2.0 * kListAim * (double)k > kListShare * (double)d)
     a.list = nullptr;
   if (!(opts && opts->tile_chunks != 0))
@@ -503,6 +520,8 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
     a.sample_m = (d + S - 1) / S;
     a.sample_k = (k * a.sample_m + d - 1) / d;
     a.sample_seed = opts ? opts->sample_seed : 0;
+    // (the sample's keys wait in the list buffer until the accumulate pass overwrites it)
+    if ((size_t)a.sample_m > list_entries(d)) a.list = nullptr;
   }
   Launcher ln{static_cast<hipStream_t>(stream),
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};

@@ -147,7 +147,7 @@ __device__ inline void list_chunk(const Args& a, int64_t tbase, const float (&v)
   }
 }
 
-template <bool FULL>
+template <bool FULL, bool HIST>
 __device__ inline void accum_hist_list_chunk(const Args& a, const Tile& t, uint32_t* h, uint32_t tau,
                                              ListCursor& lc) {
   float g[kPerThread], e[kPerThread];
@@ -157,13 +157,16 @@ __device__ inline void accum_hist_list_chunk(const Args& a, const Tile& t, uint3
   for (int i = 0; i < kPerThread; ++i) g[i] = g[i] + e[i];  // Eq. (2): one fp32 add
   if (!a.inplace) store_tile<FULL>(a.acc, t, g, valid);
   store_tile<FULL>(a.resid, t, g, valid);  // the residual if nothing of this chunk is selected
+  if (HIST) {
 #pragma unroll
-  for (int i = 0; i < kPerThread; ++i)
-    if (FULL || ((valid >> i) & 1u)) atomicAdd(&h[mag_key(g[i]) >> 23], 1u);
+    for (int i = 0; i < kPerThread; ++i)
+      if (FULL || ((valid >> i) & 1u)) atomicAdd(&h[mag_key(g[i]) >> 23], 1u);
+  }
   list_chunk<FULL>(a, t.tbase, g, valid, tau, lc);
 }
 
 // A full chunk whose loads were issued earlier (accum_issue of gaussiank.h).
+template <bool HIST>
 __device__ inline void accum_hist_list_finish(const Args& a, int64_t tbase, AccIn& in, uint32_t* h,
                                               uint32_t tau, ListCursor& lc) {
   const Tile t = full_chunk_at(tbase);
@@ -174,14 +177,17 @@ __device__ inline void accum_hist_list_finish(const Args& a, int64_t tbase, AccI
   // call reads first)
   if (!a.inplace) store_tile<true, true>(a.acc, t, in.g, 0xFFFFu);
   store_tile<true>(a.resid, t, in.g, 0xFFFFu);
+  if (HIST) {
 #pragma unroll
-  for (int i = 0; i < kPerThread; ++i) atomicAdd(&h[mag_key(in.g[i]) >> 23], 1u);
+    for (int i = 0; i < kPerThread; ++i) atomicAdd(&h[mag_key(in.g[i]) >> 23], 1u);
+  }
   list_chunk<true>(a, tbase, in.g, 0xFFFFu, tau, lc);
 }
 
 // End of an accumulate kernel with lists: the workgroup's histogram into one replica of the
 // global one, the entries its waves listed (and whether a stretch ran out) into one replica of
 // the lists' statistics.  `lds_stat` holds 2 * kWaves words.
+template <bool HIST>
 __device__ inline void finish_accum_list(const Args& a, uint32_t (*h)[256], const ListCursor& lc,
                                          uint32_t worker, uint32_t* lds_stat) {
   if (lane_id() == 0) {
@@ -189,11 +195,13 @@ __device__ inline void finish_accum_list(const Args& a, uint32_t (*h)[256], cons
     lds_stat[2 * wave_id() + 1] = lc.over ? 1u : 0u;
   }
   __syncthreads();
-  const int bin = threadIdx.x;
-  uint32_t v = 0;
+  if (HIST) {
+    const int bin = threadIdx.x;
+    uint32_t v = 0;
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) v += h[w][bin];
-  if (v) atomicAdd(&pass_hist(a, 0)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+    for (int w = 0; w < kWaves; ++w) v += h[w][bin];
+    if (v) atomicAdd(&pass_hist(a, 0)[(blockIdx.x % kTopkCopies) * 256 + bin], v);
+  }
   if (threadIdx.x == 0) {
     uint32_t n = 0, over = 0;
 #pragma unroll
@@ -210,24 +218,45 @@ __device__ inline void finish_accum_list(const Args& a, uint32_t (*h)[256], cons
 // The resident accumulate kernel of topk_filter.h plus the residual write and the lists, with
 // the next chunk's loads in flight while this one is worked on (two register sets in turn, no
 // load behind a branch inside the loop: see k_accum_moments_fused).
+//
+// DGC: the same pass for DGC_k (dgck.h).  The listing key is then the sample's threshold Ts
+// itself, chosen in the prologue from the last digit pass over the sample: every entry whose key
+// reaches Ts is listed (key >= Ts is key > Ts - 1; with Ts = 0 everything is kept, which no list
+// holds: the stretches are reported as run out at once).  No histogram is taken.
+template <bool DGC>
 __global__ __launch_bounds__(kBlock) void k_topk_accum_list(const Args a) {
-  __shared__ uint32_t h[kWaves][256];
+  __shared__ uint32_t h[DGC ? 1 : kWaves][256];
   __shared__ uint32_t lds_stat[2 * kWaves];
+  __shared__ uint32_t lds_sel[kWaves + 3];
+  uint32_t tau;
+  bool none = false;
+  if (DGC) {
+    SegCtrl& c = a.ctrl[0];
+    const Digit dg = choose_digit(pass_hist(a, 3), 3, c.sel_prefix[2], c.sel_krem[2], lds_sel);  // barriers
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      c.sel_prefix[3] = dg.prefix;  // Ts: a whole 31-bit key
+      c.sel_krem[3] = dg.k_rem;
+    }
+    none = dg.prefix == 0;
+    tau = none ? 0u : dg.prefix - 1u;
+  } else {
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
-  __syncthreads();
-  const uint32_t tau = a.ctrl[0].tau_key;
+    for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
+    __syncthreads();
+    tau = a.ctrl[0].tau_key;
+  }
   const uint32_t worker = blockIdx.x * kWaves + wave_id();
   ListCursor lc;
   lc.cur = worker * a.list_cap;
   lc.end = lc.cur + a.list_cap;
-  lc.over = false;
+  lc.over = none;
   const uint32_t nchunks = (uint32_t)((a.d_total + kChunk - 1) / kChunk);
   const uint32_t nfull = (uint32_t)(a.d_total / kChunk);
   const uint32_t step = gridDim.x;
   const uint32_t n = blockIdx.x < nfull ? (nfull - blockIdx.x + step - 1) / step : 0u;  // my full chunks
   auto at = [&](uint32_t k) { return (int64_t)(blockIdx.x + k * step) * kChunk; };
-  uint32_t* hw = h[wave_id()];
+  uint32_t* hw = h[DGC ? 0 : wave_id()];
+  constexpr bool HIST = !DGC;
   if (n > 0) {
     AccIn x, y;
     uint32_t k = 0;
@@ -235,19 +264,19 @@ __global__ __launch_bounds__(kBlock) void k_topk_accum_list(const Args a) {
     while (k + 2 < n) {
       accum_issue(a, at(k + 1), y);
       __builtin_amdgcn_sched_barrier(0);
-      accum_hist_list_finish(a, at(k), x, hw, tau, lc);
+      accum_hist_list_finish<HIST>(a, at(k), x, hw, tau, lc);
       accum_issue(a, at(k + 2), x);
       __builtin_amdgcn_sched_barrier(0);
-      accum_hist_list_finish(a, at(k + 1), y, hw, tau, lc);
+      accum_hist_list_finish<HIST>(a, at(k + 1), y, hw, tau, lc);
       k += 2;
     }
     if (n - k == 2) {
       accum_issue(a, at(k + 1), y);
       __builtin_amdgcn_sched_barrier(0);
-      accum_hist_list_finish(a, at(k), x, hw, tau, lc);
-      accum_hist_list_finish(a, at(k + 1), y, hw, tau, lc);
+      accum_hist_list_finish<HIST>(a, at(k), x, hw, tau, lc);
+      accum_hist_list_finish<HIST>(a, at(k + 1), y, hw, tau, lc);
     } else {
-      accum_hist_list_finish(a, at(k), x, hw, tau, lc);
+      accum_hist_list_finish<HIST>(a, at(k), x, hw, tau, lc);
     }
   }
   if (nfull < nchunks && nfull % step == blockIdx.x) {  // the ragged last chunk
@@ -257,16 +286,22 @@ __global__ __launch_bounds__(kBlock) void k_topk_accum_list(const Args a) {
     t.lo = t.tbase;
     t.hi = a.d_total;
     t.full = false;
-    accum_hist_list_chunk<false>(a, t, hw, tau, lc);
+    accum_hist_list_chunk<false, HIST>(a, t, hw, tau, lc);
   }
-  finish_accum_list(a, h, lc, worker, lds_stat);
+  finish_accum_list<HIST>(a, h, lc, worker, lds_stat);
 }
 
 // ---- reading the lists -----------------------------------------------------------------------------
 // Whether the lists can serve the call: no stretch ran out and they hold at least k entries.
 // Computed the same way by every workgroup of the kernel that follows the accumulate kernel
 // (`lds` holds 2 words; one barrier); the first tile's workgroup publishes it.
+__device__ inline void list_totals(const Args& a, uint32_t* lds);
 __device__ inline bool lists_usable(const Args& a, uint32_t* lds) {
+  list_totals(a, lds);
+  return lds[1] == 0 && (int64_t)lds[0] >= a.flat_k;
+}
+// lds[0] = entries listed, lds[1] = whether a stretch ran out (then lds[0] is not all of them)
+__device__ inline void list_totals(const Args& a, uint32_t* lds) {
   if (wave_id() == 0) {
     static_assert(2 * kListStatCopies == 64, "one lane per word");
     const uint32_t w = a.list_stats[lane_id()];
@@ -278,7 +313,6 @@ __device__ inline bool lists_usable(const Args& a, uint32_t* lds) {
     }
   }
   __syncthreads();
-  return lds[1] == 0 && (int64_t)lds[0] >= a.flat_k;
 }
 
 // the runs of a tile (every chunk has kRunsPerChunk records, empty ones beyond the vector's end)
@@ -331,10 +365,11 @@ __device__ inline void for_each_list_entry(const Args& a, uint32_t tile, F fn) {
 }
 
 // A digit pass over the lists: the histogram of digit `pass` among the listed keys whose higher
-// digits equal `prefix`, one wave per tile (any grid), into the wave's LDS histogram `hw`.
+// digits equal `prefix` (pass 0: among all of them), one wave per tile (any grid), into the
+// wave's LDS histogram `hw`.
 __device__ inline void list_digit_pass(const Args& a, int pass, uint32_t prefix, uint32_t* hw) {
   const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
-  const int hi_shift = digit_shift(pass - 1);
+  const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);  // keys have 31 bits: prefix 0 matches all
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
   for (uint32_t tile = blockIdx.x * kWaves + wave_id(); tile < ntiles; tile += gridDim.x * kWaves) {

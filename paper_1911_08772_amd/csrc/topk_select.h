@@ -39,6 +39,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_fused(const Args a, uint32
   if (blockIdx.x == 0) {
     for (uint32_t i = threadIdx.x; i < (uint32_t)(kBigMaxGroups * kNumThres); i += kBlock)
       a.group_counts[i] = 0;
+    if (a.list && threadIdx.x < 64) a.list_stats[threadIdx.x] = 0;  // the lists' length and overflow words
     if (threadIdx.x == 0) {
       SegCtrl& c = a.ctrl[0];
       c.prefix = 0;

@@ -164,8 +164,8 @@ def sparsify_gaussiank_static(d, k, grad, residual, acc, out_idx, out_val, cap, 
 
 def sparsify_dgck(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                   workspace_nbytes, sample_stride=0, sample_seed=0, trace=None, stream=None,
-                  check=True, tile_chunks=0, error_norms=False) -> int:
-    o = _opts(2.0, 1, trace, tile_chunks, error_norms, sample_stride, sample_seed)
+                  check=True, tile_chunks=0, error_norms=False, short_list=0) -> int:
+    o = _opts(2.0, 1, trace, tile_chunks, error_norms, sample_stride, sample_seed, short_list)
     rc = lib.sparsify_dgck(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                            _ptr(out_val), cap, _ptr(result), _ptr(workspace), workspace_nbytes,
                            C.byref(o), _stream(stream))

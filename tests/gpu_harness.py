@@ -106,8 +106,9 @@ def assert_topk_result(res, ro: O.Result, what=""):
 
 
 def assert_dgck_result(res, ro: O.Result, what=""):
-    for name in ("nnz", "rounds", "flags", "topk_key", "topk_ties_taken"):
+    for name in ("nnz", "rounds", "topk_key", "topk_ties_taken"):
         assert int(res[name]) == getattr(ro, name), (what, name, res, ro)
+    assert int(res["flags"]) & ~S.F_WAY == ro.flags, (what, res, ro)  # (the way taken is no result)
     assert tuple(int(c) for c in res["count"]) == tuple(ro.count), (what, res, ro)
     g32, o32 = np.float32(res["thres_f32"]), np.float32(ro.thres_f32)
     assert g32.view(np.uint32) == o32.view(np.uint32), (what, g32, o32)
