@@ -110,7 +110,7 @@ class Flat:
             listed += 1 if int(r["flags"]) & S.F_SHORTLIST else 0
         stage = StageMeans({n: sum(v) / len(v) for n, v in per.items()})
         stage.median = {n: statistics.median(v) for n, v in per.items()}
-        stage.listed = listed / K   # share of the steps whose Top_k pairs came from the short lists
+        stage.listed = listed / K   # share of the steps whose pairs came from the short lists (Top_k, DGC_k)
         return stage, nnz, rounds
 
     def spread(self, fn, repeats):
@@ -300,6 +300,7 @@ def main() -> int:
         dg_stage, dg_nnz, dg_rounds = f.traced(S.sparsify_dgck)
         dg = {"ms_per_step": round(dg_ms, 5), "nnz_mean": float(np.mean(dg_nnz)),
               "selections_mean": float(np.mean(dg_rounds)),
+              "steps_from_short_lists": dg_stage.listed,
               "kernel_ms": {n: round(v, 5) for n, v in dg_stage.items()}}
 
     extras = {}
