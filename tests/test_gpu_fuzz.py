@@ -52,6 +52,30 @@ def test_flat_random_cases(selector):
         check_flat(selector, gpu, g, eps, k, what=f"case {case}: d={d} k={k} cap={cap} inplace={inplace} {kw}", **kw)
 
 
+@pytest.mark.parametrize("selector", ["topk", "dgck"])
+def test_flat_random_cases_where_short_lists_are_built(selector):
+    """From 6 M elements Top_k and DGC_k list the large entries in the accumulate pass; whether a
+    call ends up using its lists depends on the data, the results must not."""
+    rng = np.random.default_rng(6_000_000 + len(selector))
+    ways = set()
+    for case in range(14):
+        d = int(rng.integers(6_000_000, 11_000_000))
+        k = int(rng.choice([1, rng.integers(2, 200), d // 1000, rng.integers(d // 500, d // 80)]))
+        g = random_vector(rng, d, int(rng.integers(0, 5)))
+        eps = random_vector(rng, d, int(rng.integers(0, 5))) if rng.random() < 0.6 else np.zeros(d, np.float32)
+        inplace = bool(rng.random() < 0.4) and selector != "dgck"
+        kw = {"tile_chunks": int(rng.choice([0, 0, 2, 5]))}
+        if selector == "dgck":
+            kw["sample_stride"] = int(rng.choice([0, 10, 37, 100, 1000, 5000]))
+            kw["sample_seed"] = int(rng.integers(0, 1 << 62))
+        gpu = FlatGpu(d, cap=k, inplace=inplace)
+        gpu.set_residual(eps)
+        check_flat(selector, gpu, g, eps, k, what=f"case {case}: d={d} k={k} inplace={inplace} {kw}", **kw)
+        ways.add(int(S.decode_results(gpu.b.result)[0]["flags"]) & S.F_WAY)
+        del gpu
+    assert S.F_SHORTLIST in ways and ways <= {S.F_SHORTLIST, S.F_SHORTLIST_MISS}, ways
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_segmented_random_cases(mode):
     rng = np.random.default_rng(77 + mode)
