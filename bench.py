@@ -396,21 +396,36 @@ def main() -> int:
     return 0
 
 
+def kernel_sources_digest() -> str:
+    """Short SHA-256 over the kernel sources (file names and contents, in name order): the
+    committed profile summaries carry the digest of the sources they were measured on."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_1911_08772_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".h", ".hip", ".c")):
+            h.update(name.encode())
+            with open(os.path.join(csrc, name), "rb") as fh:
+                h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload: str, kernel: str):
     """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this
     workload (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel) and where the figure comes
-    from: it is a profile of the committed kernels, not a counter read during this run.  None when
-    there is no summary, or when the library's sources are newer than it."""
+    from: it is a profile of the committed kernels, not a counter read during this run (the
+    summary names the digest of the kernel sources it was measured on; a figure measured on
+    other sources is still returned, and said to be).  None when there is no summary."""
     rel = os.path.join("profiles", f"bench_{workload}_hbm_traffic.txt")
     path = os.path.join(ROOT, rel)
     try:
-        csrc = os.path.join(ROOT, "paper_1911_08772_amd", "csrc")
-        newest = max(os.path.getmtime(os.path.join(csrc, f)) for f in os.listdir(csrc))
-        for line in open(path):
+        lines = open(path).read().splitlines()
+        same = f"kernel sources digest={kernel_sources_digest()}" in lines
+        for line in lines:
             if line.startswith(f"traffic kernel={kernel} "):
                 value = float(line.split("bytes_per_launch=")[1])
-                if os.path.getmtime(path) < newest:
-                    return value, f"{rel} (committed rocprofv3 --pmc summary; older than the kernel sources)"
+                if not same:
+                    return value, f"{rel} (committed rocprofv3 --pmc summary; measured on other kernel sources than these)"
                 return value, f"{rel} (committed rocprofv3 --pmc summary, not measured in this run)"
     except (OSError, ValueError):
         pass
