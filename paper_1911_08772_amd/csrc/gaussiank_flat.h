@@ -10,6 +10,7 @@
 #pragma once
 #include "common.h"
 #include "gaussiank.h"
+#include "gaussiank_list.h"
 #include "tile_io.h"
 
 namespace sp {
@@ -36,6 +37,7 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_fused(const Args a) {
   if (blockIdx.x == a.moment_parts) {
     for (uint32_t i = threadIdx.x; i < (uint32_t)(kMaxGroups * kNumThres); i += kBlock)
       a.group_counts[i] = 0;
+    if (a.list && threadIdx.x < 2 * kListStatCopies) a.list_stats[threadIdx.x] = 0;
     if (threadIdx.x == 0)
       a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
     return;
@@ -98,6 +100,7 @@ __global__ __launch_bounds__(kBlock) void k_accum_moments_chunks(const Args a) {
   if (blockIdx.x == nchunks) {  // the extra workgroup: see k_accum_moments_fused
     for (uint32_t i = threadIdx.x; i < (uint32_t)(kBigMaxGroups * kNumThres); i += kBlock)
       a.group_counts[i] = 0;
+    if (a.list && threadIdx.x < 2 * kListStatCopies) a.list_stats[threadIdx.x] = 0;
     if (threadIdx.x == 0)
       a.ctrl[0].z = norm_isf((double)a.flat_k / (a.tail_div * (double)a.d_total));
     return;
@@ -242,10 +245,27 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
   uint32_t cnt[kNumThres];
 #pragma unroll
   for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
-  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
-    const Tile t = chunk_of(sp_, u);
-    if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
-    else count_chunk<false>(a, t, thr, can_skip, cnt);
+  if (a.list && can_skip) {
+    // with lists (gaussiank_list.h): the entries above thres0, and the residual as if nothing
+    // were selected; each wave has a stretch of the list buffer for this tile
+    const uint32_t worker = tile * kWaves + wave_id();
+    ListCursor lc;
+    lc.cur = worker * a.list_cap;
+    lc.end = lc.cur + a.list_cap;
+    lc.over = false;
+    for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+      const Tile t = chunk_of(sp_, u);
+      if (t.full) count_list_chunk<true>(a, t, thr, cnt, lc);
+      else count_list_chunk<false>(a, t, thr, cnt, lc);
+    }
+    if (lc.over && lane_id() == 0) atomicOr(&a.list_stats[kListStatCopies + tile % kListStatCopies], 1u);
+  } else {
+    if (a.list && tile == 0 && threadIdx.x == 0) atomicOr(&a.list_stats[kListStatCopies], 1u);  // no lists
+    for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+      const Tile t = chunk_of(sp_, u);
+      if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
+      else count_chunk<false>(a, t, thr, can_skip, cnt);
+    }
   }
   if (lane_id() == 0) {
 #pragma unroll
@@ -269,6 +289,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   __shared__ uint32_t lds_t[GT * kNumThres];    // counts of my group's tiles [threshold][tile]
   __shared__ uint32_t lds_tot[kNumThres];
   __shared__ uint32_t lds_base;
+  __shared__ uint32_t lds_lists[2];
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
   const uint32_t tile = blockIdx.x;
@@ -337,10 +358,18 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   __syncthreads();
   const double tf = t64[w.pos];
   const float thr = (float)tf;
+  // With lists (gaussiank_list.h): they hold every survivor when no stretch ran out and the walk
+  // ended at thres0 or above it.
+  bool listed = false;
+  if (a.list) {
+    list_totals(a, lds_lists);  // barrier
+    listed = lds_lists[1] == 0 && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
+  }
   if (tile == 0 && threadIdx.x == 0) {
     uint32_t flags = flags0;
     if (!w.in_band) flags |= SPARSIFY_F_EXHAUSTED;
     if (overflow) flags |= SPARSIFY_F_OVERFLOW;
+    if (a.list) flags |= listed ? SPARSIFY_F_SHORTLIST : SPARSIFY_F_SHORTLIST_MISS;  // which way, no result
     sparsify_result& r = a.result[0];
     r.nnz = overflow ? 0u : tot[w.pos];
     r.rounds = w.rounds;
@@ -357,6 +386,10 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
     r.residual_sqnorm = 0.0;
   }
   const int64_t out0 = (int64_t)lds_base;
+  if (listed) {  // the residual is in place (the count kernel wrote it); one wave writes the tile's pairs
+    if (!overflow && wave_id() == 0) gk_list_compact_tile(a, tile, thr, (uint32_t)out0);
+    return;
+  }
   uint32_t run = 0;
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {

@@ -298,6 +298,10 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   if (want > a.max_tiles) want = a.max_tiles;
   if (want < 1) want = 1;
   a.moment_parts = want;
+  if (a.list) {  // gaussiank_list.h: a stretch of the list buffer per wave of the count kernel
+    a.list_cap = (uint32_t)(list_entries(a.d_total) / ((size_t)tiles * kWaves));
+    a.list_last = (uint32_t)(list_entries(a.d_total) - 1);
+  }
   if (nchunks > kChunkGridFrom) {  // (flat_call has checked that the group tables hold `tiles`)
     // long vector: one chunk per workgroup and a fold of the partials, then short tiles in
     // groups of kBigGroupTiles
@@ -496,8 +500,7 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   a.flat_cap = cap;
   // the short-list forms: Top_k and DGC_k without the norms, k small enough for the lists' share
   // of the workspace, where the workspace has room at all (prepare)
-  if (selector == kSelGaussian || a.norms || (opts && opts->short_list < 0) ||
-      2.0 * kListAim * (double)k > kListShare * (double)d)
+  if (a.norms || (opts && opts->short_list < 0) || 2.0 * kListAim * (double)k > kListShare * (double)d)
     a.list = nullptr;
   if (!(opts && opts->tile_chunks != 0))
     a.tile_chunks = tile_chunks_of(d, selector == kSelGaussian || (selector == kSelTopk && !a.inplace));

@@ -136,8 +136,8 @@ class Trace:
 
 def sparsify_gaussiank(d, k, grad, residual, acc, out_idx, out_val, cap, result, workspace,
                        workspace_nbytes, tail_div=2.0, ddof=1, trace=None, stream=None,
-                       check=True, tile_chunks=0, error_norms=False) -> int:
-    o = _opts(tail_div, ddof, trace, tile_chunks, error_norms)
+                       check=True, tile_chunks=0, error_norms=False, short_list=0) -> int:
+    o = _opts(tail_div, ddof, trace, tile_chunks, error_norms, short_list=short_list)
     rc = lib.sparsify_gaussiank(d, k, _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                                 _ptr(out_val), cap, _ptr(result), _ptr(workspace),
                                 workspace_nbytes, C.byref(o), _stream(stream))

@@ -81,7 +81,7 @@ def assert_pairs_match(got, idx_o, val_o, what=""):
 def assert_gaussiank_result(res, ro: O.Result, what=""):
     assert int(res["rounds"]) == ro.rounds, (what, res, ro)
     assert list(res["count"]) == list(ro.count), (what, res, ro)
-    assert int(res["flags"]) == ro.flags, (what, res, ro)
+    assert int(res["flags"]) & ~S.F_WAY == ro.flags, (what, res, ro)  # (the way taken is no result)
     assert int(res["nnz"]) == ro.nnz, (what, res, ro)
     for name in ("mean", "std", "z", "thres0", "thres"):
         g, o = float(res[name]), getattr(ro, name)
