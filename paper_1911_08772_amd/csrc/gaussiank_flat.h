@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void k_fold_moments(const Args a) {
 // K3: thresholds from the moment partials (every workgroup), then the ten counts of its tile.
 // One pass over the partials around the provisional centre P = mean of partial 0:
 //   A = sum n_i (mean_i - P), B = sum M2_i + n_i (mean_i - P)^2, mean = P + A/N, M2 = B - A^2/N.
-template <int GT>  // tiles per group
+template <int GT, bool STREAM = false>  // tiles per group; non-temporal reads of acc (with lists only)
 __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
   __shared__ double lds_m[2 * kWaves];
   __shared__ uint32_t lds[kWaves * kNumThres];
@@ -255,8 +255,8 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
     lc.over = false;
     for (uint32_t u = 0; u < sp_.nchunks; ++u) {
       const Tile t = chunk_of(sp_, u);
-      if (t.full) count_list_chunk<true>(a, t, thr, cnt, lc);
-      else count_list_chunk<false>(a, t, thr, cnt, lc);
+      if (t.full) count_list_chunk<true, STREAM>(a, t, thr, cnt, lc);
+      else count_list_chunk<false, STREAM>(a, t, thr, cnt, lc);
     }
     if (lc.over && lane_id() == 0) atomicOr(&a.list_stats[kListStatCopies + tile % kListStatCopies], 1u);
   } else {

@@ -78,13 +78,13 @@ __device__ inline void count_list_values(const Args& a, int64_t tbase, const flo
 
 // One chunk of the count kernel with lists: counts, the residual as if nothing were selected
 // (nothing to write when acc is the residual), the list.
-template <bool FULL>
+template <bool FULL, bool STREAM>  // STREAM: acc is read with the non-temporal hint (its last use if the lists serve)
 __device__ inline void count_list_chunk(const Args& a, const Tile& t, const float (&thr)[kNumThres],
                                         uint32_t (&cnt)[kNumThres], ListCursor& lc) {
   float v[kPerThread];
-  const uint32_t valid = load_tile<FULL>(a.acc, t, v);
-  if (!a.inplace) store_tile<FULL>(a.resid, t, v, valid);
+  const uint32_t valid = load_tile<FULL, STREAM>(a.acc, t, v);
   count_list_values<FULL>(a, t.tbase, v, valid, thr, cnt, lc);
+  if (!a.inplace) store_tile<FULL>(a.resid, t, v, valid);
 }
 
 // The pairs of one tile from its lists, in index order, by one wave: `out0` survivors precede
