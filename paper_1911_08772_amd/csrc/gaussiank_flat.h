@@ -283,22 +283,26 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
 
 // K5: every workgroup totals the group counts, walks Alg. 1 steps 5-13, finds the first output
 // slot of its tile (groups before its own + tiles before it inside its group), then compacts.
+// A workgroup takes a.compact_tiles consecutive tiles of one group (one tile without lists;
+// with lists several, so that the tables are read a fraction as often: a wave then writes a
+// tile's pairs from its lists, and if the lists do not serve the workgroup streams its tiles one
+// after the other).
 template <bool NORMS, int GT, int MG, bool STREAM>  // tiles per group, groups at most, non-temporal reads
 __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   __shared__ uint32_t lds_g[MG * kNumThres];    // group totals [group][threshold]
   __shared__ uint32_t lds_t[GT * kNumThres];    // counts of my group's tiles [threshold][tile]
   __shared__ uint32_t lds_tot[kNumThres];
-  __shared__ uint32_t lds_base;
+  __shared__ uint32_t lds_base[2];              // survivors in the groups before mine; before the tile
   __shared__ uint32_t lds_lists[2];
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
-  const uint32_t tile = blockIdx.x;
-  Span sp_;
-  if (!locate_span<false>(a, tile, &sp_)) return;
+  const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  const uint32_t tile0 = blockIdx.x * a.compact_tiles;
+  if (tile0 >= ntiles) return;
+  const uint32_t tile1 = tile0 + a.compact_tiles < ntiles ? tile0 + a.compact_tiles : ntiles;
   SegCtrl& c = a.ctrl[0];
-  const uint32_t ntiles = gridDim.x;
   const uint32_t ngroups = (ntiles + GT - 1) / GT;
-  const uint32_t g = tile / GT, g0 = g * GT, within = tile - g0;
+  const uint32_t g = tile0 / GT, g0 = g * GT;                // (GT is a multiple of a.compact_tiles)
 
   // Both tables go to LDS in rounds of four loads per thread, every load issued before the first
   // is waited for and none behind a branch (an index beyond the table re-reads a valid entry).
@@ -315,18 +319,19 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
       if (i < ngroups * kNumThres) lds_g[i] = v[u];
     }
   }
+  const uint32_t upto = tile1 - 1u - g0;  // tiles of the group before my last tile: all I need
   for (uint32_t i0 = 0; i0 < (uint32_t)(GT * kNumThres); i0 += 4 * kBlock) {
     uint32_t v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t i = i0 + u * kBlock + threadIdx.x;
       const uint32_t p = i < (uint32_t)(GT * kNumThres) ? i / GT : 0u, j = i % GT;
-      v[u] = a.tile_counts[(size_t)p * a.max_tiles + g0 + (j < within ? j : within)];
+      v[u] = a.tile_counts[(size_t)p * a.max_tiles + g0 + (j < upto ? j : upto)];
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t i = i0 + u * kBlock + threadIdx.x;
-      if (i < (uint32_t)(GT * kNumThres)) lds_t[i] = (i % GT < within) ? v[u] : 0u;
+      if (i < (uint32_t)(GT * kNumThres)) lds_t[i] = (i % GT < upto) ? v[u] : 0u;
     }
   }
   double t64[kNumThres];
@@ -350,12 +355,9 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
 #pragma unroll
     for (int j = 0; j < MG; j += 64)
       if ((uint32_t)(j + lane_id()) < g) x += lds_g[(j + lane_id()) * kNumThres + w.pos];
-#pragma unroll
-    for (int j = 0; j < GT; j += 64) x += lds_t[w.pos * GT + j + lane_id()];  // zero from `within` on
     x = wave_sum(x);
-    if (lane_id() == 0) lds_base = x;
+    if (lane_id() == 0) lds_base[0] = x;
   }
-  __syncthreads();
   const double tf = t64[w.pos];
   const float thr = (float)tf;
   // With lists (gaussiank_list.h): they hold every survivor when no stretch ran out and the walk
@@ -365,7 +367,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
     list_totals(a, lds_lists);  // barrier
     listed = lds_lists[1] == 0 && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
   }
-  if (tile == 0 && threadIdx.x == 0) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t flags = flags0;
     if (!w.in_band) flags |= SPARSIFY_F_EXHAUSTED;
     if (overflow) flags |= SPARSIFY_F_OVERFLOW;
@@ -385,19 +387,41 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
     r.acc_sqnorm = 0.0;  // filled by k_norms_finalize when asked for
     r.residual_sqnorm = 0.0;
   }
-  const int64_t out0 = (int64_t)lds_base;
-  if (listed) {  // the residual is in place (the count kernel wrote it); one wave writes the tile's pairs
-    if (!overflow && wave_id() == 0) gk_list_compact_tile(a, tile, thr, (uint32_t)out0);
+  __syncthreads();
+  const uint32_t groups_before = lds_base[0];
+  // survivors of my group's tiles before `tile` (lds_t holds zeros from my last tile on)
+  auto before_in_group = [&](uint32_t tile) {
+    uint32_t x = 0;
+#pragma unroll
+    for (int j = 0; j < GT; j += 64)
+      if ((uint32_t)(j + lane_id()) < tile - g0) x += lds_t[w.pos * GT + j + lane_id()];
+    return wave_sum(x);
+  };
+  if (listed) {  // the residual is in place (the count kernel wrote it); a wave writes a tile's pairs
+    if (!overflow)
+      for (uint32_t tile = tile0 + wave_id(); tile < tile1; tile += kWaves)
+        gk_list_compact_tile(a, tile, thr, groups_before + before_in_group(tile));
     return;
   }
-  uint32_t run = 0;
-  NormAcc norms = {0.0, 0.0};
-  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
-    const Tile t = chunk_of(sp_, u);
-    if (t.full) run = compact_chunk<true, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
-    else run = compact_chunk<false, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
+  for (uint32_t tile = tile0; tile < tile1; ++tile) {
+    Span sp_;
+    if (!locate_span<false>(a, tile, &sp_)) return;
+    if (wave_id() == 0) {
+      const uint32_t x = before_in_group(tile);
+      if (lane_id() == 0) lds_base[1] = groups_before + x;
+    }
+    __syncthreads();
+    const int64_t out0 = (int64_t)lds_base[1];
+    uint32_t run = 0;
+    NormAcc norms = {0.0, 0.0};
+    for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+      const Tile t = chunk_of(sp_, u);
+      if (t.full) run = compact_chunk<true, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
+      else run = compact_chunk<false, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
+    }
+    if (NORMS) store_norm_partial(a, norms, tile, lds_n);
+    __syncthreads();  // lds_base[1] and lds_n are reused by the next tile
   }
-  if (NORMS) store_norm_partial(a, norms, tile, lds_n);
 }
 
 static_assert(kMaxGroups % 64 == 0 && kGroupTiles % 64 == 0 && kBigMaxGroups % 64 == 0 &&

@@ -269,6 +269,10 @@ uint32_t compute_units() {
 // the count kernel then finds less of acc in the cache and slows down, the accumulate kernel gains
 // more (per call: 2 % faster at 50 M elements, 4 % at 59 M, 5 % at 66 M; no difference at 42 M;
 // 3-5 % slower at 84 M and 100 M, and slightly slower at 25.6 M, where it is not used).
+// With lists a workgroup of the compact kernel takes this many tiles (a divisor of the group
+// sizes): the tables every workgroup reads are then read a fraction as often.
+constexpr uint32_t kListCompactTiles = 4;
+static_assert(kGroupTiles % kListCompactTiles == 0 && kBigGroupTiles % kListCompactTiles == 0, "a workgroup's tiles share a group");
 constexpr int64_t kStreamAccFrom = 40'000'000, kStreamAccBelow = 80'000'000;
 bool stream_acc(const Args& a) { return a.d_total >= kStreamAccFrom && a.d_total < kStreamAccBelow; }
 
@@ -298,10 +302,13 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   if (want > a.max_tiles) want = a.max_tiles;
   if (want < 1) want = 1;
   a.moment_parts = want;
+  a.compact_tiles = 1;
   if (a.list) {  // gaussiank_list.h: a stretch of the list buffer per wave of the count kernel
     a.list_cap = (uint32_t)(list_entries(a.d_total) / ((size_t)tiles * kWaves));
     a.list_last = (uint32_t)(list_entries(a.d_total) - 1);
+    a.compact_tiles = kListCompactTiles;
   }
+  const dim3 cgrid((tiles + a.compact_tiles - 1) / a.compact_tiles);
   if (nchunks > kChunkGridFrom) {  // (flat_call has checked that the group tables hold `tiles`)
     // long vector: one chunk per workgroup and a fold of the partials, then short tiles in
     // groups of kBigGroupTiles
@@ -311,10 +318,10 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
     ln.run("fold_moments", k_fold_moments, dim3(a.moment_parts), blk, a);
     ln.run("gk_count", k_gk_count_fused<kBigGroupTiles>, dim3(tiles), blk, a);
     if (a.norms) {
-      ln.run("gk_compact", k_gk_compact_fused<true, kBigGroupTiles, kBigMaxGroups, false>, dim3(tiles), blk, a);
+      ln.run("gk_compact", k_gk_compact_fused<true, kBigGroupTiles, kBigMaxGroups, false>, cgrid, blk, a);
       ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
     } else {
-      ln.run("gk_compact", k_gk_compact_fused<false, kBigGroupTiles, kBigMaxGroups, false>, dim3(tiles), blk, a);
+      ln.run("gk_compact", k_gk_compact_fused<false, kBigGroupTiles, kBigMaxGroups, false>, cgrid, blk, a);
     }
     return;
   }
@@ -327,12 +334,12 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
     if (a.list && a.d_total >= kStreamAccFrom) ln.run("gk_count", k_gk_count_fused<kGroupTiles, true>, dim3(tiles), blk, a);
     else ln.run("gk_count", k_gk_count_fused<kGroupTiles>, dim3(tiles), blk, a);
     if (a.norms) {
-      if (stream_acc(a)) ln.run("gk_compact", k_gk_compact_fused<true, kGroupTiles, kMaxGroups, true>, dim3(tiles), blk, a);
-      else ln.run("gk_compact", k_gk_compact_fused<true, kGroupTiles, kMaxGroups, false>, dim3(tiles), blk, a);
+      if (stream_acc(a)) ln.run("gk_compact", k_gk_compact_fused<true, kGroupTiles, kMaxGroups, true>, cgrid, blk, a);
+      else ln.run("gk_compact", k_gk_compact_fused<true, kGroupTiles, kMaxGroups, false>, cgrid, blk, a);
       ln.run("norms", k_norms_finalize<false>, dim3(1), dim3(kFinBlock), a);
     } else {
-      if (stream_acc(a)) ln.run("gk_compact", k_gk_compact_fused<false, kGroupTiles, kMaxGroups, true>, dim3(tiles), blk, a);
-      else ln.run("gk_compact", k_gk_compact_fused<false, kGroupTiles, kMaxGroups, false>, dim3(tiles), blk, a);
+      if (stream_acc(a)) ln.run("gk_compact", k_gk_compact_fused<false, kGroupTiles, kMaxGroups, true>, cgrid, blk, a);
+      else ln.run("gk_compact", k_gk_compact_fused<false, kGroupTiles, kMaxGroups, false>, cgrid, blk, a);
     }
   }
 }
