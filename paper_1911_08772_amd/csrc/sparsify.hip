@@ -270,9 +270,13 @@ uint32_t compute_units() {
 // more (per call: 2 % faster at 50 M elements, 4 % at 59 M, 5 % at 66 M; no difference at 42 M;
 // 3-5 % slower at 84 M and 100 M, and slightly slower at 25.6 M, where it is not used).
 // With lists a workgroup of the compact kernel takes this many tiles (a divisor of the group
-// sizes): the tables every workgroup reads are then read a fraction as often.
-constexpr uint32_t kListCompactTiles = 4;
-static_assert(kGroupTiles % kListCompactTiles == 0 && kBigGroupTiles % kListCompactTiles == 0, "a workgroup's tiles share a group");
+// size): the tables every workgroup reads are then read a fraction as often, and a wave writes
+// one or two tiles' pairs.  Measured (kernel, event to event): 25.6 M elements 12.3 us with one
+// tile, 10.0 with two or four, 11.8 with eight, 15.1 with sixteen; 66 M elements 17.2 / 14.8 /
+// 18.1 us with two / four / eight; 268 M elements (the larger tables) 87 us with one, 64 with
+// two, 36 with eight or sixteen.
+constexpr uint32_t kListCompactTiles = 4, kBigListCompactTiles = 8;
+static_assert(kGroupTiles % kListCompactTiles == 0 && kBigGroupTiles % kBigListCompactTiles == 0, "a workgroup's tiles share a group");
 constexpr int64_t kStreamAccFrom = 40'000'000, kStreamAccBelow = 80'000'000;
 bool stream_acc(const Args& a) { return a.d_total >= kStreamAccFrom && a.d_total < kStreamAccBelow; }
 
@@ -306,7 +310,7 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   if (a.list) {  // gaussiank_list.h: a stretch of the list buffer per wave of the count kernel
     a.list_cap = (uint32_t)(list_entries(a.d_total) / ((size_t)tiles * kWaves));
     a.list_last = (uint32_t)(list_entries(a.d_total) - 1);
-    a.compact_tiles = kListCompactTiles;
+    a.compact_tiles = nchunks > kChunkGridFrom ? kBigListCompactTiles : kListCompactTiles;
   }
   const dim3 cgrid((tiles + a.compact_tiles - 1) / a.compact_tiles);
   if (nchunks > kChunkGridFrom) {  // (flat_call has checked that the group tables hold `tiles`)
