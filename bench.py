@@ -3,9 +3,12 @@ gradient vector (d = 25,557,032, rho = 0.001) on one MI355X.
 
 One step = one pass of the whole hot path on a fresh synthetic gradient already resident in
 HBM: accumulate, select (Algorithm 1), compact, residual, with the residual carried from step
-to step as in Eq. (2).  `value` is algorithmic GB/s of the Gaussian_k path (24 B per element +
-8 B per survivor); the exact Top_k path, timed the same way, is reported beside it (16 B per
-element when its short lists serve, which the result records say; 24 otherwise), and under
+to step as in Eq. (2).  `value` is algorithmic GB/s of the Gaussian_k path as run: 20 B per
+element when its short lists serve, which the result records say (accumulate 12; count, which
+also writes the residual, 8), 24 otherwise, + 8 B per survivor; the same time priced at 24 B is
+given beside it, for comparison with measurements made before the lists existed.  The exact
+Top_k path, timed the same way, is reported too (16 B per element with its short lists, 24
+without), and under
 `also`: the same two selectors on the workloads that do not fit the last-level cache (LSTM-sized,
 66 M elements) or sit below the headline (VGG-16-sized), in place, layer-wise, the sampling
 comparator DGC_k, and the aggregation of 16 workers' lists (sparsify_scatter_add).
@@ -29,6 +32,11 @@ KERNEL_BYTES_PER_ELEM = {"accum_moments": 12, "gk_count": 4, "gk_compact": 8,
                          "topk_accum_hist": 12, "topk_filter": 4, "topk_compact": 8,
                          "topk_hist1": 4, "topk_hist2": 4, "topk_hist3": 4}
 GK_BYTES_PER_ELEM = 24   # r g, r eps, w acc | r acc (one count pass) | r acc, w eps'
+# Gaussian_k with short lists built in the count pass (from 6 M elements, when the lists serve:
+# the result record says so): r g, r eps, w acc | r acc, w eps'; the compact kernel reads the
+# lists (about k entries), not counted.  In place: r g, r eps, w acc | r acc.
+GK_LIST_BYTES_PER_ELEM = 20
+GK_LIST_INPLACE_BYTES_PER_ELEM = 16
 # r g, r eps, w acc (+digit 1) | r acc (filter: candidates written out) | r acc, w eps'; the
 # candidate lists the three later digit passes read are data dependent and not counted
 TOPK_BYTES_PER_ELEM = 24
@@ -136,6 +144,14 @@ def gbps(bytes_per_elem, d, nnz_mean, ms):
     return (bytes_per_elem * d + 8.0 * nnz_mean) / (ms * 1e-3) / 1e9
 
 
+def gk_bytes_per_elem(listed, inplace):
+    """Algorithmic bytes per element of the Gaussian_k path as run: `listed` of the steps took
+    the short-list way (20 B, 16 in place), the others three passes (24 B, 20 in place)."""
+    a = GK_LIST_INPLACE_BYTES_PER_ELEM if inplace else GK_LIST_BYTES_PER_ELEM
+    b = GK_INPLACE_BYTES_PER_ELEM if inplace else GK_BYTES_PER_ELEM
+    return round(listed * a + (1.0 - listed) * b, 3)
+
+
 def topk_bytes_per_elem(listed, inplace):
     """Algorithmic bytes per element of the Top_k path as run: `listed` of the steps took the
     short-list way (16 B, 12 in place), the others the passes over acc (24 B, 28 in place)."""
@@ -144,10 +160,15 @@ def topk_bytes_per_elem(listed, inplace):
     return round(listed * a + (1.0 - listed) * b, 3)
 
 
-def dominant(stage, d):
+def dominant(stage, d, inplace=False):
     """The streaming kernel with the longest average duration and its algorithmic GB/s."""
-    dom = max((n for n in stage if KERNEL_BYTES_PER_ELEM.get(n, 0) > 0), key=lambda n: stage[n])
-    nbytes = KERNEL_BYTES_PER_ELEM[dom] * d
+    per = dict(KERNEL_BYTES_PER_ELEM)
+    if stage.listed == 1.0 and "gk_count" in stage:
+        # with lists the count kernel also writes eps' and the compact kernel streams nothing
+        per["gk_count"] = 4 if inplace else 8
+        per["gk_compact"] = 0
+    dom = max((n for n in stage if per.get(n, 0) > 0), key=lambda n: stage[n])
+    nbytes = per[dom] * d
     return dom, nbytes, nbytes / (stage[dom] * 1e-3) / 1e9
 
 
@@ -164,13 +185,16 @@ def side_workload(S, torch, synth, name, K, W):
     tk_ms, _, _ = f.timed(S.sparsify_topk)
     tk_stage, _, _ = f.traced(S.sparsify_topk)
     dom, nbytes, dom_gbps = dominant(gk_stage, wl.d)
-    g = gbps(GK_BYTES_PER_ELEM, wl.d, float(np.mean(gk_nnz)), gk_ms)
+    gk_bpe = gk_bytes_per_elem(gk_stage.listed, False)
+    g = gbps(gk_bpe, wl.d, float(np.mean(gk_nnz)), gk_ms)
     tk_bpe = topk_bytes_per_elem(tk_stage.listed, False)
     t = gbps(tk_bpe, wl.d, float(wl.k), tk_ms)
     out = {"workload": wl.describe(), "gradient_pool": pool, "steps": K, "warmup": W,
            "working_set_MB": round(12 * wl.d / 1e6, 1),
            "gaussiank": {"ms_per_step": round(gk_ms, 5), "GBps": round(g, 2),
                          "pct_hbm_peak": round(100.0 * g / HBM_PEAK_GBPS, 2),
+                         "bytes_per_elem": gk_bpe, "steps_from_short_lists": gk_stage.listed,
+                         "GBps_at_24B_per_elem": round(gbps(GK_BYTES_PER_ELEM, wl.d, float(np.mean(gk_nnz)), gk_ms), 2),
                          "nnz_mean": float(np.mean(gk_nnz)), "rounds_mean": float(np.mean(gk_rounds)),
                          "kernel_ms": {n: round(v, 5) for n, v in gk_stage.items()},
                          "kernel_ms_median": {n: round(v, 5) for n, v in gk_stage.median.items()}},
@@ -309,7 +333,7 @@ def main() -> int:
         fi = Flat(S, torch, wl, grads, K, W, True)
         extras["inplace"] = {"gaussiank_ms": round(fi.timed(S.sparsify_gaussiank)[1], 5),
                              "topk_ms": round(fi.timed(S.sparsify_topk)[1], 5),
-                             "note": "acc == residual: 20 B per element for Gaussian_k, 12 for Top_k when its short lists serve (28 otherwise)"}
+                             "note": "acc == residual: 16 B per element for Gaussian_k and 12 for Top_k when their short lists serve (20 and 28 otherwise)"}
         del fi
         # layer-wise call: 54 segments of the same total length, one launch sequence per step
         if wl.d == 25_557_032:
@@ -339,11 +363,11 @@ def main() -> int:
             del bs
         extras["scatter_add"] = scatter_add_bench(S, torch, wl, grads, K, W)
 
-    gk_bpe = GK_INPLACE_BYTES_PER_ELEM if args.inplace else GK_BYTES_PER_ELEM
+    gk_bpe = gk_bytes_per_elem(gk_stage.listed, args.inplace)
     tk_bpe = topk_bytes_per_elem(tk_stage.listed, args.inplace)
     gk_gbps = gbps(gk_bpe, d, float(np.mean(gk_nnz)), gk_ms)
     tk_gbps = gbps(tk_bpe, d, float(k), tk_ms)
-    dom, dom_bytes, dom_gbps = dominant(gk_stage, d)
+    dom, dom_bytes, dom_gbps = dominant(gk_stage, d, args.inplace)
     traffic, traffic_source = read_traffic(args.workload, dom)
 
     if not args.no_extras and args.workload == "cfg3_resnet50":
@@ -367,6 +391,11 @@ def main() -> int:
         "pct_hbm_peak": round(100.0 * gk_gbps / HBM_PEAK_GBPS, 2),
         "gaussiank": {"ms_per_step": round(gk_ms, 5), "wall_ms": round(gk_wall, 5),
                       "event_ms": round(gk_ev, 5), "bytes_per_elem": gk_bpe,
+                      "steps_from_short_lists": gk_stage.listed,
+                      # the same time priced at the three passes' 24 B (20 in place) per element,
+                      # the figure of the measurements made before the lists existed
+                      "GBps_at_three_pass_bytes": round(gbps(GK_INPLACE_BYTES_PER_ELEM if args.inplace else GK_BYTES_PER_ELEM,
+                                                             d, float(np.mean(gk_nnz)), gk_ms), 2),
                       "nnz_mean": float(np.mean(gk_nnz)), "rounds_mean": float(np.mean(gk_rounds)),
                       "spread": gk_spread,
                       "kernel_ms": {n: round(v, 5) for n, v in gk_stage.items()},
