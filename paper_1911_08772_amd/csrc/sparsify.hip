@@ -106,9 +106,10 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
 // replicas of each segment's global histogram: spreads same-address atomics of the flat call
 uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
 
-// Short-list Top_k (topk_list.h): flat vectors long enough for the passes saved to matter.  The
-// list buffer holds kListShare of the vector's length in entries (the lists are expected to take
-// max(4 k, 0.4 % of d)), split evenly among the accumulate kernel's waves.
+// Short lists (lists.h; Top_k: topk_list.h, DGC_k: dgck.h, Gaussian_k: gaussiank_list.h): flat
+// vectors long enough for the passes saved to matter.  The list buffer holds kListShare of the
+// vector's length in entries (Top_k's lists are expected to take max(4 k, 0.4 % of d), the
+// others' about k), split evenly among the waves of the kernel that writes them.
 constexpr int64_t kListFrom = 6'000'000;
 constexpr double kListShare = 0.10;
 bool list_sized(int64_t d_total, int32_t L) {
@@ -513,8 +514,8 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   if (rc != SPARSIFY_OK) return rc;
   a.flat_k = k;
   a.flat_cap = cap;
-  // the short-list forms: Top_k and DGC_k without the norms, k small enough for the lists' share
-  // of the workspace, where the workspace has room at all (prepare)
+  // the short-list forms: no norms asked for, k small enough for the lists' share of the
+  // workspace, where the workspace has room at all (prepare)
   if (a.norms || (opts && opts->short_list < 0) || 2.0 * kListAim * (double)k > kListShare * (double)d)
     a.list = nullptr;
   if (!(opts && opts->tile_chunks != 0))
