@@ -103,6 +103,7 @@ struct Args {
   uint2* run_table;       // [chunks * 16]: (first entry, entries) of each 256-element run
   uint32_t* list_stats;   // [2][kListStatCopies]: entries listed (replicated sums), stretches that ran out
   uint32_t compact_tiles; // Gaussian_k, flat: consecutive tiles per workgroup of the compact kernel
+  uint32_t flat_tiles;    //   and the number of tiles of the vector
   uint32_t list_cap;      // entries per wave of the accumulate kernel
   uint32_t list_last;     // index of the buffer's last entry
 };

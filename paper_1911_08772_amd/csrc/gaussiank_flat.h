@@ -296,13 +296,23 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   __shared__ uint32_t lds_lists[2];
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
-  const uint32_t ntiles = seg_ntiles(0, a.d_total, a.tile_chunks);
+  const uint32_t ntiles = a.flat_tiles;
   const uint32_t tile0 = blockIdx.x * a.compact_tiles;
   if (tile0 >= ntiles) return;
   const uint32_t tile1 = tile0 + a.compact_tiles < ntiles ? tile0 + a.compact_tiles : ntiles;
   SegCtrl& c = a.ctrl[0];
   const uint32_t ngroups = (ntiles + GT - 1) / GT;
   const uint32_t g = tile0 / GT, g0 = g * GT;                // (GT is a multiple of a.compact_tiles)
+  // with lists: what the end of this kernel reads first is fetched before the tables (the lists'
+  // statistics words, the records of the runs of this wave's first tile), so that those trips to
+  // memory overlap the prologue
+  uint32_t list_word = 0;
+  uint2 first_rec = make_uint2(0u, 0u);
+  if (a.list) {
+    list_word = a.list_stats[lane_id()];
+    const uint32_t t = tile0 + wave_id();
+    first_rec = gk_list_first_records(a, t < tile1 ? t : tile1 - 1u);
+  }
 
   // Both tables go to LDS in rounds of four loads per thread, every load issued before the first
   // is waited for and none behind a branch (an index beyond the table re-reads a valid entry).
@@ -351,12 +361,19 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   const Walk w = walk_thresholds(tot, a.flat_k);
   const bool overflow = (int64_t)tot[w.pos] > a.flat_cap;
   if (wave_id() == 0) {
-    uint32_t x = 0;
+    uint32_t x = 0, y = 0;
 #pragma unroll
     for (int j = 0; j < MG; j += 64)
       if ((uint32_t)(j + lane_id()) < g) x += lds_g[(j + lane_id()) * kNumThres + w.pos];
+#pragma unroll
+    for (int j = 0; j < GT; j += 64)
+      if ((uint32_t)(j + lane_id()) < tile0 - g0) y += lds_t[w.pos * GT + j + lane_id()];
     x = wave_sum(x);
-    if (lane_id() == 0) lds_base[0] = x;
+    y = wave_sum(y);
+    if (lane_id() == 0) {
+      lds_base[0] = x;
+      lds_base[1] = x + y;  // survivors before my first tile
+    }
   }
   const double tf = t64[w.pos];
   const float thr = (float)tf;
@@ -364,7 +381,11 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   // ended at thres0 or above it.
   bool listed = false;
   if (a.list) {
-    list_totals(a, lds_lists);  // barrier
+    if (wave_id() == 0) {  // (list_totals of lists.h on the word fetched above)
+      const uint64_t over = __ballot(lane_id() >= kListStatCopies && list_word != 0);
+      if (lane_id() == 0) lds_lists[1] = over != 0 ? 1u : 0u;
+    }
+    __syncthreads();
     listed = lds_lists[1] == 0 && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -399,18 +420,22 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   };
   if (listed) {  // the residual is in place (the count kernel wrote it); a wave writes a tile's pairs
     if (!overflow)
-      for (uint32_t tile = tile0 + wave_id(); tile < tile1; tile += kWaves)
-        gk_list_compact_tile(a, tile, thr, groups_before + before_in_group(tile));
+      for (uint32_t tile = tile0 + wave_id(); tile < tile1; tile += kWaves) {
+        const uint2 rec = tile == tile0 + wave_id() ? first_rec : gk_list_first_records(a, tile);
+        gk_list_compact_tile(a, tile, thr, groups_before + before_in_group(tile), rec);
+      }
     return;
   }
   for (uint32_t tile = tile0; tile < tile1; ++tile) {
     Span sp_;
     if (!locate_span<false>(a, tile, &sp_)) return;
-    if (wave_id() == 0) {
-      const uint32_t x = before_in_group(tile);
-      if (lane_id() == 0) lds_base[1] = groups_before + x;
+    if (tile != tile0) {  // (the first tile's slot is there already)
+      if (wave_id() == 0) {
+        const uint32_t x = before_in_group(tile);
+        if (lane_id() == 0) lds_base[1] = groups_before + x;
+      }
+      __syncthreads();
     }
-    __syncthreads();
     const int64_t out0 = (int64_t)lds_base[1];
     uint32_t run = 0;
     NormAcc norms = {0.0, 0.0};
@@ -420,7 +445,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
       else run = compact_chunk<false, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
     }
     if (NORMS) store_norm_partial(a, norms, tile, lds_n);
-    __syncthreads();  // lds_base[1] and lds_n are reused by the next tile
+    if (tile + 1 < tile1) __syncthreads();  // lds_base[1] and lds_n are reused by the next tile
   }
 }
 

@@ -87,42 +87,41 @@ __device__ inline void count_list_chunk(const Args& a, const Tile& t, const floa
   if (!a.inplace) store_tile<FULL>(a.resid, t, v, valid);
 }
 
+// The records of the first 64 runs of a tile, one per lane: fetched before the compact kernel's
+// prologue so that they are there when the walk is done.
+__device__ inline uint2 gk_list_first_records(const Args& a, uint32_t tile) {
+  uint32_t r0, r1;
+  tile_runs(a, tile, &r0, &r1);
+  const uint32_t r = r0 + lane_id();
+  return a.run_table[r < r1 ? r : r1 - 1u];
+}
+
 // The pairs of one tile from its lists, in index order, by one wave: `out0` survivors precede
 // the tile.  A lane owns a run; the lanes' counts are scanned across the wave, then every lane
-// writes its run's survivors one after the other and clears them in the residual.
-__device__ inline void gk_list_compact_tile(const Args& a, uint32_t tile, float thr, uint32_t out0) {
+// writes its run's survivors one after the other and clears them in the residual.  `first` holds
+// the records of the tile's first 64 runs (gk_list_first_records).  Runs of up to kListBatch
+// entries, the rule, are read once and kept in registers between the count and the write.
+__device__ inline void gk_list_compact_tile(const Args& a, uint32_t tile, float thr, uint32_t out0,
+                                            uint2 first) {
   uint32_t r0, r1;
   tile_runs(a, tile, &r0, &r1);
   uint32_t out_run = out0;
   for (uint32_t rb = r0; rb < r1; rb += 64) {
     const uint32_t r = rb + lane_id();
-    const uint2 rec = a.run_table[r < r1 ? r : r1 - 1u];
+    const uint2 rec = rb == r0 ? first : a.run_table[r < r1 ? r : r1 - 1u];
     const uint32_t n = r < r1 ? rec.y : 0u, off = rec.x;
     const uint32_t last = n ? n - 1u : 0u;
     const uint32_t nmax = wave_max(n);
-    uint32_t csel = 0;
-    for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
-      uint2 e[kListBatch];
+    if (nmax == 0) continue;
+    auto fetch = [&](uint32_t i0, uint2 (&e)[kListBatch]) {
 #pragma unroll
       for (int u = 0; u < kListBatch; ++u) {
         uint32_t i = off + (i0 + u < last ? i0 + u : last);
         i = i < a.list_last ? i : a.list_last;
         e[u] = a.list[i];
       }
-#pragma unroll
-      for (int u = 0; u < kListBatch; ++u)
-        csel += (i0 + u < n && fabsf(__uint_as_float(e[u].y)) > thr) ? 1u : 0u;
-    }
-    const uint32_t inc = wave_inclusive_scan(csel);
-    uint32_t pos = out_run + inc - csel;
-    for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
-      uint2 e[kListBatch];
-#pragma unroll
-      for (int u = 0; u < kListBatch; ++u) {
-        uint32_t i = off + (i0 + u < last ? i0 + u : last);
-        i = i < a.list_last ? i : a.list_last;
-        e[u] = a.list[i];
-      }
+    };
+    auto emit = [&](uint32_t i0, const uint2 (&e)[kListBatch], uint32_t& pos) {
 #pragma unroll
       for (int u = 0; u < kListBatch; ++u) {
         const float val = __uint_as_float(e[u].y);
@@ -134,6 +133,24 @@ __device__ inline void gk_list_compact_tile(const Args& a, uint32_t tile, float 
           a.resid[e[u].x] = 0.0f;
           ++pos;
         }
+      }
+    };
+    uint2 e[kListBatch];
+    uint32_t csel = 0;
+    for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
+      fetch(i0, e);
+#pragma unroll
+      for (int u = 0; u < kListBatch; ++u)
+        csel += (i0 + u < n && fabsf(__uint_as_float(e[u].y)) > thr) ? 1u : 0u;
+    }
+    const uint32_t inc = wave_inclusive_scan(csel);
+    uint32_t pos = out_run + inc - csel;
+    if (nmax <= (uint32_t)kListBatch) {
+      emit(0, e, pos);  // (the one batch is still in registers)
+    } else {
+      for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
+        fetch(i0, e);
+        emit(i0, e, pos);
       }
     }
     out_run += __shfl(inc, 63, 64);

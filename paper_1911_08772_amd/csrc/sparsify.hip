@@ -308,6 +308,7 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
   if (want < 1) want = 1;
   a.moment_parts = want;
   a.compact_tiles = 1;
+  a.flat_tiles = tiles;
   if (a.list) {  // gaussiank_list.h: a stretch of the list buffer per wave of the count kernel
     a.list_cap = (uint32_t)(list_entries(a.d_total) / ((size_t)tiles * kWaves));
     a.list_last = (uint32_t)(list_entries(a.d_total) - 1);
