@@ -50,8 +50,9 @@ enum {
   SPARSIFY_F_BADSEGMENT = 8u, /* segmented call: this segment's offsets, k or output range are
                                 invalid (or its start lies before an earlier offset); no kernel
                                 touches its stretch of acc, residual or the output */
-  /* The next two say which way a flat call took, not what it computed (the results are the same
-     either way); neither is set when the call built no short lists to begin with. */
+  /* The next two say which way a flat call (or a segment of a layer-wise Gaussian_k call) took,
+     not what it computed (the results are the same either way); neither is set when the call
+     built no short lists to begin with. */
   SPARSIFY_F_SHORTLIST = 16u,     /* the pairs (Top_k, DGC_k: and the digit passes) were taken from
                                      the short lists */
   SPARSIFY_F_SHORTLIST_MISS = 32u /* the lists were built but held fewer than k entries (Top_k),
@@ -97,14 +98,16 @@ typedef struct {
   int32_t sample_stride; /* DGC_k only.  0 (default): 100, a 1 % sample (Sec. 4.3).  Otherwise the
                       stratum length S >= 1: one sampled position per S consecutive elements */
   uint64_t sample_seed;  /* DGC_k only: seed of the counter-based choice of those positions */
-  int32_t short_list;    /* flat calls.  0 (default): the library decides.  -1: never build the
-                      short lists (below).  Results do not depend on it. */
+  int32_t short_list;    /* flat calls and layer-wise Gaussian_k.  0 (default): the library
+                      decides.  -1: never build the short lists (below).  Results do not depend
+                      on it. */
 } sparsify_opts;
 
 /* Bytes of `workspace` for a vector of d_total elements in num_segments segments (1 for the
  * flat calls).  Returns 0 for invalid arguments.
- *   sparsify_workspace_bytes      the size to allocate.  For flat vectors of 6 M elements and more
- *                                 it includes room for short lists (0.8 bytes per element).  Top_k:
+ *   sparsify_workspace_bytes      the size to allocate.  For vectors of 6 M elements and more (in
+ *                                 up to 1024 segments) it includes room for short lists (0.8
+ *                                 bytes per element).  Top_k, flat call:
  *                                 the accumulate pass then also writes the residual and
  *                                 lists the entries above a key guessed from a sample of acc,
  *                                 a fraction of a per cent of the vector; if the lists turn out
@@ -119,7 +122,8 @@ typedef struct {
  *                                 residual and lists the entries above thres0, and when the
  *                                 refinement ends at thres0 or above, the pairs are written from
  *                                 those lists (20 bytes per element instead of 24, 16 instead of
- *                                 20 in place).
+ *                                 20 in place); in the layer-wise call every segment decides for
+ *                                 itself.
  *   sparsify_workspace_bytes_min  the smallest size any call accepts; with less than the size
  *                                 above, no call builds the lists. */
 size_t sparsify_workspace_bytes(int64_t d_total, int32_t num_segments);

@@ -104,7 +104,8 @@ struct Args {
   uint32_t* list_stats;   // [2][kListStatCopies]: entries listed (replicated sums), stretches that ran out
   uint32_t compact_tiles; // Gaussian_k, flat: consecutive tiles per workgroup of the compact kernel
   uint32_t flat_tiles;    //   and the number of tiles of the vector
-  uint32_t list_cap;      // entries per wave of the accumulate kernel
+  uint32_t list_cap;      // entries per wave of the kernel that writes the lists
+  uint32_t run_cap;       // records the run table holds (host-side check only)
   uint32_t list_last;     // index of the buffer's last entry
 };
 

@@ -255,8 +255,9 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
     lc.over = false;
     for (uint32_t u = 0; u < sp_.nchunks; ++u) {
       const Tile t = chunk_of(sp_, u);
-      if (t.full) count_list_chunk<true, STREAM>(a, t, thr, cnt, lc);
-      else count_list_chunk<false, STREAM>(a, t, thr, cnt, lc);
+      const uint32_t run0 = (uint32_t)(t.tbase / kRun);
+      if (t.full) count_list_chunk<true, STREAM>(a, t, run0, thr, cnt, lc);
+      else count_list_chunk<false, STREAM>(a, t, run0, thr, cnt, lc);
     }
     if (lc.over && lane_id() == 0) atomicOr(&a.list_stats[kListStatCopies + tile % kListStatCopies], 1u);
   } else {
@@ -311,7 +312,9 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   if (a.list) {
     list_word = a.list_stats[lane_id()];
     const uint32_t t = tile0 + wave_id();
-    first_rec = gk_list_first_records(a, t < tile1 ? t : tile1 - 1u);
+    uint32_t r0, r1;
+    tile_runs(a, t < tile1 ? t : tile1 - 1u, &r0, &r1);
+    first_rec = gk_list_first_records(a, r0, r1);
   }
 
   // Both tables go to LDS in rounds of four loads per thread, every load issued before the first
@@ -421,8 +424,10 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   if (listed) {  // the residual is in place (the count kernel wrote it); a wave writes a tile's pairs
     if (!overflow)
       for (uint32_t tile = tile0 + wave_id(); tile < tile1; tile += kWaves) {
-        const uint2 rec = tile == tile0 + wave_id() ? first_rec : gk_list_first_records(a, tile);
-        gk_list_compact_tile(a, tile, thr, groups_before + before_in_group(tile), rec);
+        uint32_t r0, r1;
+        tile_runs(a, tile, &r0, &r1);
+        const uint2 rec = tile == tile0 + wave_id() ? first_rec : gk_list_first_records(a, r0, r1);
+        gk_list_compact_tile(a, r0, r1, thr, (int64_t)(groups_before + before_in_group(tile)), a.flat_cap, rec);
       }
     return;
   }

@@ -24,9 +24,10 @@ constexpr int kGkListPos = 5;  // position of thres0 among the ten thresholds in
 // count_values of gaussiank.h for thresholds known to ascend, plus the list of the slot's
 // entries above thr[kGkListPos] (the ballots are those of the count).
 template <bool FULL>
-__device__ inline void count_list_values(const Args& a, int64_t tbase, const float (&v)[kPerThread],
-                                         uint32_t valid, const float (&thr)[kNumThres],
-                                         uint32_t (&cnt)[kNumThres], ListCursor& lc) {
+__device__ inline void count_list_values(const Args& a, int64_t tbase, uint32_t run0,
+                                         const float (&v)[kPerThread], uint32_t valid,
+                                         const float (&thr)[kNumThres], uint32_t (&cnt)[kNumThres],
+                                         ListCursor& lc) {
   uint32_t off[kSlots], len[kSlots];
 #pragma unroll
   for (int j = 0; j < kSlots; ++j) {
@@ -73,39 +74,36 @@ __device__ inline void count_list_values(const Args& a, int64_t tbase, const flo
       }
     }
   }
-  list_record_runs(a, tbase, off, len);
+  list_record_runs(a, run0, off, len);
 }
 
 // One chunk of the count kernel with lists: counts, the residual as if nothing were selected
 // (nothing to write when acc is the residual), the list.
 template <bool FULL, bool STREAM>  // STREAM: acc is read with the non-temporal hint (its last use if the lists serve)
-__device__ inline void count_list_chunk(const Args& a, const Tile& t, const float (&thr)[kNumThres],
-                                        uint32_t (&cnt)[kNumThres], ListCursor& lc) {
+__device__ inline void count_list_chunk(const Args& a, const Tile& t, uint32_t run0,
+                                        const float (&thr)[kNumThres], uint32_t (&cnt)[kNumThres],
+                                        ListCursor& lc) {
   float v[kPerThread];
   const uint32_t valid = load_tile<FULL, STREAM>(a.acc, t, v);
-  count_list_values<FULL>(a, t.tbase, v, valid, thr, cnt, lc);
+  count_list_values<FULL>(a, t.tbase, run0, v, valid, thr, cnt, lc);
   if (!a.inplace) store_tile<FULL>(a.resid, t, v, valid);
 }
 
-// The records of the first 64 runs of a tile, one per lane: fetched before the compact kernel's
-// prologue so that they are there when the walk is done.
-__device__ inline uint2 gk_list_first_records(const Args& a, uint32_t tile) {
-  uint32_t r0, r1;
-  tile_runs(a, tile, &r0, &r1);
+// The records of the first 64 runs of a tile (runs r0 .. r1 - 1), one per lane: fetched before
+// the compact kernel's prologue so that they are there when the walk is done.
+__device__ inline uint2 gk_list_first_records(const Args& a, uint32_t r0, uint32_t r1) {
   const uint32_t r = r0 + lane_id();
   return a.run_table[r < r1 ? r : r1 - 1u];
 }
 
-// The pairs of one tile from its lists, in index order, by one wave: `out0` survivors precede
-// the tile.  A lane owns a run; the lanes' counts are scanned across the wave, then every lane
+// The pairs of one tile (runs r0 .. r1 - 1) from its lists, in index order, by one wave: the
+// tile's first pair goes to slot `out0`; nothing is written at or beyond slot `cap`.  A lane owns a run; the lanes' counts are scanned across the wave, then every lane
 // writes its run's survivors one after the other and clears them in the residual.  `first` holds
 // the records of the tile's first 64 runs (gk_list_first_records).  Runs of up to kListBatch
 // entries, the rule, are read once and kept in registers between the count and the write.
-__device__ inline void gk_list_compact_tile(const Args& a, uint32_t tile, float thr, uint32_t out0,
-                                            uint2 first) {
-  uint32_t r0, r1;
-  tile_runs(a, tile, &r0, &r1);
-  uint32_t out_run = out0;
+__device__ inline void gk_list_compact_tile(const Args& a, uint32_t r0, uint32_t r1, float thr,
+                                            int64_t out0, int64_t cap, uint2 first) {
+  int64_t out_run = out0;
   for (uint32_t rb = r0; rb < r1; rb += 64) {
     const uint32_t r = rb + lane_id();
     const uint2 rec = rb == r0 ? first : a.run_table[r < r1 ? r : r1 - 1u];
@@ -121,12 +119,12 @@ __device__ inline void gk_list_compact_tile(const Args& a, uint32_t tile, float 
         e[u] = a.list[i];
       }
     };
-    auto emit = [&](uint32_t i0, const uint2 (&e)[kListBatch], uint32_t& pos) {
+    auto emit = [&](uint32_t i0, const uint2 (&e)[kListBatch], int64_t& pos) {
 #pragma unroll
       for (int u = 0; u < kListBatch; ++u) {
         const float val = __uint_as_float(e[u].y);
         if (i0 + u < n && fabsf(val) > thr) {
-          if ((int64_t)pos < a.flat_cap) {
+          if (pos < cap) {
             a.out_idx[pos] = e[u].x;
             a.out_val[pos] = val;
           }
@@ -144,7 +142,7 @@ __device__ inline void gk_list_compact_tile(const Args& a, uint32_t tile, float 
         csel += (i0 + u < n && fabsf(__uint_as_float(e[u].y)) > thr) ? 1u : 0u;
     }
     const uint32_t inc = wave_inclusive_scan(csel);
-    uint32_t pos = out_run + inc - csel;
+    int64_t pos = out_run + (int64_t)(inc - csel);
     if (nmax <= (uint32_t)kListBatch) {
       emit(0, e, pos);  // (the one batch is still in registers)
     } else {
@@ -153,7 +151,7 @@ __device__ inline void gk_list_compact_tile(const Args& a, uint32_t tile, float 
         emit(i0, e, pos);
       }
     }
-    out_run += __shfl(inc, 63, 64);
+    out_run += (int64_t)__shfl(inc, 63, 64);
   }
 }
 

@@ -4,9 +4,17 @@
 // segment's groups of 64 tiles, walks Algorithm 1 and finds its first output slot.  A segment's
 // groups are its own (numbered by k_seg_setup), so no total mixes two segments' thresholds.
 // All workgroups of a segment run the same arithmetic on the same inputs in the same order.
+//
+// With short lists (gaussiank_list.h; vectors of 6 M elements and more, where the workspace has
+// room): the count kernel also writes the residual and lists each tile's entries above its
+// segment's thres0, and the tiles of a segment whose walk ended at thres0 or above take their
+// pairs from the lists.  Segments decide for themselves; a stretch of the list buffer that ran
+// out anywhere leaves all of them with the streaming compaction.  A tile's runs are numbered
+// (tile * tile_chunks + chunk) * 16 + run.
 #pragma once
 #include "common.h"
 #include "gaussiank.h"
+#include "gaussiank_list.h"
 #include "setup.h"
 #include "tile_io.h"
 
@@ -93,10 +101,27 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_seg(const Args a) {
   uint32_t cnt[kNumThres];
 #pragma unroll
   for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
-  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
-    const Tile t = chunk_of(sp_, u);
-    if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
-    else count_chunk<false>(a, t, thr, can_skip, cnt);
+  if (a.list && can_skip) {
+    // with lists: the entries above thres0, and the residual as if nothing were selected; each
+    // wave has a stretch of the list buffer for this tile
+    const uint32_t worker = tile * kWaves + wave_id();
+    ListCursor lc;
+    lc.cur = worker * a.list_cap;
+    lc.end = lc.cur + a.list_cap;
+    lc.over = false;
+    for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+      const Tile t = chunk_of(sp_, u);
+      const uint32_t run0 = (tile * a.tile_chunks + u) * kRunsPerChunk;
+      if (t.full) count_list_chunk<true, false>(a, t, run0, thr, cnt, lc);
+      else count_list_chunk<false, false>(a, t, run0, thr, cnt, lc);
+    }
+    if (lc.over && lane_id() == 0) atomicOr(&a.list_stats[kListStatCopies + tile % kListStatCopies], 1u);
+  } else {
+    for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+      const Tile t = chunk_of(sp_, u);
+      if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
+      else count_chunk<false>(a, t, thr, can_skip, cnt);
+    }
   }
   if (lane_id() == 0) {
 #pragma unroll
@@ -159,11 +184,16 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_seg(const Args a) {
   __shared__ uint32_t lds_pre[kNumThres];
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
+  __shared__ uint32_t lds_lists[2];
   const uint32_t tile = blockIdx.x;
   Span sp_;
   if (!locate_span<true>(a, tile, &sp_)) return;
   SegCtrl& c = a.ctrl[sp_.seg];
   if (c.bad) return;
+  // with lists: the runs of this tile, and their records fetched before the tables
+  const uint32_t r0 = tile * a.tile_chunks * kRunsPerChunk, r1 = r0 + sp_.nchunks * kRunsPerChunk;
+  uint2 first_rec = make_uint2(0u, 0u);
+  if (a.list) first_rec = gk_list_first_records(a, r0, r1);
   double t64[kNumThres];
 #pragma unroll
   for (int p = 0; p < kNumThres; ++p) t64[p] = c.t64[p];
@@ -176,10 +206,18 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_seg(const Args a) {
   const bool overflow = (int64_t)tot[w.pos] > c.cap;
   const double tf = t64[w.pos];
   const float thr = (float)tf;
+  // With lists: they hold the segment's survivors when no stretch ran out (anywhere), the
+  // segment's thres0 is positive and its walk ended at thres0 or above it.
+  bool listed = false;
+  if (a.list) {
+    list_totals(a, lds_lists);  // barrier
+    listed = lds_lists[1] == 0 && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
+  }
   if (tile == c.tile0 && threadIdx.x == 0) {
     uint32_t flags = flags0;
     if (!w.in_band) flags |= SPARSIFY_F_EXHAUSTED;
     if (overflow) flags |= SPARSIFY_F_OVERFLOW;
+    if (a.list) flags |= listed ? SPARSIFY_F_SHORTLIST : SPARSIFY_F_SHORTLIST_MISS;  // which way, no result
     sparsify_result& r = a.result[sp_.seg];
     r.nnz = overflow ? 0u : tot[w.pos];
     r.rounds = w.rounds;
@@ -196,6 +234,10 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_seg(const Args a) {
     r.residual_sqnorm = 0.0;
   }
   const int64_t out0 = c.out_base + (int64_t)lds_pre[w.pos];
+  if (listed) {  // the residual is in place (the count kernel wrote it); one wave writes the tile's pairs
+    if (!overflow && wave_id() == 0) gk_list_compact_tile(a, r0, r1, thr, out0, c.out_base + c.cap, first_rec);
+    return;
+  }
   uint32_t run = 0;
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {

@@ -51,15 +51,16 @@ __device__ inline void list_append_run(const Args& a, uint32_t i0, const float (
   }
 }
 
-// The records of this wave's four runs of the chunk at tbase: run (chunk, slot j, wave w) covers
-// elements [256 r, 256 r + 256), r = tbase / 256 + 4 j + w.
-__device__ inline void list_record_runs(const Args& a, int64_t tbase, const uint32_t (&off)[kSlots],
+// The records of this wave's four runs of a chunk whose first run is run0: run (chunk, slot j,
+// wave w) is run0 + 4 j + w.  (Flat vectors: run0 = tbase / 256, run r covers elements
+// [256 r, 256 r + 256); layer-wise calls number the runs by tile and chunk.)
+__device__ inline void list_record_runs(const Args& a, uint32_t run0, const uint32_t (&off)[kSlots],
                                         const uint32_t (&cnt)[kSlots]) {
   if (lane_id() < kSlots) {
     const int j = lane_id();
     const uint32_t o = j == 0 ? off[0] : j == 1 ? off[1] : j == 2 ? off[2] : off[3];
     const uint32_t c = j == 0 ? cnt[0] : j == 1 ? cnt[1] : j == 2 ? cnt[2] : cnt[3];
-    a.run_table[(tbase / kRun) + j * kWaves + wave_id()] = make_uint2(o, c);
+    a.run_table[run0 + j * kWaves + wave_id()] = make_uint2(o, c);
   }
 }
 

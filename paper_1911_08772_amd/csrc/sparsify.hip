@@ -112,8 +112,10 @@ uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 
 // others' about k), split evenly among the waves of the kernel that writes them.
 constexpr int64_t kListFrom = 6'000'000;
 constexpr double kListShare = 0.10;
+// (Layer-wise calls: Gaussian_k only, and up to kListMaxSegments segments, which bounds the run table.)
+constexpr int32_t kListMaxSegments = 1024;
 bool list_sized(int64_t d_total, int32_t L) {
-  return L == 1 && d_total >= kListFrom;
+  return L <= kListMaxSegments && d_total >= kListFrom;
 }
 size_t list_entries(int64_t d_total) { return (size_t)(kListShare * (double)d_total) + 64 * (size_t)kWaves * kMaxMomentParts; }
 
@@ -121,6 +123,7 @@ struct Carve {
   size_t ctrl, tile_start, partial, folded, tile_counts, tile_base, tie_base, group_counts, seg_groups,
       norm_partial, hist, tile_hist, total;
   size_t list, run_table, list_stats;  // with lists only
+  size_t run_entries;
   uint32_t max_groups;
 };
 Carve carve(int64_t d_total, int32_t L, bool lists = false) {
@@ -146,10 +149,14 @@ Carve carve(int64_t d_total, int32_t L, bool lists = false) {
   const size_t hist_tiles = mt < (size_t)kFusedMaxTiles ? mt : (size_t)kFusedMaxTiles;
   c.tile_hist = off;   off = align_up(off + sizeof(uint32_t) * kLastDigitBins * hist_tiles);
   c.list = c.run_table = c.list_stats = 0;
+  c.run_entries = 0;
   if (lists) {  // appended, so that the layout above does not depend on them
+    // one record per 256-element run of every chunk of every tile: the vector's chunks plus, per
+    // segment, the ragged head and tail tiles at the default tile length
     const size_t chunks = (size_t)((d_total + kChunk - 1) / kChunk);
+    c.run_entries = (chunks + (size_t)tile_chunks_of(d_total, false) * (2 * (size_t)L + 1)) * kRunsPerChunk;
     c.list_stats = off;  off = align_up(off + sizeof(uint32_t) * 2 * kListStatCopies);
-    c.run_table = off;   off = align_up(off + sizeof(uint2) * chunks * kRunsPerChunk);
+    c.run_table = off;   off = align_up(off + sizeof(uint2) * c.run_entries);
     c.list = off;        off = align_up(off + sizeof(uint2) * list_entries(d_total));
   }
   c.total = off;
@@ -240,6 +247,7 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
     a.list = reinterpret_cast<uint2*>(w + cv.list);
     a.run_table = reinterpret_cast<uint2*>(w + cv.run_table);
     a.list_stats = reinterpret_cast<uint32_t*>(w + cv.list_stats);
+    a.run_cap = (uint32_t)cv.run_entries;
   }
   a.tile_chunks = tile_chunks_of(d_total, false);
   if (opts && opts->tile_chunks != 0) {
@@ -628,11 +636,21 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   a.seg_off = seg_off;
   a.seg_k = seg_k;
   a.out_off = out_off;
+  // upper bound of the tile count for this tiling; surplus workgroups exit at once
+  const uint32_t tiles = max_tiles_of(d_total, num_segments, a.tile_chunks);
+  // short lists (gaussiank_seg.h): Gaussian_k without the norms, where the workspace has room
+  // (prepare) and the run table holds this tiling's runs
+  if (mode != 1 || a.norms || (opts && opts->short_list < 0) ||
+      (uint64_t)tiles * a.tile_chunks * kRunsPerChunk > (uint64_t)a.run_cap)
+    a.list = nullptr;
+  if (a.list) {
+    a.list_cap = (uint32_t)(list_entries(d_total) / ((size_t)tiles * kWaves));
+    a.list_last = (uint32_t)(list_entries(d_total) - 1);
+    if (a.list_cap < 1) a.list = nullptr;
+  }
   Launcher ln{static_cast<hipStream_t>(stream),
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
   ln.begin();
-  // upper bound of the tile count for this tiling; surplus workgroups exit at once
-  const uint32_t tiles = max_tiles_of(d_total, num_segments, a.tile_chunks);
   ln.run("seg_setup", k_seg_setup, dim3(1), dim3(kBlock), a, (int)mode);
   if (mode == 1) {
     launch_gaussiank_seg(ln, a, tiles);

@@ -114,7 +114,7 @@ __device__ inline void list_chunk(const Args& a, int64_t tbase, const float (&v)
     const uint32_t i0 = (uint32_t)(tbase + (int64_t)(j * kBlock + (int)threadIdx.x) * 4);
     list_append_run(a, i0, x, in, lc, &off[j], &cnt[j]);
   }
-  list_record_runs(a, tbase, off, cnt);
+  list_record_runs(a, (uint32_t)(tbase / kRun), off, cnt);
 }
 
 template <bool FULL, bool HIST>

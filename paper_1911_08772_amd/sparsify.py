@@ -189,8 +189,8 @@ def sparsify_topk(d, k, grad, residual, acc, out_idx, out_val, cap, result, work
 def sparsify_segmented(num_segments, d_total, seg_off, seg_k, mode, grad, residual, acc, out_idx,
                        out_val, out_off, out_cap, results, workspace, workspace_nbytes,
                        tail_div=2.0, ddof=1, trace=None, stream=None, check=True,
-                       tile_chunks=0, error_norms=False) -> int:
-    o = _opts(tail_div, ddof, trace, tile_chunks, error_norms)
+                       tile_chunks=0, error_norms=False, short_list=0) -> int:
+    o = _opts(tail_div, ddof, trace, tile_chunks, error_norms, short_list=short_list)
     rc = lib.sparsify_segmented(num_segments, d_total, _ptr(seg_off), _ptr(seg_k), mode,
                                 _ptr(grad), _ptr(residual), _ptr(acc), _ptr(out_idx),
                                 _ptr(out_val), _ptr(out_off), out_cap, _ptr(results),

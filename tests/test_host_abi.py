@@ -42,13 +42,16 @@ def test_workspace_bytes():
     assert 0 < small < big < 4 * 1024 * 1024
     assert S.workspace_bytes_min(25_557_032, 54) > S.workspace_bytes_min(25_557_032, 1)
     assert small % 256 == 0 and big % 256 == 0
-    # the size to allocate adds Top_k's short lists for flat vectors of 6 M elements and more:
-    # 0.1 entries of 8 bytes per element and the per-run records (8 bytes per 256 elements)
-    for d, L in ((1000, 1), (5_999_999, 1), (25_557_032, 54)):
+    # the size to allocate adds the short lists for vectors of 6 M elements and more in up to
+    # 1024 segments: 0.1 entries of 8 bytes per element and the per-run records (8 bytes per 256
+    # elements, plus those of every segment's ragged first and last tile)
+    for d, L in ((1000, 1), (5_999_999, 1), (5_999_999, 54), (25_557_032, 1025)):
         assert S.workspace_bytes(d, L) == S.workspace_bytes_min(d, L)
     for d in (6_000_000, 25_557_032, 66_034_000, 536_870_912):
-        extra = S.workspace_bytes(d, 1) - S.workspace_bytes_min(d, 1)
-        assert 0.8 * d < extra < 0.9 * d + (3 << 20) and S.workspace_bytes(d, 1) % 256 == 0
+        for L in (1, 54, 1024):
+            extra = S.workspace_bytes(d, L) - S.workspace_bytes_min(d, L)
+            assert 0.8 * d < extra < 0.9 * d + (3 << 20) + 8 * 16 * 40 * (2 * L + 1), (d, L, extra)
+            assert S.workspace_bytes(d, L) % 256 == 0
 
 
 BASE = 0x7000_0000_0000  # fake, 256-byte aligned "device" addresses; never dereferenced
