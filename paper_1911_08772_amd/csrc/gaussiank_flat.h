@@ -7,6 +7,10 @@
 //
 // The group tables hold kFusedMaxTiles tiles (kBigMaxTiles for long vectors); the host chooses
 // the tile length accordingly and refuses a forced tile length that would need more.
+//
+// From 6 M elements the count kernel also writes the residual and lists the entries above
+// thres0, and the compact kernel writes the pairs from those lists when the walk ended at
+// thres0 or above (gaussiank_list.h): two passes over the vector instead of three.
 #pragma once
 #include "common.h"
 #include "gaussiank.h"

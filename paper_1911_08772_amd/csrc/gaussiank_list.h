@@ -1,5 +1,6 @@
-// Gaussian_k, flat vectors, with short lists (from 6 M elements, where the workspace has room
-// for them).  The count kernel knows thres0 when it streams acc, and in every walk of Alg. 1
+// Gaussian_k with short lists (vectors of 6 M elements and more, where the workspace has room
+// for them; flat calls: gaussiank_flat.h, layer-wise calls, per segment: gaussiank_seg.h).
+// The count kernel knows thres0 when it streams acc, and in every walk of Alg. 1
 // steps 5-13 that ends at thres0 or above it (1, 1.125, 1.5, 2.25 or 3.375 times thres0: what
 // error feedback produces, since the accumulated vector has lost its tail) the survivors are
 // among the entries above thres0, about k of them.  So the count kernel also lists those
