@@ -55,6 +55,7 @@ struct SegCtrl {
   uint32_t topk_take;
   uint32_t tau_key;         // short-list form (topk_list.h): entries with a larger key are listed
   uint32_t list_mode;       //   1 once the kernel after the accumulate kernel found the lists usable
+                            //   (layer-wise Gaussian_k: 1 when a stretch of this segment's lists ran out)
 };
 
 struct Args {

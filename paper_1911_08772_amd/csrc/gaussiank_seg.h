@@ -8,9 +8,9 @@
 // With short lists (gaussiank_list.h; vectors of 6 M elements and more, where the workspace has
 // room): the count kernel also writes the residual and lists each tile's entries above its
 // segment's thres0, and the tiles of a segment whose walk ended at thres0 or above take their
-// pairs from the lists.  Segments decide for themselves; a stretch of the list buffer that ran
-// out anywhere leaves all of them with the streaming compaction.  A tile's runs are numbered
-// (tile * tile_chunks + chunk) * 16 + run.
+// pairs from the lists.  Segments decide for themselves (a stretch of the list buffer that ran
+// out leaves its own segment with the streaming compaction, no other).  A tile's runs are
+// numbered (tile * tile_chunks + chunk) * 16 + run.
 #pragma once
 #include "common.h"
 #include "gaussiank.h"
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_seg(const Args a) {
       if (t.full) count_list_chunk<true, false>(a, t, run0, thr, cnt, lc);
       else count_list_chunk<false, false>(a, t, run0, thr, cnt, lc);
     }
-    if (lc.over && lane_id() == 0) atomicOr(&a.list_stats[kListStatCopies + tile % kListStatCopies], 1u);
+    if (lc.over && lane_id() == 0) atomicOr(&c.list_mode, 1u);  // this segment's lists are incomplete
   } else {
     for (uint32_t u = 0; u < sp_.nchunks; ++u) {
       const Tile t = chunk_of(sp_, u);
@@ -184,7 +184,6 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_seg(const Args a) {
   __shared__ uint32_t lds_pre[kNumThres];
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
-  __shared__ uint32_t lds_lists[2];
   const uint32_t tile = blockIdx.x;
   Span sp_;
   if (!locate_span<true>(a, tile, &sp_)) return;
@@ -194,6 +193,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_seg(const Args a) {
   const uint32_t r0 = tile * a.tile_chunks * kRunsPerChunk, r1 = r0 + sp_.nchunks * kRunsPerChunk;
   uint2 first_rec = make_uint2(0u, 0u);
   if (a.list) first_rec = gk_list_first_records(a, r0, r1);
+  const uint32_t list_over = c.list_mode;
   double t64[kNumThres];
 #pragma unroll
   for (int p = 0; p < kNumThres; ++p) t64[p] = c.t64[p];
@@ -206,13 +206,9 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_seg(const Args a) {
   const bool overflow = (int64_t)tot[w.pos] > c.cap;
   const double tf = t64[w.pos];
   const float thr = (float)tf;
-  // With lists: they hold the segment's survivors when no stretch ran out (anywhere), the
-  // segment's thres0 is positive and its walk ended at thres0 or above it.
-  bool listed = false;
-  if (a.list) {
-    list_totals(a, lds_lists);  // barrier
-    listed = lds_lists[1] == 0 && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
-  }
+  // With lists: they hold the segment's survivors when none of its stretches ran out, its
+  // thres0 is positive and its walk ended at thres0 or above it.
+  const bool listed = a.list && list_over == 0 && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
   if (tile == c.tile0 && threadIdx.x == 0) {
     uint32_t flags = flags0;
     if (!w.in_band) flags |= SPARSIFY_F_EXHAUSTED;

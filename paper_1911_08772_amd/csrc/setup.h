@@ -69,7 +69,6 @@ __device__ inline int64_t block_exclusive_max(int64_t v, int64_t lowest, int64_t
 __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
   __shared__ uint32_t lds_scan[kWaves + 1];
   __shared__ int64_t lds_max[kWaves];
-  if (a.list && threadIdx.x < 64) a.list_stats[threadIdx.x] = 0;  // the lists' length and overflow words
   uint32_t carry = 0;    // tiles numbered so far (block-uniform, saturating)
   uint32_t gcarry = 0;   // groups numbered so far
   int64_t off_max = 0;   // largest offset among the segments of earlier rounds
@@ -124,6 +123,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
       c.rank_ties = 0;
       c.select_none = 0;
       c.t_final = 0.0f;
+      c.list_mode = 0;  // layer-wise Gaussian_k with lists: set when one of the segment's stretches ran out
       sparsify_result& r = a.result[s];
       clear_result(r);
       if (bad) {
