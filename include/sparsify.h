@@ -58,7 +58,8 @@ enum {
   SPARSIFY_F_SHORTLIST_MISS = 32u /* the lists were built but held fewer than k entries (Top_k),
                                      ran out of room, or do not hold the survivors (Gaussian_k: the
                                      walk ended below thres0, or thres0 is not positive): the
-                                     passes over acc ran after all */
+                                     passes over acc ran after all (Gaussian_k with lists that ran
+                                     out of room: over the tiles, or the segment, concerned) */
 };
 
 /* Written on the stream; valid once the stream has been synchronised. */

@@ -174,6 +174,7 @@ template <int GT, bool STREAM = false>  // tiles per group; non-temporal reads o
 __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
   __shared__ double lds_m[2 * kWaves];
   __shared__ uint32_t lds[kWaves * kNumThres];
+  __shared__ uint32_t lds_over[kWaves];
   // The tiles are visited from the last to the first: the end of acc is what the accumulate
   // kernel wrote most recently, so it is the part most likely still to sit in the last-level cache.
   const uint32_t tile = gridDim.x - 1u - blockIdx.x;
@@ -249,6 +250,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
   uint32_t cnt[kNumThres];
 #pragma unroll
   for (int p = 0; p < kNumThres; ++p) cnt[p] = 0;
+  bool over = true;  // whether this tile's lists are incomplete (no lists at all: as good as that)
   if (a.list && can_skip) {
     // with lists (gaussiank_list.h): the entries above thres0, and the residual as if nothing
     // were selected; each wave has a stretch of the list buffer for this tile
@@ -263,9 +265,8 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
       if (t.full) count_list_chunk<true, STREAM>(a, t, run0, thr, cnt, lc);
       else count_list_chunk<false, STREAM>(a, t, run0, thr, cnt, lc);
     }
-    if (lc.over && lane_id() == 0) atomicOr(&a.list_stats[kListStatCopies + tile % kListStatCopies], 1u);
+    over = lc.over;
   } else {
-    if (a.list && tile == 0 && threadIdx.x == 0) atomicOr(&a.list_stats[kListStatCopies], 1u);  // no lists
     for (uint32_t u = 0; u < sp_.nchunks; ++u) {
       const Tile t = chunk_of(sp_, u);
       if (t.full) count_chunk<true>(a, t, thr, can_skip, cnt);
@@ -275,6 +276,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
   if (lane_id() == 0) {
 #pragma unroll
     for (int p = 0; p < kNumThres; ++p) lds[wave_id() * kNumThres + p] = cnt[p];
+    lds_over[wave_id()] = over ? 1u : 0u;
   }
   __syncthreads();
   if (threadIdx.x < kNumThres) {
@@ -283,6 +285,15 @@ __global__ __launch_bounds__(kBlock) void k_gk_count_fused(const Args a) {
     for (int w = 0; w < kWaves; ++w) s += lds[w * kNumThres + threadIdx.x];
     a.tile_counts[(size_t)threadIdx.x * a.max_tiles + tile] = s;  // [threshold][tile]
     if (s) atomicAdd(&a.group_counts[(tile / GT) * kNumThres + threadIdx.x], s);
+  }
+  if (a.list && threadIdx.x == 0) {
+    // the compact kernel streams a tile whose lists are incomplete; the call's record says
+    // whether there was one
+    uint32_t any = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) any |= lds_over[w];
+    a.tile_base[tile] = any;
+    if (any) atomicOr(&a.list_stats[kListStatCopies + tile % kListStatCopies], 1u);
   }
 }
 
@@ -311,10 +322,11 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   // with lists: what the end of this kernel reads first is fetched before the tables (the lists'
   // statistics words, the records of the runs of this wave's first tile), so that those trips to
   // memory overlap the prologue
-  uint32_t list_word = 0;
+  uint32_t list_word = 0, over_mask = 0;  // bit j: the lists of tile0 + j are incomplete
   uint2 first_rec = make_uint2(0u, 0u);
   if (a.list) {
     list_word = a.list_stats[lane_id()];
+    for (uint32_t j = 0; j < tile1 - tile0; ++j) over_mask |= (a.tile_base[tile0 + j] != 0 ? 1u : 0u) << j;
     const uint32_t t = tile0 + wave_id();
     uint32_t r0, r1;
     tile_runs(a, t < tile1 ? t : tile1 - 1u, &r0, &r1);
@@ -384,8 +396,10 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
   }
   const double tf = t64[w.pos];
   const float thr = (float)tf;
-  // With lists (gaussiank_list.h): they hold every survivor when no stretch ran out and the walk
-  // ended at thres0 or above it.
+  // With lists (gaussiank_list.h): a tile's lists hold its survivors when none of its stretches
+  // ran out, thres0 is positive and the walk ended at thres0 or above it; a tile whose lists
+  // are incomplete is streamed.  The record says "from the lists" when every tile's were.
+  const bool lists_ok = a.list && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
   bool listed = false;
   if (a.list) {
     if (wave_id() == 0) {  // (list_totals of lists.h on the word fetched above)
@@ -393,7 +407,7 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
       if (lane_id() == 0) lds_lists[1] = over != 0 ? 1u : 0u;
     }
     __syncthreads();
-    listed = lds_lists[1] == 0 && w.pos >= kGkListPos && t64[kGkListPos] > 0.0;
+    listed = lists_ok && lds_lists[1] == 0;
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t flags = flags0;
@@ -425,20 +439,27 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
       if ((uint32_t)(j + lane_id()) < tile - g0) x += lds_t[w.pos * GT + j + lane_id()];
     return wave_sum(x);
   };
-  if (listed) {  // the residual is in place (the count kernel wrote it); a wave writes a tile's pairs
-    if (!overflow)
-      for (uint32_t tile = tile0 + wave_id(); tile < tile1; tile += kWaves) {
-        uint32_t r0, r1;
-        tile_runs(a, tile, &r0, &r1);
-        const uint2 rec = tile == tile0 + wave_id() ? first_rec : gk_list_first_records(a, r0, r1);
-        gk_list_compact_tile(a, r0, r1, thr, (int64_t)(groups_before + before_in_group(tile)), a.flat_cap, rec);
-      }
-    return;
+  if (lists_ok && !overflow) {
+    // the residual is in place (the count kernel wrote it); a wave writes a tile's pairs
+    for (uint32_t tile = tile0 + wave_id(); tile < tile1; tile += kWaves) {
+      if ((over_mask >> (tile - tile0)) & 1u) continue;
+      uint32_t r0, r1;
+      tile_runs(a, tile, &r0, &r1);
+      const uint2 rec = tile == tile0 + wave_id() ? first_rec : gk_list_first_records(a, r0, r1);
+      gk_list_compact_tile(a, r0, r1, thr, (int64_t)(groups_before + before_in_group(tile)), a.flat_cap, rec);
+    }
+    if (over_mask == 0) return;
+    __syncthreads();
+  } else if (lists_ok) {
+    return;  // more survivors than cap: nothing is selected, and the residual is acc already
   }
+  // the streaming compaction: every tile without lists, or the tiles whose lists are incomplete
   for (uint32_t tile = tile0; tile < tile1; ++tile) {
+    if (lists_ok && !((over_mask >> (tile - tile0)) & 1u)) continue;
     Span sp_;
     if (!locate_span<false>(a, tile, &sp_)) return;
-    if (tile != tile0) {  // (the first tile's slot is there already)
+    if (tile != tile0 || lists_ok) {  // (without lists the first tile's slot is there already)
+      __syncthreads();
       if (wave_id() == 0) {
         const uint32_t x = before_in_group(tile);
         if (lane_id() == 0) lds_base[1] = groups_before + x;
@@ -454,7 +475,6 @@ __global__ __launch_bounds__(kBlock) void k_gk_compact_fused(const Args a) {
       else run = compact_chunk<false, NORMS, STREAM>(a, t, thr, overflow, out0, run, lds, norms);
     }
     if (NORMS) store_norm_partial(a, norms, tile, lds_n);
-    if (tile + 1 < tile1) __syncthreads();  // lds_base[1] and lds_n are reused by the next tile
   }
 }
 

@@ -9,9 +9,11 @@
 // entries of the residual instead of streaming acc and the residual once more: 12 + 8 bytes per
 // element instead of 12 + 4 + 8 (12 + 4 instead of 12 + 4 + 4 in place).
 //
-// A walk that ends below thres0, a thres0 that is not positive (the ten thresholds are then not
-// in ascending order) or a list that ran out of room leave the lists unused: the compact kernel
-// takes its streaming body, which rewrites the whole residual.  Same launches, same results.
+// A walk that ends below thres0 or a thres0 that is not positive (the ten thresholds are then
+// not in ascending order) leave the lists unused: the compact kernel takes its streaming body,
+// which rewrites the whole residual.  A tile whose lists ran out of room (a flag per tile) is
+// streamed in the same way, alone; in a layer-wise call its whole segment is.  Same launches,
+// same results.
 #pragma once
 #include "common.h"
 #include "gaussiank.h"
