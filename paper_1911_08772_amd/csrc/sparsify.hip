@@ -525,8 +525,9 @@ int flat_call(int selector, int64_t d, int64_t k, const float* grad, float* resi
   a.flat_cap = cap;
   // the short-list forms: no norms asked for, k small enough for the lists' share of the
   // workspace, where the workspace has room at all (prepare)
-  if (a.norms || (opts && opts->short_list < 0) || 2.0 * kListAim * (double)k > kListShare * (double)d)
-    a.list = nullptr;
+  // (Top_k's and DGC_k's lists are built to hold about four times k entries, Gaussian_k's about k)
+  const double list_need = selector == kSelGaussian ? 2.0 * (double)k : 2.0 * kListAim * (double)k;
+  if (a.norms || (opts && opts->short_list < 0) || list_need > kListShare * (double)d) a.list = nullptr;
   if (!(opts && opts->tile_chunks != 0))
     a.tile_chunks = tile_chunks_of(d, selector == kSelGaussian || (selector == kSelTopk && !a.inplace));
   const uint32_t tiles = seg_ntiles(0, d, a.tile_chunks);

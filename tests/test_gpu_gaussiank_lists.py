@@ -1,6 +1,6 @@
 """GPU parity of flat Gaussian_k (Algorithm 1) where the count kernel also lists the entries above
 thres0 and writes the residual, so that the compact kernel can write the pairs from the lists
-(vectors of 6 M elements and more, k up to d/80).  Whether a call ends up using its lists depends
+(vectors of 6 M elements and more, k up to d/20).  Whether a call ends up using its lists depends
 on the data (a walk that ends below thres0, a thres0 that is not positive and a list that runs
 out of room all leave them unused); the results must not, so every case is compared with the CPU
 oracle bit for bit, and the way the call took (two informational flag bits) is checked against
@@ -116,10 +116,13 @@ def test_the_lists_can_be_declined():
     g = synth.normal(d, 46, 0, 0.01)
     eps = synth.normal(d, 47, 0, 0.003)
     gpu = FlatGpu(d, cap=d // 20)
-    for kk, kw in ((k, {"short_list": -1}), (k, {"error_norms": True}), (d // 79, {})):
+    for kk, kw in ((k, {"short_list": -1}), (k, {"error_norms": True}), (d // 19, {})):
         gpu.set_residual(eps)
         check_flat("gaussiank", gpu, g, eps, kk, what=f"{kw} k={kk}", **kw)
         assert way(gpu) == 0, (kk, kw)
+    gpu.set_residual(eps)
+    check_flat("gaussiank", gpu, g, eps, d // 21, what="k = d/21")   # up to a twentieth of the vector
+    assert way(gpu) in (S.F_SHORTLIST, S.F_SHORTLIST_MISS)
     for kw in ({"tile_chunks": 1}, {"tile_chunks": 2}, {"tile_chunks": 5}, {"tail_div": 1.0}, {"ddof": 0}):
         gpu.set_residual(eps)
         check_flat("gaussiank", gpu, g, eps, k, what=f"{kw}", **kw)
