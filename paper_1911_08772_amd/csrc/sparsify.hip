@@ -288,6 +288,9 @@ constexpr uint32_t kListCompactTiles = 4, kBigListCompactTiles = 8;
 static_assert(kGroupTiles % kListCompactTiles == 0 && kBigGroupTiles % kBigListCompactTiles == 0, "a workgroup's tiles share a group");
 constexpr int64_t kStreamAccFrom = 40'000'000, kStreamAccBelow = 80'000'000;
 bool stream_acc(const Args& a) { return a.d_total >= kStreamAccFrom && a.d_total < kStreamAccBelow; }
+// Gaussian_k with lists reads acc once (the count kernel) and the hints pay from a shorter
+// vector on: per call 4.5 % faster at 33.5 M elements, no difference at 30 M and below.
+constexpr int64_t kStreamAccListFrom = 32'000'000;
 
 // Layer-wise Gaussian_k: setup + three launches (gaussiank_seg.h).
 void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
@@ -340,12 +343,13 @@ void launch_gaussiank_flat(Launcher& ln, Args& a, uint32_t tiles) {
     return;
   }
   {
-    if (stream_acc(a) && !a.inplace) ln.run("accum_moments", k_accum_moments_fused<true>, dim3(want + 1), blk, a);
+    const bool nt_store = (stream_acc(a) || (a.list && a.d_total >= kStreamAccListFrom && a.d_total < kStreamAccBelow)) && !a.inplace;
+    if (nt_store) ln.run("accum_moments", k_accum_moments_fused<true>, dim3(want + 1), blk, a);
     else ln.run("accum_moments", k_accum_moments_fused<false>, dim3(want + 1), blk, a);
-    // with lists the count kernel is acc's last reader: from 40 M elements (up to the 123 M this
+    // with lists the count kernel is acc's last reader: from 32 M elements (up to the 123 M this
     // branch serves) it reads acc with the non-temporal hint (per call: 11 % faster at 66 M
-    // elements, 2 % at 100 M, no difference at 85 M; slower beyond 123 M; nothing below 40 M)
-    if (a.list && a.d_total >= kStreamAccFrom) ln.run("gk_count", k_gk_count_fused<kGroupTiles, true>, dim3(tiles), blk, a);
+    // elements, 2 % at 100 M, no difference at 85 M; slower beyond 123 M)
+    if (a.list && a.d_total >= kStreamAccListFrom) ln.run("gk_count", k_gk_count_fused<kGroupTiles, true>, dim3(tiles), blk, a);
     else ln.run("gk_count", k_gk_count_fused<kGroupTiles>, dim3(tiles), blk, a);
     if (a.norms) {
       if (stream_acc(a)) ln.run("gk_compact", k_gk_compact_fused<true, kGroupTiles, kMaxGroups, true>, cgrid, blk, a);
