@@ -125,3 +125,61 @@ def test_more_segments_than_the_run_table_is_sized_for():
     gpu.set_residual(zero)
     check_segmented(1, gpu, g, zero, what="1025 segments")
     assert set(ways(gpu)) == {0}
+
+
+def test_a_layer_wise_call_with_lists_can_be_captured_in_a_hip_graph():
+    """Every segment's way is decided on the device, so a captured call replays with or without
+    the lists as each replay's data asks."""
+    from gpu_harness import same_bits
+    from oracle import oracle as O
+    sizes = [3_000_000, 2_000_001, 1_499_999]
+    seg_off, seg_k, caps = layout(sizes)
+    d, L = int(seg_off[-1]), 3
+    out_off = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+    ocap = int(out_off[-1])
+    b = S.Buffers.allocate(d, ocap, L)
+    grad = torch.zeros(d, device="cuda:0")
+    d_off, d_k, d_oo = (torch.from_numpy(x).to("cuda:0") for x in (seg_off, seg_k, out_off))
+
+    def call():
+        S.sparsify_segmented(L, d, d_off, d_k, 1, grad, b.residual, b.acc, b.out_idx, b.out_val, d_oo,
+                             ocap, b.result, b.workspace, b.workspace_nbytes)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # warm-up outside capture (first-call queries of the runtime)
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    b.residual.zero_()
+    eps = np.zeros(d, np.float32)
+    rng = np.random.default_rng(8)
+    for step in range(4):
+        g = synth.normal(d, 83, step, 0.01)
+        if step == 2:   # the middle segment uniform: its walk ends below thres0, it alone streams
+            g[seg_off[1]:seg_off[2]] = rng.uniform(-1, 1, sizes[1]).astype(np.float32)
+            eps = np.zeros(d, np.float32)
+            b.residual.zero_()
+        grad.copy_(torch.from_numpy(g))
+        b.out_idx.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        acc_o = O.accumulate(g, eps)
+        idx_o, val_o, eps, res_o = O.segmented(acc_o, seg_off, seg_k, 1, out_off)
+        res = S.decode_results(b.result)
+        got_idx, got_val = b.out_idx.cpu().numpy(), b.out_val.cpu().numpy()
+        for l in range(L):
+            n, o0 = res_o[l].nnz, int(out_off[l])
+            assert int(res[l]["nnz"]) == n and int(res[l]["rounds"]) == res_o[l].rounds, (step, l)
+            assert np.array_equal(got_idx[o0:o0 + n].view(np.uint32), idx_o[o0:o0 + n]), (step, l)
+            assert same_bits(got_val[o0:o0 + n], val_o[o0:o0 + n]), (step, l)
+        w = [int(r["flags"]) & S.F_WAY for r in res]
+        if step == 2:
+            assert w == [S.F_SHORTLIST, S.F_SHORTLIST_MISS, S.F_SHORTLIST], w
+        else:
+            assert all(x in (S.F_SHORTLIST, S.F_SHORTLIST_MISS) for x in w) and S.F_SHORTLIST in w, w
+        assert same_bits(b.residual.cpu().numpy(), eps), step
+        assert same_bits(b.acc.cpu().numpy(), acc_o), step
+        _ = (b.acc * 2).sum().item()   # unrelated eager work between replays
