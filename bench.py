@@ -386,9 +386,9 @@ def main() -> int:
             extras[name] = side_workload(S, torch, synth, name, K, W)
 
     out = {
-        "metric": ("Gaussian-k sparsify GB/s (algorithmic bytes: 24 B per element) at d=25.6M, rho=0.001; exact Top-k beside it"
+        "metric": (f"Gaussian-k sparsify GB/s (algorithmic bytes: {gk_alg_bpe} B per element) at d=25.6M, rho=0.001; exact Top-k beside it"
                    if args.workload == "cfg3_resnet50" else
-                   f"Gaussian-k sparsify GB/s (algorithmic bytes: 24 B per element) on {wl.name}; exact Top-k beside it"),
+                   f"Gaussian-k sparsify GB/s (algorithmic bytes: {gk_alg_bpe} B per element) on {wl.name}; exact Top-k beside it"),
         "value": round(gk_gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(gk_ms, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
