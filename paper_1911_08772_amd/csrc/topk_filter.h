@@ -144,14 +144,20 @@ __global__ __launch_bounds__(kBlock) void k_topk_filter(const Args a) {
   Span sp_;
   if (!locate_span<false>(a, tile, &sp_)) return;
   SegCtrl& c = a.ctrl[0];
+  bool usable = false;
+  if (a.list) {  // short-list form (topk_list.h): do the lists serve?
+    usable = lists_usable(a, lds_lists);
+    if (tile == 0 && threadIdx.x == 0) c.list_mode = usable ? 1u : 0u;
+    // one wave per tile reads the lists: the workgroups beyond a quarter of the grid have nothing
+    // to do (but the first tile's, which publishes the digit)
+    if (usable && tile != 0 && blockIdx.x * kWaves >= gridDim.x) return;
+  }
   const Digit dg = choose_digit(pass_hist(a, 0), 0, 0u, (uint32_t)a.flat_k, lds_sel);  // barriers
   if (tile == 0 && threadIdx.x == 0) {
     c.sel_prefix[0] = dg.prefix;
     c.sel_krem[0] = dg.k_rem;
   }
-  if (a.list) {  // short-list form (topk_list.h): if the lists serve, the second digit's histogram from them
-    const bool usable = lists_usable(a, lds_lists);
-    if (tile == 0 && threadIdx.x == 0) c.list_mode = usable ? 1u : 0u;
+  if (a.list) {  // if the lists serve, the second digit's histogram from them
     if (usable) {
       list_digit_pass(a, 1, dg.prefix, h[wave_id()]);
       __syncthreads();
