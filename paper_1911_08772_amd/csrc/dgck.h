@@ -227,20 +227,15 @@ __global__ __launch_bounds__(kBlock) void k_dgck_filter(const Args a) {
   Span sp_;
   if (!locate_span<false>(a, tile, &sp_)) return;
   SegCtrl& c = a.ctrl[0];
-  const Digit dg = choose_digit(pass_hist(a, 3), 3, c.sel_prefix[2], c.sel_krem[2], lds_sel);
-  const uint32_t Ts = dg.prefix;  // the sample's threshold: a whole 31-bit key
-  if (tile == 0 && threadIdx.x == 0) {
-    c.sel_prefix[3] = Ts;
-    c.sel_krem[3] = dg.k_rem;
-  }
   if (a.list) {
-    // the accumulate pass listed the keys that reach Ts.  If no stretch ran out the lists are
-    // the kept entries: more than k of them, a second selection follows (way 1: the first
-    // digit's histogram from the lists); otherwise all of them are the result (way 2).
+    // the accumulate pass listed the keys that reach Ts (and published Ts).  If no stretch ran
+    // out the lists are the kept entries: more than k of them, a second selection follows (way
+    // 1: the first digit's histogram from the lists, one wave per tile); otherwise all of them
+    // are the result (way 2).
     list_totals(a, lds_lists);
     const uint32_t way = lds_lists[1] != 0 ? 0u : (int64_t)lds_lists[0] > a.flat_k ? 1u : 2u;
     if (tile == 0 && threadIdx.x == 0) c.list_mode = way;
-    if (way == 1) {
+    if (way == 1 && blockIdx.x * kWaves < gridDim.x) {
       list_digit_pass(a, 0, 0u, h[wave_id()]);
       __syncthreads();
       uint32_t v = 0;
@@ -249,6 +244,12 @@ __global__ __launch_bounds__(kBlock) void k_dgck_filter(const Args a) {
       if (v) atomicAdd(&pass_hist(a, 4)[(blockIdx.x % kTopkCopies) * 256 + threadIdx.x], v);
     }
     if (way != 0) return;
+  }
+  const Digit dg = choose_digit(pass_hist(a, 3), 3, c.sel_prefix[2], c.sel_krem[2], lds_sel);
+  const uint32_t Ts = dg.prefix;  // the sample's threshold: a whole 31-bit key
+  if (tile == 0 && threadIdx.x == 0) {
+    c.sel_prefix[3] = Ts;
+    c.sel_krem[3] = dg.k_rem;
   }
   uint32_t* list = tile_candidates(a, tile);
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {
