@@ -131,6 +131,8 @@ __global__ __launch_bounds__(kBlock) void k_dgck_lists_hist(const Args a, int st
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   SegCtrl& c = a.ctrl[0];
+  // (the kept keys are all taken, from the lists: there is no k-th key to find among them)
+  if ((stage & 4) && a.list && c.list_mode == 2) return;
   const int pass = stage & 3;
   const uint32_t k0 = (uint32_t)((stage & 4) ? a.flat_k : a.sample_k);
   const uint32_t prefix_in = pass == 1 ? 0u : c.sel_prefix[stage - 2];
