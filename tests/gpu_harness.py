@@ -78,7 +78,25 @@ def assert_pairs_match(got, idx_o, val_o, what=""):
     assert np.all(got["tail_idx"] == -1), what  # nothing written beyond nnz
 
 
-def assert_gaussiank_result(res, ro: O.Result, what=""):
+def assert_same_threshold(res, ro: O.Result, acc=None, what=""):
+    """The fp32 threshold the final mask compared against.  GPU and oracle sum the moments in
+    fp64 in different orders, so their fp64 thresholds differ in the last bits (<= 1e-11
+    relative, far inside the 1e-6 the benchmark spec allows) and can, once in thousands of vectors,
+    round to neighbouring fp32 values.  That is accepted when no entry of `acc` lies between the
+    two (both thresholds then select the same entries, which the callers go on to compare bit
+    for bit); otherwise the bits must be equal."""
+    g32, o32 = np.float32(res["thres_f32"]), np.float32(ro.thres_f32)
+    if g32.view(np.uint32) == o32.view(np.uint32):
+        return
+    assert acc is not None and np.isfinite(g32) and np.isfinite(o32), (what, g32, o32)
+    assert abs(float(res["thres"]) - ro.thres) <= 1e-11 * abs(ro.thres), (what, res["thres"], ro.thres)
+    lo, hi = min(g32, o32), max(g32, o32)
+    assert np.nextafter(lo, np.float32(np.inf)) == hi, (what, g32, o32)   # neighbours
+    m = np.abs(acc)
+    assert not np.any((m > lo) & (m <= hi)), (what, g32, o32)
+
+
+def assert_gaussiank_result(res, ro: O.Result, what="", acc=None):
     assert int(res["rounds"]) == ro.rounds, (what, res, ro)
     assert list(res["count"]) == list(ro.count), (what, res, ro)
     assert int(res["flags"]) & ~S.F_WAY == ro.flags, (what, res, ro)  # (the way taken is no result)
@@ -93,8 +111,7 @@ def assert_gaussiank_result(res, ro: O.Result, what=""):
             assert abs(g - o) <= 1e-9 * max(abs(o), ro.std, 1e-300), (what, name, g, o)
         else:
             assert g == o or abs(g - o) <= THRES_RTOL * abs(o), (what, name, g, o)
-    g32, o32 = np.float32(res["thres_f32"]), np.float32(ro.thres_f32)
-    assert g32.view(np.uint32) == o32.view(np.uint32), (what, g32, o32)
+    assert_same_threshold(res, ro, acc, what)
     assert int(res["topk_key"]) == 0 and int(res["topk_ties_taken"]) == 0
 
 
@@ -123,7 +140,7 @@ def check_flat(selector, gpu: FlatGpu, g, eps_in, k, what="", **kw):
         idx_o, val_o, eps_o, ro = O.gaussiank(acc_o, k, cap=gpu.cap,
                                               tail_div=kw.get("tail_div", 2.0),
                                               ddof=kw.get("ddof", 1))
-        assert_gaussiank_result(got["res"], ro, what)
+        assert_gaussiank_result(got["res"], ro, what, acc=acc_o)
     elif selector == "dgck":
         idx_o, val_o, eps_o, ro = O.dgck(acc_o, k, kw.get("sample_stride", 0) or 100,
                                          kw.get("sample_seed", 0))
@@ -185,7 +202,7 @@ def check_segmented(mode: int, gpu: SegGpu, g, eps_in, what="", **kw):
         w = f"{what} segment {l}"
         res, ro = got["res"][l], res_o[l]
         if mode == 1:
-            assert_gaussiank_result(res, ro, w)
+            assert_gaussiank_result(res, ro, w, acc=acc_o[int(gpu.seg_off[l]):int(gpu.seg_off[l + 1])])
         else:
             assert int(res["nnz"]) == ro.nnz and int(res["flags"]) == ro.flags, (w, res, ro)
             assert int(res["topk_key"]) == ro.topk_key, (w, res, ro)

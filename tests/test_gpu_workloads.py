@@ -58,7 +58,7 @@ class Chain:
         th.join()
         idx_o, val_o, _, ro = box["o"]
         if selector == "gaussiank":
-            assert_gaussiank_result(got["res"], ro, what)
+            assert_gaussiank_result(got["res"], ro, what, acc=self.acc_o)
             self.rounds.append(ro.rounds)
         elif selector == "dgck":
             assert_dgck_result(got["res"], ro, what)
