@@ -76,6 +76,57 @@ def test_flat_random_cases_where_short_lists_are_built(selector):
     assert S.F_SHORTLIST in ways and ways <= {S.F_SHORTLIST, S.F_SHORTLIST_MISS}, ways
 
 
+def awkward_vector(rng, d):
+    """Bell-shaped, heavy-tailed, tied, sparse, uniform (no tail), two-level, one loud stretch, or
+    far from zero: what makes Algorithm 1's walk end high, low or nowhere."""
+    kind = int(rng.integers(0, 9))
+    if kind < 5:
+        return random_vector(rng, d, kind)
+    if kind == 5:
+        return rng.uniform(-1, 1, d).astype(np.float32)
+    if kind == 6:
+        v = (rng.standard_normal(d) * 1e-6).astype(np.float32)
+        n = int(rng.integers(1, max(2, d // 50)))
+        w = rng.choice(d, n, replace=False)
+        v[w[: n // 3]] = 1.0
+        v[w[n // 3:]] = np.float32(rng.uniform(0.01, 0.2))
+        return v
+    if kind == 7:
+        v = rng.standard_normal(d).astype(np.float32)
+        a = int(rng.integers(0, max(1, d - 300_000)))
+        v[a:a + int(rng.integers(1000, 300_000))] *= np.float32(100)
+        return v
+    return (rng.standard_normal(d) * 0.01 + rng.choice([-5.0, 0.3, 5.0])).astype(np.float32)
+
+
+def test_segmented_gaussiank_random_cases_where_short_lists_are_built():
+    """Layer-wise Gaussian_k on vectors of 6 M elements and more: every segment decides for itself
+    whether its pairs come from its lists; results must not depend on it."""
+    rng = np.random.default_rng(60_000_001)
+    ways = set()
+    for case in range(10):
+        d = int(rng.integers(6_000_000, 8_500_000))
+        L = int(rng.integers(2, 120))
+        sizes = np.maximum(1, (rng.dirichlet(np.ones(L) * 0.3) * d).astype(np.int64))
+        sizes[0] += d - int(sizes.sum())
+        if sizes[0] < 1:
+            continue
+        seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        seg_k = np.array([rng.integers(1, max(2, s // int(rng.choice([10, 100, 1000])) + 1)) for s in sizes], np.int64)
+        seg_k = np.minimum(np.maximum(seg_k, 1), sizes)
+        caps = np.array([max(4 * k, 16) if rng.random() < 0.8 else rng.integers(0, 2 * s + 2)
+                         for s, k in zip(sizes, seg_k)], np.int64)
+        g = np.concatenate([awkward_vector(rng, int(s)) if s > 400_000 else
+                            random_vector(rng, int(s), int(rng.integers(0, 5))) for s in sizes])
+        eps = awkward_vector(rng, d) if rng.random() < 0.4 else np.zeros(d, np.float32)
+        gpu = SegGpu(seg_off, seg_k, caps, inplace=bool(rng.random() < 0.3))
+        gpu.set_residual(eps)
+        check_segmented(1, gpu, g, eps, what=f"case {case}: L={L} d={d}", tile_chunks=int(rng.choice([0, 0, 1, 3])))
+        ways |= {int(r["flags"]) & S.F_WAY for r in S.decode_results(gpu.b.result) if not int(r["flags"]) & S.F_BADSEGMENT}
+        del gpu
+    assert ways == {S.F_SHORTLIST, S.F_SHORTLIST_MISS}, ways   # both ways were exercised
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_segmented_random_cases(mode):
     rng = np.random.default_rng(77 + mode)
