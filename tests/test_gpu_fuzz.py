@@ -52,23 +52,32 @@ def test_flat_random_cases(selector):
         check_flat(selector, gpu, g, eps, k, what=f"case {case}: d={d} k={k} cap={cap} inplace={inplace} {kw}", **kw)
 
 
-@pytest.mark.parametrize("selector", ["topk", "dgck"])
+@pytest.mark.parametrize("selector", ["topk", "dgck", "gaussiank"])
 def test_flat_random_cases_where_short_lists_are_built(selector):
-    """From 6 M elements Top_k and DGC_k list the large entries in the accumulate pass; whether a
-    call ends up using its lists depends on the data, the results must not."""
+    """From 6 M elements Top_k and DGC_k list the large entries in the accumulate pass and
+    Gaussian_k in the count pass; whether a call ends up using its lists depends on the data,
+    the results must not."""
     rng = np.random.default_rng(6_000_000 + len(selector))
     ways = set()
     for case in range(14):
         d = int(rng.integers(6_000_000, 11_000_000))
         k = int(rng.choice([1, rng.integers(2, 200), d // 1000, rng.integers(d // 500, d // 80)]))
-        g = random_vector(rng, d, int(rng.integers(0, 5)))
-        eps = random_vector(rng, d, int(rng.integers(0, 5))) if rng.random() < 0.6 else np.zeros(d, np.float32)
+        if selector == "gaussiank":
+            g = awkward_vector(rng, d)
+            eps = awkward_vector(rng, d) if rng.random() < 0.5 else np.zeros(d, np.float32)
+        else:
+            g = random_vector(rng, d, int(rng.integers(0, 5)))
+            eps = random_vector(rng, d, int(rng.integers(0, 5))) if rng.random() < 0.6 else np.zeros(d, np.float32)
         inplace = bool(rng.random() < 0.4) and selector != "dgck"
         kw = {"tile_chunks": int(rng.choice([0, 0, 2, 5]))}
         if selector == "dgck":
             kw["sample_stride"] = int(rng.choice([0, 10, 37, 100, 1000, 5000]))
             kw["sample_seed"] = int(rng.integers(0, 1 << 62))
-        gpu = FlatGpu(d, cap=k, inplace=inplace)
+        if selector == "gaussiank":
+            kw["tail_div"] = float(rng.choice([2.0, 2.0, 1.0]))
+            kw["ddof"] = int(rng.choice([1, 0]))
+        cap = k if selector != "gaussiank" else int(rng.choice([4 * k, d, max(1, k // 2)]))
+        gpu = FlatGpu(d, cap=cap, inplace=inplace)
         gpu.set_residual(eps)
         check_flat(selector, gpu, g, eps, k, what=f"case {case}: d={d} k={k} inplace={inplace} {kw}", **kw)
         ways.add(int(S.decode_results(gpu.b.result)[0]["flags"]) & S.F_WAY)
