@@ -28,6 +28,8 @@ __host__ __device__ inline int thres_pos(int a, int b) {
   return (int)((0x9620841735ull >> (4 * thres_index(a, b))) & 0xF);
 }
 
+constexpr uint32_t kNoListKey = 0x7FFFFFFFu;  // a listing key that no key exceeds: nothing is listed
+
 // One per segment, lives in the workspace; written by kernels, read by later kernels.
 struct SegCtrl {
   // layout
@@ -55,7 +57,8 @@ struct SegCtrl {
   uint32_t topk_take;
   uint32_t tau_key;         // short-list form (topk_list.h): entries with a larger key are listed
   uint32_t list_mode;       //   1 once the kernel after the accumulate kernel found the lists usable
-                            //   (layer-wise Gaussian_k: 1 when a stretch of this segment's lists ran out)
+                            //   (layer-wise calls: 1 when a stretch of this segment's lists ran out)
+  uint32_t list_count;      // layer-wise Top_k with lists: entries of this segment listed
 };
 
 struct Args {

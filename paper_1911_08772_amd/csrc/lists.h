@@ -98,16 +98,14 @@ __device__ inline uint32_t wave_max(uint32_t v) {
   return v;
 }
 
-// One lane per run of the tile, 64 runs at a time: the lanes fetch their runs' records, then
+// One lane per run of the tile (runs r0 .. r1 - 1), 64 runs at a time: the lanes fetch their runs' records, then
 // their runs' entries four at a time.  No load sits behind a branch (a wave would wait for each
 // before it issues the next): a lane past the end of its run re-reads the run's last entry (an
 // empty run the entry at its offset), kept inside the buffer, and reports it as not valid.
 // fn(entry, valid) is called by the whole wave; the order of the calls is not the index order.
 constexpr int kListBatch = 4;
 template <typename F>
-__device__ inline void for_each_list_entry(const Args& a, uint32_t tile, F fn) {
-  uint32_t r0, r1;
-  tile_runs(a, tile, &r0, &r1);
+__device__ inline void for_each_list_entry_of_runs(const Args& a, uint32_t r0, uint32_t r1, F fn) {
   for (uint32_t rb = r0; rb < r1; rb += 64) {
     const uint32_t r = rb + lane_id();
     const uint2 rec = a.run_table[r < r1 ? r : r1 - 1u];
@@ -127,6 +125,12 @@ __device__ inline void for_each_list_entry(const Args& a, uint32_t tile, F fn) {
         if (i0 + u < nmax) fn(e[u], i0 + u < n);  // wave-uniform condition
     }
   }
+}
+template <typename F>
+__device__ inline void for_each_list_entry(const Args& a, uint32_t tile, F fn) {
+  uint32_t r0, r1;
+  tile_runs(a, tile, &r0, &r1);
+  for_each_list_entry_of_runs(a, r0, r1, fn);
 }
 
 }  // namespace sp

@@ -123,7 +123,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
       c.rank_ties = 0;
       c.select_none = 0;
       c.t_final = 0.0f;
-      c.list_mode = 0;  // layer-wise Gaussian_k with lists: set when one of the segment's stretches ran out
+      c.list_mode = 0;  // layer-wise calls with lists: set when one of the segment's stretches ran out
+      c.list_count = 0;
+      c.tau_key = kNoListKey;  // layer-wise Top_k with lists: until the segment's sample says otherwise
       sparsify_result& r = a.result[s];
       clear_result(r);
       if (bad) {

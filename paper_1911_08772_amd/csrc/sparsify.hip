@@ -112,7 +112,8 @@ uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 
 // others' about k), split evenly among the waves of the kernel that writes them.
 constexpr int64_t kListFrom = 6'000'000;
 constexpr double kListShare = 0.10;
-// (Layer-wise calls: Gaussian_k only, and up to kListMaxSegments segments, which bounds the run table.)
+// (Layer-wise calls: Gaussian_k and Top_k with a separate acc, up to kListMaxSegments segments,
+// which bounds the run table.)
 constexpr int32_t kListMaxSegments = 1024;
 bool list_sized(int64_t d_total, int32_t L) {
   return L <= kListMaxSegments && d_total >= kListFrom;
@@ -432,7 +433,8 @@ void launch_topk_seg(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
   const dim3 pg(tiles);
   if (!a.inplace) {
-    ln.run("topk_accum_hist", k_topk_accum_hist, pg, blk, a);
+    if (a.list) ln.run("topk_accum_hist", k_topk_accum_list_seg, pg, blk, a);
+    else ln.run("topk_accum_hist", k_topk_accum_hist, pg, blk, a);
     ln.run("topk_filter", k_topk_filter_seg, pg, blk, a);
     ln.run("topk_cand2", k_topk_cand_hist_seg, pg, blk, a, 2);
     ln.run("topk_cand3", k_topk_cand_hist_seg, pg, blk, a, 3);
@@ -643,9 +645,9 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   a.out_off = out_off;
   // upper bound of the tile count for this tiling; surplus workgroups exit at once
   const uint32_t tiles = max_tiles_of(d_total, num_segments, a.tile_chunks);
-  // short lists (gaussiank_seg.h): Gaussian_k without the norms, where the workspace has room
-  // (prepare) and the run table holds this tiling's runs
-  if (mode != 1 || a.norms || (opts && opts->short_list < 0) ||
+  // short lists (gaussiank_seg.h; topk_seg.h, with a separate acc): without the norms, where the
+  // workspace has room (prepare) and the run table holds this tiling's runs
+  if ((mode == 0 && a.inplace) || a.norms || (opts && opts->short_list < 0) ||
       (uint64_t)tiles * a.tile_chunks * kRunsPerChunk > (uint64_t)a.run_cap)
     a.list = nullptr;
   if (a.list) {
@@ -661,8 +663,11 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
     launch_gaussiank_seg(ln, a, tiles);
   } else {
     const size_t n = (size_t)kDigits * 256 * (size_t)num_segments * a.hist_copies;
-    ln.run("hist_zero", k_fill_u32, dim3((unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024)),
-           dim3(256), a.hist, n, 0u);
+    const unsigned fill_wgs = (unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024);
+    if (a.list)  // (at most kListMaxSegments segments: n fits 32 bits)
+      ln.run("hist_zero", k_topk_init_seg, dim3((unsigned)num_segments + fill_wgs), dim3(kBlock), a, (uint32_t)n);
+    else
+      ln.run("hist_zero", k_fill_u32, dim3(fill_wgs), dim3(256), a.hist, n, 0u);
     launch_topk_seg(ln, a, tiles);
   }
   if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);

@@ -33,6 +33,8 @@ constexpr int kListAim = 4;                       // the lists should hold about
 // 16-bit key bin (sign dropped: exponent and eight mantissa bits) that holds the sample's r-th
 // largest key, r = the sample's share of kListAim * k entries, at least 16.  `lds_h` holds 256
 // words, `lds_sel` kWaves + 3.
+__device__ inline uint32_t listing_key_from_sample(const uint32_t (&key)[16], int64_t k, int64_t n,
+                                                   int64_t m, uint32_t* lds_h, uint32_t* lds_sel);
 __device__ inline uint32_t sample_listing_key(const Args& a, uint32_t* lds_h, uint32_t* lds_sel) {
   const int64_t stride4 = (a.d_total / 4) / (kListSample / 4);  // >= 1: the host asks for d >= 4 * kListSample
   uint32_t key[16];
@@ -46,9 +48,15 @@ __device__ inline uint32_t sample_listing_key(const Args& a, uint32_t* lds_h, ui
     key[4 * u + 2] = mag_key(g.z + e.z);
     key[4 * u + 3] = mag_key(g.w + e.w);
   }
-  uint64_t want = ((uint64_t)kListAim * (uint64_t)a.flat_k * kListSample + (uint64_t)a.d_total - 1) / (uint64_t)a.d_total;
+  return listing_key_from_sample(key, a.flat_k, a.d_total, kListSample, lds_h, lds_sel);
+}
+
+// The sample holds m of the n entries (keys beyond the sample are zero) and k entries are asked for.
+__device__ inline uint32_t listing_key_from_sample(const uint32_t (&key)[16], int64_t k, int64_t n,
+                                                   int64_t m, uint32_t* lds_h, uint32_t* lds_sel) {
+  uint64_t want = ((uint64_t)kListAim * (uint64_t)k * (uint64_t)m + (uint64_t)n - 1) / (uint64_t)n;
   if (want < 16) want = 16;
-  if (want > kListSample) want = kListSample;
+  if (want > (uint64_t)m) want = (uint64_t)m;
   uint32_t prefix = 0, rank = (uint32_t)want;
 #pragma unroll 1
   for (int pass = 0; pass < 2; ++pass) {
@@ -98,8 +106,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_init_list(const Args a, uint32_
 // Appends the entries of this wave's four runs of a chunk (keys above tau) and records the runs.
 // `v` holds acc.
 template <bool FULL>
-__device__ inline void list_chunk(const Args& a, int64_t tbase, const float (&v)[kPerThread],
-                                  uint32_t valid, uint32_t tau, ListCursor& lc) {
+__device__ inline void list_chunk(const Args& a, int64_t tbase, uint32_t run0,
+                                  const float (&v)[kPerThread], uint32_t valid, uint32_t tau,
+                                  ListCursor& lc) {
   uint32_t off[kSlots], cnt[kSlots];
 #pragma unroll
   for (int j = 0; j < kSlots; ++j) {
@@ -114,12 +123,12 @@ __device__ inline void list_chunk(const Args& a, int64_t tbase, const float (&v)
     const uint32_t i0 = (uint32_t)(tbase + (int64_t)(j * kBlock + (int)threadIdx.x) * 4);
     list_append_run(a, i0, x, in, lc, &off[j], &cnt[j]);
   }
-  list_record_runs(a, (uint32_t)(tbase / kRun), off, cnt);
+  list_record_runs(a, run0, off, cnt);
 }
 
 template <bool FULL, bool HIST>
-__device__ inline void accum_hist_list_chunk(const Args& a, const Tile& t, uint32_t* h, uint32_t tau,
-                                             ListCursor& lc) {
+__device__ inline void accum_hist_list_chunk(const Args& a, const Tile& t, uint32_t run0, uint32_t* h,
+                                             uint32_t tau, ListCursor& lc) {
   float g[kPerThread], e[kPerThread];
   const uint32_t valid = load_tile<FULL>(a.grad, t, g);
   load_tile<FULL>(a.resid, t, e);
@@ -132,7 +141,7 @@ __device__ inline void accum_hist_list_chunk(const Args& a, const Tile& t, uint3
     for (int i = 0; i < kPerThread; ++i)
       if (FULL || ((valid >> i) & 1u)) atomicAdd(&h[mag_key(g[i]) >> 23], 1u);
   }
-  list_chunk<FULL>(a, t.tbase, g, valid, tau, lc);
+  list_chunk<FULL>(a, t.tbase, run0, g, valid, tau, lc);
 }
 
 // A full chunk whose loads were issued earlier (accum_issue of gaussiank.h).
@@ -151,7 +160,7 @@ __device__ inline void accum_hist_list_finish(const Args& a, int64_t tbase, AccI
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) atomicAdd(&h[mag_key(in.g[i]) >> 23], 1u);
   }
-  list_chunk<true>(a, tbase, in.g, 0xFFFFu, tau, lc);
+  list_chunk<true>(a, tbase, (uint32_t)(tbase / kRun), in.g, 0xFFFFu, tau, lc);
 }
 
 // End of an accumulate kernel with lists: the workgroup's histogram into one replica of the
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_accum_list(const Args a) {
     t.lo = t.tbase;
     t.hi = a.d_total;
     t.full = false;
-    accum_hist_list_chunk<false, HIST>(a, t, hw, tau, lc);
+    accum_hist_list_chunk<false, HIST>(a, t, (uint32_t)(t.tbase / kRun), hw, tau, lc);
   }
   finish_accum_list<HIST>(a, h, lc, worker, lds_stat);
 }
@@ -314,14 +323,14 @@ __device__ inline void list_tile_counts(const Args& a, uint32_t T, bool rank_tie
   }
 }
 
-// The pairs of one tile from its lists, in index order, by one wave: `out_run` survivors and
+// The pairs of one tile (runs r0 .. r1 - 1) from its lists, in index order, by one wave: `out_run` survivors and
 // `tie_run` keys equal to T precede the tile (ties before it capped by the caller).  A lane owns
 // a run; the lanes' counts are scanned across the wave, then every lane writes its run's
 // survivors one after the other and clears them in the residual.
-__device__ inline void list_compact_tile(const Args& a, uint32_t tile, uint32_t T, uint32_t take,
-                                         bool rank_ties, uint32_t out_run, uint32_t tie_run) {
-  uint32_t r0, r1;
-  tile_runs(a, tile, &r0, &r1);
+// The output range starts at slot `out0` and holds `cap` pairs (flat calls: 0 and the call's cap).
+__device__ inline void list_compact_runs(const Args& a, uint32_t r0, uint32_t r1, uint32_t T,
+                                         uint32_t take, bool rank_ties, uint32_t out_run,
+                                         uint32_t tie_run, int64_t out0, int64_t cap) {
   for (uint32_t rb = r0; rb < r1; rb += 64) {
     const uint32_t r = rb + lane_id();
     const uint2 rec = a.run_table[r < r1 ? r : r1 - 1u];
@@ -372,9 +381,9 @@ __device__ inline void list_compact_tile(const Args& a, uint32_t tile, uint32_t 
           ++tie_pos;
         }
         if (sel) {
-          if ((int64_t)pos < a.flat_cap) {
-            a.out_idx[pos] = e[u].x;
-            a.out_val[pos] = __uint_as_float(e[u].y);
+          if ((int64_t)pos < cap) {
+            a.out_idx[out0 + pos] = e[u].x;
+            a.out_val[out0 + pos] = __uint_as_float(e[u].y);
           }
           a.resid[e[u].x] = 0.0f;
           ++pos;
@@ -384,6 +393,12 @@ __device__ inline void list_compact_tile(const Args& a, uint32_t tile, uint32_t 
     out_run += __shfl(inc, 63, 64);
     tie_run += __shfl(ties_inc, 63, 64);
   }
+}
+__device__ inline void list_compact_tile(const Args& a, uint32_t tile, uint32_t T, uint32_t take,
+                                         bool rank_ties, uint32_t out_run, uint32_t tie_run) {
+  uint32_t r0, r1;
+  tile_runs(a, tile, &r0, &r1);
+  list_compact_runs(a, r0, r1, T, take, rank_ties, out_run, tie_run, 0, a.flat_cap);
 }
 
 }  // namespace sp

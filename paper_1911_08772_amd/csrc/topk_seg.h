@@ -5,10 +5,21 @@
 // Each workgroup works for one tile and chooses its segment's digits itself; the workgroup of a
 // segment's first tile publishes them.  Launches: setup, histogram clear, accumulate, filter,
 // two list passes, final, ordered compaction.
+//
+// With short lists (topk_list.h, per segment; vectors of 6 M elements and more where the
+// workspace has room): the kernel that clears the histograms also takes a sample of every
+// segment and sets the segment's listing key; the accumulate kernel
+// also writes the residual (as if nothing were selected) and lists the entries above their
+// segment's key, a stretch of the list buffer per wave of a tile's workgroup.  A segment whose
+// lists hold at least its k entries, none of its stretches having run out, is served from them
+// by the five kernels that follow (one wave per tile reads the tile's lists); every other
+// segment of the same call takes the bodies without lists, which overwrite whatever the
+// accumulate kernel left in its stretch of the residual.  Same launches, same results.
 #pragma once
 #include "common.h"
 #include "gaussiank_seg.h"
 #include "topk_filter.h"
+#include "topk_list.h"
 
 namespace sp {
 
@@ -24,6 +35,128 @@ __device__ inline void flush_seg_hist(const Args& a, int pass, int seg, uint32_t
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) v += h[w][bin];
   if (v) atomicAdd(&seg_pass_hist(a, pass, seg)[(blockIdx.x % a.hist_copies) * 256 + bin], v);
+}
+
+// ---- short lists per segment ------------------------------------------------------------------------
+constexpr int64_t kSegListFrom = 4 * kListSample;      // shorter segments are sampled entry by entry
+
+// The sample of topk_list.h over one segment (single loads: a segment may start anywhere).  From
+// kSegListFrom elements: 4096 entries of acc, four consecutive ones every n/1024 elements.  Shorter
+// segments: min(n, 4096) entries evenly spaced, so that a segment of up to 4096 elements is its
+// own sample.
+__device__ inline uint32_t sample_listing_key_seg(const Args& a, int64_t start, int64_t n, int64_t k,
+                                                  uint32_t* lds_h, uint32_t* lds_sel) {
+  uint32_t key[16];
+  int64_t m = kListSample;
+  if (n >= kSegListFrom) {  // block-uniform
+    const int64_t stride4 = (n / 4) / (kListSample / 4);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = start + (int64_t)(u * kBlock + (int)threadIdx.x) * stride4 * 4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) key[4 * u + q] = mag_key(a.grad[i + q] + a.resid[i + q]);
+    }
+  } else {
+    m = n < kListSample ? n : (int64_t)kListSample;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int64_t j = u * kBlock + (int)threadIdx.x;
+      const int64_t i = start + (j < m ? j : m - 1) * n / m;  // (a lane beyond the sample re-reads its last entry)
+      const float x = a.grad[i] + a.resid[i];
+      key[u] = j < m ? mag_key(x) : 0u;
+    }
+  }
+  return listing_key_from_sample(key, k, n, m, lds_h, lds_sel);
+}
+
+// Clears the histograms (the workgroups from a.L on) and sets the listing key of every segment
+// whose lists would stay short (workgroup s: segment s); the setup kernel has left "nothing is
+// listed" in every segment.
+__global__ __launch_bounds__(kBlock) void k_topk_init_seg(const Args a, uint32_t hist_words) {
+  __shared__ uint32_t lds_h[256];
+  __shared__ uint32_t lds_sel[kWaves + 3];
+  if (blockIdx.x >= (uint32_t)a.L) {
+    const uint32_t nb = gridDim.x - (uint32_t)a.L;
+    for (uint32_t i = (blockIdx.x - (uint32_t)a.L) * kBlock + threadIdx.x; i < hist_words; i += nb * kBlock)
+      a.hist[i] = 0;
+    return;
+  }
+  SegCtrl& c = a.ctrl[blockIdx.x];
+  if (c.bad || c.select_none) return;
+  const int64_t n = c.end - c.start;
+  // as the flat call: lists of about 8 k entries at most are to stay within a tenth of n (a
+  // segment that fits a wave's stretch of the list buffer whole cannot make one run out)
+  if (2 * kListAim * c.k * 10 > n && n > (int64_t)a.list_cap) return;
+  const uint32_t tau = sample_listing_key_seg(a, c.start, n, c.k, lds_h, lds_sel);  // barriers
+  if (threadIdx.x == 0) c.tau_key = tau;
+}
+
+// The accumulate kernel with lists: k_topk_accum_hist plus the residual write and the lists of
+// the tile's entries above its segment's key.  The runs are numbered by tile and chunk
+// (gaussiank_seg.h); the segment's control block collects how many entries its tiles listed and
+// whether a stretch ran out.
+__global__ __launch_bounds__(kBlock) void k_topk_accum_list_seg(const Args a) {
+  __shared__ uint32_t h[kWaves][256];
+  __shared__ uint32_t lds_stat[2 * kWaves];
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t tile = blockIdx.x;
+  Span sp_;
+  if (!locate_span<true>(a, tile, &sp_)) return;
+  SegCtrl& c = a.ctrl[sp_.seg];
+  if (c.bad) return;
+  const uint32_t tau = c.tau_key;
+  const uint32_t worker = tile * kWaves + wave_id();
+  ListCursor lc;
+  lc.cur = worker * a.list_cap;
+  lc.end = lc.cur + a.list_cap;
+  lc.over = false;
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    const uint32_t run0 = (tile * a.tile_chunks + u) * kRunsPerChunk;
+    if (t.full) accum_hist_list_chunk<true, true>(a, t, run0, h[wave_id()], tau, lc);
+    else accum_hist_list_chunk<false, true>(a, t, run0, h[wave_id()], tau, lc);
+  }
+  if (lane_id() == 0) {
+    lds_stat[2 * wave_id()] = lc.cur - worker * a.list_cap;
+    lds_stat[2 * wave_id() + 1] = lc.over ? 1u : 0u;
+  }
+  flush_hist(a, sp_.seg, h);  // starts with a barrier
+  if (threadIdx.x == 0) {
+    uint32_t n = 0, over = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      n += lds_stat[2 * w];
+      over |= lds_stat[2 * w + 1];
+    }
+    if (n) atomicAdd(&c.list_count, n);
+    if (over) atomicOr(&c.list_mode, 1u);
+  }
+}
+
+// Whether a segment's lists serve it: none of its stretches ran out and they hold at least k
+// entries (then they hold the k largest: every key >= the k-th key exceeds the listing key).
+// Every workgroup of the kernels after the accumulate kernel reads the same final words.
+__device__ inline bool seg_lists_usable(const Args& a, const SegCtrl& c) {
+  return a.list && c.list_mode == 0 && (int64_t)c.list_count >= c.k;
+}
+// the runs of a layer-wise tile
+__device__ inline void seg_tile_runs(const Args& a, uint32_t tile, const Span& s, uint32_t* r0, uint32_t* r1) {
+  *r0 = tile * a.tile_chunks * kRunsPerChunk;
+  *r1 = *r0 + s.nchunks * kRunsPerChunk;
+}
+// A digit pass over a tile's lists by the workgroup's first wave (list_digit_pass of topk_list.h).
+__device__ inline void seg_list_digit_pass(const Args& a, uint32_t r0, uint32_t r1, int pass,
+                                           uint32_t prefix, uint32_t* hw) {
+  if (wave_id() != 0) return;
+  const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);
+  const int shift = digit_shift(pass);
+  const uint32_t mask = (1u << digit_bits(pass)) - 1u;
+  for_each_list_entry_of_runs(a, r0, r1, [&](uint2 e, bool valid) {
+    const uint32_t key = e.y & 0x7FFFFFFFu;
+    wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == prefix);
+  });
 }
 
 __global__ __launch_bounds__(kBlock) void k_topk_filter_seg(const Args a) {
@@ -44,6 +177,14 @@ __global__ __launch_bounds__(kBlock) void k_topk_filter_seg(const Args a) {
   if (tile == c.tile0 && threadIdx.x == 0) {
     c.sel_prefix[0] = dg.prefix;
     c.sel_krem[0] = dg.k_rem;
+  }
+  if (seg_lists_usable(a, c)) {  // the second digit's histogram from the tile's lists
+    uint32_t r0, r1;
+    seg_tile_runs(a, tile, sp_, &r0, &r1);
+    seg_list_digit_pass(a, r0, r1, 1, dg.prefix, h[0]);
+    __syncthreads();
+    flush_seg_hist(a, 1, sp_.seg, h);
+    return;
   }
   uint32_t* cand = span_candidates(a, sp_);
   uint32_t above = 0;
@@ -82,6 +223,14 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist_seg(const Args a, int
     c.sel_prefix[pass - 1] = dg.prefix;
     c.sel_krem[pass - 1] = dg.k_rem;
   }
+  if (seg_lists_usable(a, c)) {
+    uint32_t r0, r1;
+    seg_tile_runs(a, tile, sp_, &r0, &r1);
+    seg_list_digit_pass(a, r0, r1, pass, dg.prefix, h[0]);
+    __syncthreads();
+    flush_seg_hist(a, pass, sp_.seg, h);
+    return;
+  }
   const int hi_shift = digit_shift(pass - 1);
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
@@ -119,10 +268,32 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final_seg(const Args a) {
     sparsify_result& r = a.result[sp_.seg];
     r.topk_key = T;
     r.topk_ties_taken = dg.k_rem;
+    if (a.list) r.flags |= seg_lists_usable(a, c) ? SPARSIFY_F_SHORTLIST : SPARSIFY_F_SHORTLIST_MISS;  // which way, no result
+  }
+  uint32_t gt = 0, eq = 0;
+  if (seg_lists_usable(a, c)) {  // the tile's counts from its lists, by one wave
+    if (wave_id() != 0) return;
+    uint32_t r0, r1;
+    seg_tile_runs(a, tile, sp_, &r0, &r1);
+    for_each_list_entry_of_runs(a, r0, r1, [&](uint2 e, bool valid) {
+      const uint32_t key = e.y & 0x7FFFFFFFu;
+      gt += (valid && key > T) ? 1u : 0u;
+      eq += (valid && key == T) ? 1u : 0u;
+    });
+    gt = wave_sum(gt);
+    eq = wave_sum(eq);
+    if (lane_id() == 0) {
+      const uint32_t taken = gt + (rank_ties ? 0u : eq);
+      tile_row(a, kRowTake)[tile] = taken;
+      tile_row(a, kRowTies)[tile] = rank_ties ? eq : 0u;
+      uint32_t* grp = a.seg_groups + (size_t)(c.group0 + (tile - c.tile0) / kSegGroupTiles) * kNumThres;
+      if (taken) atomicAdd(&grp[kColTake], taken);
+      if (rank_ties && eq) atomicAdd(&grp[kColTies], eq);
+    }
+    return;
   }
   const uint32_t n = tile_row(a, kRowCand)[tile];
   const uint32_t* cand = span_candidates(a, sp_);
-  uint32_t gt = 0, eq = 0;
   for (uint32_t i = threadIdx.x; i < n; i += kBlock) {
     const uint32_t key = cand[i];
     gt += key > T ? 1u : 0u;
@@ -166,12 +337,20 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered_seg(const Args 
   const SegCtrl& c = a.ctrl[sp_.seg];
   if (c.bad) return;
   const bool none = c.select_none != 0;
+  if (a.list && none) return;  // the accumulate kernel has written residual' = acc
   const OrderedSel o = {c.topk_key, c.topk_take, c.rank_ties != 0, none, c.out_base, c.cap};
   uint32_t tie_run = 0, out_run = 0;
   if (!none) {  // block-uniform
     segment_totals(a, c, tile, lds_tot, lds_pre);
     tie_run = o.rank_ties ? lds_pre[kColTies] : 0u;
     out_run = lds_pre[kColTake] + (tie_run < o.take ? tie_run : o.take);
+  }
+  if (seg_lists_usable(a, c)) {  // the tile's pairs from its lists, by one wave; the residual is in place
+    if (wave_id() != 0) return;
+    uint32_t r0, r1;
+    seg_tile_runs(a, tile, sp_, &r0, &r1);
+    list_compact_runs(a, r0, r1, o.T, o.take, o.rank_ties, out_run, tie_run, o.out0, o.cap);
+    return;
   }
   NormAcc norms = {0.0, 0.0};
   for (uint32_t u = 0; u < sp_.nchunks; ++u) {

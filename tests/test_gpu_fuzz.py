@@ -108,10 +108,11 @@ def awkward_vector(rng, d):
     return (rng.standard_normal(d) * 0.01 + rng.choice([-5.0, 0.3, 5.0])).astype(np.float32)
 
 
-def test_segmented_gaussiank_random_cases_where_short_lists_are_built():
-    """Layer-wise Gaussian_k on vectors of 6 M elements and more: every segment decides for itself
+@pytest.mark.parametrize("mode", [1, 0])
+def test_segmented_random_cases_where_short_lists_are_built(mode):
+    """Layer-wise calls on vectors of 6 M elements and more: every segment decides for itself
     whether its pairs come from its lists; results must not depend on it."""
-    rng = np.random.default_rng(60_000_001)
+    rng = np.random.default_rng(60_000_001 + mode)
     ways = set()
     for case in range(10):
         d = int(rng.integers(6_000_000, 8_500_000))
@@ -130,10 +131,12 @@ def test_segmented_gaussiank_random_cases_where_short_lists_are_built():
         eps = awkward_vector(rng, d) if rng.random() < 0.4 else np.zeros(d, np.float32)
         gpu = SegGpu(seg_off, seg_k, caps, inplace=bool(rng.random() < 0.3))
         gpu.set_residual(eps)
-        check_segmented(1, gpu, g, eps, what=f"case {case}: L={L} d={d}", tile_chunks=int(rng.choice([0, 0, 1, 3])))
-        ways |= {int(r["flags"]) & S.F_WAY for r in S.decode_results(gpu.b.result) if not int(r["flags"]) & S.F_BADSEGMENT}
+        check_segmented(mode, gpu, g, eps, what=f"mode {mode} case {case}: L={L} d={d}", tile_chunks=int(rng.choice([0, 0, 1, 3])))
+        ways |= {int(r["flags"]) & S.F_WAY for r in S.decode_results(gpu.b.result)
+                 if not int(r["flags"]) & (S.F_BADSEGMENT | S.F_OVERFLOW)}
         del gpu
-    assert ways == {S.F_SHORTLIST, S.F_SHORTLIST_MISS}, ways   # both ways were exercised
+    # both ways were exercised (Top_k in place has no lists: no way bit at all)
+    assert ways - {0} == {S.F_SHORTLIST, S.F_SHORTLIST_MISS} and (mode == 0 or 0 not in ways), ways
 
 
 @pytest.mark.parametrize("mode", [0, 1])

@@ -92,7 +92,7 @@ def test_the_lists_can_be_declined():
     g = synth.normal(d, 72, 0, 0.01)
     eps = synth.normal(d, 73, 0, 0.003)
     gpu = SegGpu(seg_off, seg_k, caps)
-    for mode, kw in ((1, {"short_list": -1}), (1, {"error_norms": True}), (0, {})):
+    for mode, kw in ((1, {"short_list": -1}), (1, {"error_norms": True})):
         gpu.set_residual(eps)
         check_segmented(mode, gpu, g, eps, what=f"mode {mode} {kw}", **kw)
         assert ways(gpu) == [0, 0, 0], (mode, kw)

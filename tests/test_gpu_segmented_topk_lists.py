@@ -1,0 +1,187 @@
+"""GPU parity of the layer-wise Top_k call (separate acc) with short lists per segment (vectors of
+6 M elements and more, up to 1024 segments): a sample of every segment sets the segment's listing key, the accumulate kernel writes the residual and lists the entries
+above it, and a segment whose lists hold at least its k entries is served from them; every other
+segment of the same call takes the bodies without lists.  Results must not depend on the way, so
+every case is compared with the CPU oracle bit for bit, and the way each segment took (two
+informational flag bits) is checked against what the input was built to provoke."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_harness import SegGpu, check_segmented
+from paper_1911_08772_amd import sparsify as S
+from paper_1911_08772_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LIST, MISS = S.F_SHORTLIST, S.F_SHORTLIST_MISS
+
+
+def ways(gpu):
+    return [int(r["flags"]) & S.F_WAY for r in S.decode_results(gpu.b.result)]
+
+
+def layout(sizes, rho=0.001):
+    sizes = np.asarray(sizes, np.int64)
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    seg_k = np.maximum(1, np.ceil(sizes * rho)).astype(np.int64)
+    caps = np.maximum(4 * seg_k, 64)
+    return seg_off, seg_k, caps
+
+
+def test_resnet50_sized_layout_takes_the_lists():
+    wl = synth.workload("cfg4_segmented")
+    caps = np.maximum(4 * wl.seg_k, 1024)
+    gpu = SegGpu(wl.seg_off, wl.seg_k, caps)
+    sizes = np.diff(wl.seg_off)
+    eps = np.zeros(wl.d, np.float32)
+    for step in range(4):
+        gpu.set_residual(eps)
+        eps = check_segmented(0, gpu, wl.grad(step), eps, what=f"cfg4 step {step}")
+        w = ways(gpu)
+        # the sample aims at four times k entries (16 of the sample at least): every segment is served
+        assert all(x == LIST for x in w), (step, w, sizes)
+
+
+def test_segments_decide_for_themselves():
+    """Bell-shaped segments, tiny ones among them, between an all-zero one, a constant one, one with
+    half of its entries asked for and one whose k-th key is shared by thousands of entries; ragged
+    offsets."""
+    sizes = [2_000_003, 700_001, 1_500_000, 1, 4097, 900_000, 1_100_007, 333, 16_383, 16_385, 800_001]
+    seg_off, seg_k, caps = layout(sizes)
+    seg_k[5] = sizes[5] // 2
+    caps[5] = sizes[5]
+    d = int(seg_off[-1])
+    rng = np.random.default_rng(13)
+    g = synth.normal(d, 171, 0, 0.01)
+    g[seg_off[1]:seg_off[2]] = 0.0
+    g[seg_off[6]:seg_off[7]] = np.float32(0.3)
+    tied = rng.choice(sizes[10], 3 * int(seg_k[10]), replace=False) + seg_off[10]
+    g[tied] = np.float32(0.51) * rng.choice([-1.0, 1.0], tied.size).astype(np.float32)
+    gpu = SegGpu(seg_off, seg_k, caps)
+    zero = np.zeros(d, np.float32)
+    gpu.set_residual(zero)
+    check_segmented(0, gpu, g, zero, what="mixed segments")
+    w = ways(gpu)
+    assert [w[i] for i in (0, 2, 4, 7, 8, 9, 10)] == [LIST] * 7, w
+    assert [w[i] for i in (1, 5, 6)] == [MISS] * 3, w
+    assert w[3] in (LIST, MISS), w   # (one element: listed unless its key is its bin's lower edge)
+    res = S.decode_results(gpu.b.result)
+    assert int(res[10]["topk_ties_taken"]) == int(seg_k[10])  # (all of its survivors are ranked ties)
+
+
+def test_a_stretch_that_runs_out_leaves_its_own_segment_to_the_other_bodies():
+    sizes = [3_000_000, 2_000_000, 1_500_000]
+    seg_off, seg_k, caps = layout(sizes)
+    d = int(seg_off[-1])
+    rng = np.random.default_rng(14)
+    g = rng.standard_normal(d).astype(np.float32)
+    g[3_100_000:3_120_000] *= np.float32(100.0)   # a third of this stretch exceeds its segment's listing key
+    gpu = SegGpu(seg_off, seg_k, caps)
+    zero = np.zeros(d, np.float32)
+    gpu.set_residual(zero)
+    check_segmented(0, gpu, g, zero, what="one loud stretch")
+    assert ways(gpu) == [LIST, MISS, LIST]
+
+
+def test_the_lists_can_be_declined():
+    sizes = [3_000_000, 2_000_001, 1_499_999]
+    seg_off, seg_k, caps = layout(sizes)
+    d = int(seg_off[-1])
+    g = synth.normal(d, 172, 0, 0.01)
+    eps = synth.normal(d, 173, 0, 0.003)
+    gpu = SegGpu(seg_off, seg_k, caps)
+    for kw in ({"short_list": -1}, {"error_norms": True}):
+        gpu.set_residual(eps)
+        check_segmented(0, gpu, g, eps, what=f"{kw}", **kw)
+        assert ways(gpu) == [0, 0, 0], kw
+    for kw in ({}, {"tile_chunks": 1}, {"tile_chunks": 2}):
+        gpu.set_residual(eps)
+        check_segmented(0, gpu, g, eps, what=f"{kw}", **kw)
+        assert ways(gpu) == [LIST] * 3, kw
+    # a forced tile length whose ragged tiles the run table does not hold
+    gpu.set_residual(eps)
+    check_segmented(0, gpu, g, eps, what="tile_chunks=64", tile_chunks=64)
+    assert ways(gpu) == [0, 0, 0]
+    small = S.workspace_bytes_min(d, 3)
+    assert small < gpu.b.workspace_nbytes
+    gpu.b.workspace = torch.empty(small, dtype=torch.uint8, device="cuda:0")
+    gpu.set_residual(eps)
+    check_segmented(0, gpu, g, eps, what="small workspace")
+    assert ways(gpu) == [0, 0, 0]
+    # acc == residual: the in-place form has no lists
+    gpu = SegGpu(seg_off, seg_k, caps, inplace=True)
+    gpu.set_residual(eps)
+    check_segmented(0, gpu, g, eps, what="in place")
+    assert ways(gpu) == [0, 0, 0]
+
+
+def test_an_output_range_smaller_than_k():
+    """A segment whose output range cannot hold its k entries selects nothing and keeps acc as
+    its residual (which the accumulate kernel has written); the others are served as usual."""
+    sizes = [2_500_000, 2_000_000, 1_700_000]
+    seg_off, seg_k, caps = layout(sizes)
+    caps[1] = seg_k[1] - 1
+    d = int(seg_off[-1])
+    g = synth.normal(d, 174, 0, 0.01)
+    eps = synth.normal(d, 175, 0, 0.003)
+    gpu = SegGpu(seg_off, seg_k, caps)
+    gpu.set_residual(eps)
+    check_segmented(0, gpu, g, eps, what="cap < k")
+    res = S.decode_results(gpu.b.result)
+    assert int(res[1]["flags"]) == S.F_OVERFLOW and int(res[1]["nnz"]) == 0
+    assert [ways(gpu)[0], ways(gpu)[2]] == [LIST, LIST]
+
+
+def test_a_layer_wise_call_with_lists_can_be_captured_in_a_hip_graph():
+    """Every segment's way is decided on the device, so a captured call replays with or without
+    the lists as each replay's data asks."""
+    from gpu_harness import same_bits
+    from oracle import oracle as O
+    sizes = [3_000_000, 2_000_001, 1_499_999]
+    seg_off, seg_k, caps = layout(sizes)
+    d, L = int(seg_off[-1]), 3
+    out_off = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+    ocap = int(out_off[-1])
+    b = S.Buffers.allocate(d, ocap, L)
+    grad = torch.zeros(d, device="cuda:0")
+    d_off, d_k, d_oo = (torch.from_numpy(x).to("cuda:0") for x in (seg_off, seg_k, out_off))
+
+    def call():
+        S.sparsify_segmented(L, d, d_off, d_k, 0, grad, b.residual, b.acc, b.out_idx, b.out_val, d_oo,
+                             ocap, b.result, b.workspace, b.workspace_nbytes)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # warm-up outside capture (first-call queries of the runtime)
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    b.residual.zero_()
+    eps = np.zeros(d, np.float32)
+    for step in range(4):
+        g = synth.normal(d, 183, step, 0.01)
+        if step == 2:   # the middle segment constant: no list holds it, it alone takes the other bodies
+            g[seg_off[1]:seg_off[2]] = np.float32(0.3)
+            eps = np.zeros(d, np.float32)
+            b.residual.zero_()
+        grad.copy_(torch.from_numpy(g))
+        b.out_idx.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        acc_o = O.accumulate(g, eps)
+        idx_o, val_o, eps, res_o = O.segmented(acc_o, seg_off, seg_k, 0, out_off)
+        res = S.decode_results(b.result)
+        got_idx, got_val = b.out_idx.cpu().numpy(), b.out_val.cpu().numpy()
+        for l in range(L):
+            n, o0 = res_o[l].nnz, int(out_off[l])
+            assert int(res[l]["nnz"]) == n and int(res[l]["topk_key"]) == res_o[l].topk_key, (step, l)
+            assert np.array_equal(got_idx[o0:o0 + n].view(np.uint32), idx_o[o0:o0 + n]), (step, l)
+            assert same_bits(got_val[o0:o0 + n], val_o[o0:o0 + n]), (step, l)
+        w = [int(r["flags"]) & S.F_WAY for r in res]
+        assert w == ([LIST, MISS, LIST] if step == 2 else [LIST] * 3), (step, w)
+        assert same_bits(b.residual.cpu().numpy(), eps), step
+        assert same_bits(b.acc.cpu().numpy(), acc_o), step
+        _ = (b.acc * 2).sum().item()   # unrelated eager work between replays
