@@ -104,21 +104,52 @@ __device__ inline uint32_t wave_max(uint32_t v) {
 // empty run the entry at its offset), kept inside the buffer, and reports it as not valid.
 // fn(entry, valid) is called by the whole wave; the order of the calls is not the index order.
 constexpr int kListBatch = 4;
+
+// The head of a tile's lists, which a wave can have on order before it knows the tile's extent
+// or whether it will read the lists at all (a kernel whose prologue makes several dependent
+// trips to memory of its own): the records of the tile's first 64 run slots, then the first
+// kListBatch entries at each record's offset.  A slot beyond the tile's chunks was never written
+// and may hold anything: every index is kept inside the buffers, and the reader drops what lies
+// beyond the tile's runs and the runs' lengths.
+struct ListHead {
+  uint2 rec;
+  uint2 e[kListBatch];
+};
+__device__ inline void list_head_records(const Args& a, uint32_t r0, uint32_t nslots, ListHead& h) {
+  const uint32_t l = (uint32_t)lane_id();
+  h.rec = a.run_table[r0 + (l < nslots ? l : nslots - 1u)];
+}
+__device__ inline void list_head_entries(const Args& a, ListHead& h) {
+#pragma unroll
+  for (int u = 0; u < kListBatch; ++u) {
+    const uint32_t i = h.rec.x + (uint32_t)u;
+    h.e[u] = a.list[i < a.list_last ? i : a.list_last];
+  }
+}
+
+// `head`: the head of these runs if the caller has fetched it (then r0 is its first slot), else null.
 template <typename F>
-__device__ inline void for_each_list_entry_of_runs(const Args& a, uint32_t r0, uint32_t r1, F fn) {
+__device__ inline void for_each_list_entry_of_runs(const Args& a, uint32_t r0, uint32_t r1,
+                                                   const ListHead* head, F fn) {
   for (uint32_t rb = r0; rb < r1; rb += 64) {
     const uint32_t r = rb + lane_id();
-    const uint2 rec = a.run_table[r < r1 ? r : r1 - 1u];
+    const bool first = head != nullptr && rb == r0;  // wave-uniform
+    const uint2 rec = first ? head->rec : a.run_table[r < r1 ? r : r1 - 1u];
     const uint32_t n = r < r1 ? rec.y : 0u, off = rec.x;
     const uint32_t last = n ? n - 1u : 0u;
     const uint32_t nmax = wave_max(n);
     for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
       uint2 e[kListBatch];
+      if (first && i0 == 0) {
 #pragma unroll
-      for (int u = 0; u < kListBatch; ++u) {
-        uint32_t i = off + (i0 + u < last ? i0 + u : last);
-        i = i < a.list_last ? i : a.list_last;
-        e[u] = a.list[i];
+        for (int u = 0; u < kListBatch; ++u) e[u] = head->e[u];
+      } else {
+#pragma unroll
+        for (int u = 0; u < kListBatch; ++u) {
+          uint32_t i = off + (i0 + u < last ? i0 + u : last);
+          i = i < a.list_last ? i : a.list_last;
+          e[u] = a.list[i];
+        }
       }
 #pragma unroll
       for (int u = 0; u < kListBatch; ++u)
@@ -130,7 +161,7 @@ template <typename F>
 __device__ inline void for_each_list_entry(const Args& a, uint32_t tile, F fn) {
   uint32_t r0, r1;
   tile_runs(a, tile, &r0, &r1);
-  for_each_list_entry_of_runs(a, r0, r1, fn);
+  for_each_list_entry_of_runs(a, r0, r1, nullptr, fn);
 }
 
 }  // namespace sp

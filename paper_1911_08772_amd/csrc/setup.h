@@ -19,12 +19,6 @@ __device__ inline void clear_result(sparsify_result& r) {
   r.residual_sqnorm = 0.0;
 }
 
-__global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-       i += (size_t)gridDim.x * blockDim.x)
-    p[i] = v;
-}
-
 // Plain copy of n floats (n a multiple of 4, both pointers 16-byte aligned): a kernel of known
 // traffic, 4n bytes read and 4n written, against which hardware byte counters are scaled.
 __global__ __launch_bounds__(kBlock) void k_calibration_copy(float* dst, const float* src, size_t n4) {
@@ -66,7 +60,7 @@ __device__ inline int64_t block_exclusive_max(int64_t v, int64_t lowest, int64_t
   return before;
 }
 
-__global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
+__device__ inline void seg_setup_body(const Args& a, int mode) {
   __shared__ uint32_t lds_scan[kWaves + 1];
   __shared__ int64_t lds_max[kWaves];
   uint32_t carry = 0;    // tiles numbered so far (block-uniform, saturating)
@@ -125,7 +119,6 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
       c.t_final = 0.0f;
       c.list_mode = 0;  // layer-wise calls with lists: set when one of the segment's stretches ran out
       c.list_count = 0;
-      c.tau_key = kNoListKey;  // layer-wise Top_k with lists: until the segment's sample says otherwise
       sparsify_result& r = a.result[s];
       clear_result(r);
       if (bad) {
@@ -147,5 +140,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) {
   const uint32_t words = (gcarry < a.max_groups ? gcarry : a.max_groups) * (uint32_t)kNumThres;
   for (uint32_t i = threadIdx.x; i < words; i += kBlock) a.seg_groups[i] = 0;
 }
+
+__global__ __launch_bounds__(kBlock) void k_seg_setup(const Args a, int mode) { seg_setup_body(a, mode); }
 
 }  // namespace sp

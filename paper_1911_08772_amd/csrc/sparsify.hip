@@ -103,8 +103,19 @@ uint32_t max_tiles_of(int64_t d_total, int32_t L, uint32_t tile_chunks) {
   return (uint32_t)(d_total / ((int64_t)kChunk * tile_chunks) + 2 * (int64_t)L + 1);
 }
 
-// replicas of each segment's global histogram: spreads same-address atomics of the flat call
-uint32_t hist_copies_of(int32_t L) { return L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u; }
+// Replicas of each segment's global histogram.  Every tile of a segment adds its bins to one
+// replica with device-wide atomics, and those that meet on one address are performed one after
+// the other (tens of nanoseconds each): the more tiles a segment has, the more replicas it
+// needs.  By the number of segments, and at least one replica per eight tiles of an average
+// segment at the default tile length (54 segments of 25.6 M elements: 1 -> 8 replicas took
+// 6 us off the kernel that follows the accumulate kernel).
+uint32_t hist_copies_of(int64_t d_total, int32_t L) {
+  const uint32_t by_segments = L >= 32 ? 1u : L >= 8 ? 4u : L >= 2 ? 16u : 32u;
+  const int64_t tiles_per_segment = d_total / ((int64_t)kChunk * 3 * L);
+  uint32_t by_tiles = 1;
+  while (by_tiles < 32u && (int64_t)by_tiles * 8 <= tiles_per_segment) by_tiles *= 2;
+  return by_segments > by_tiles ? by_segments : by_tiles;
+}
 
 // Short lists (lists.h; Top_k: topk_list.h, DGC_k: dgck.h, Gaussian_k: gaussiank_list.h): flat
 // vectors long enough for the passes saved to matter.  The list buffer holds kListShare of the
@@ -143,7 +154,7 @@ Carve carve(int64_t d_total, int32_t L, bool lists = false) {
   c.max_groups = (uint32_t)(mt / kGroupTiles + (size_t)L + 1);
   c.seg_groups = off;  off = align_up(off + sizeof(uint32_t) * kNumThres * (size_t)c.max_groups);
   c.norm_partial = off; off = align_up(off + sizeof(double) * 2 * mt);
-  size_t hist_words = (size_t)kDigits * 256 * (size_t)L * hist_copies_of(L);  // [pass][segment][replica]
+  size_t hist_words = (size_t)kDigits * 256 * (size_t)L * hist_copies_of(d_total, L);  // [pass][segment][replica]
   if (hist_words < (size_t)kDgcHistWords) hist_words = kDgcHistWords;  // per-pass buffers (flat): 4 or 8
   c.hist = off;        off = align_up(off + sizeof(uint32_t) * hist_words);
   // per-tile histograms of the last digit: flat Top_k in place, at most kFusedMaxTiles tiles
@@ -243,7 +254,7 @@ int prepare(Args& a, int32_t L, int64_t d_total, const float* grad, float* resid
   a.norms = (opts && opts->error_norms) ? 1 : 0;
   a.hist = reinterpret_cast<uint32_t*>(w + cv.hist);
   a.tile_hist = reinterpret_cast<uint32_t*>(w + cv.tile_hist);
-  a.hist_copies = hist_copies_of(L);
+  a.hist_copies = hist_copies_of(d_total, L);
   if (lists) {
     a.list = reinterpret_cast<uint2*>(w + cv.list);
     a.run_table = reinterpret_cast<uint2*>(w + cv.run_table);
@@ -658,16 +669,16 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
   Launcher ln{static_cast<hipStream_t>(stream),
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
   ln.begin();
-  ln.run("seg_setup", k_seg_setup, dim3(1), dim3(kBlock), a, (int)mode);
   if (mode == 1) {
+    ln.run("seg_setup", k_seg_setup, dim3(1), dim3(kBlock), a, 1);
     launch_gaussiank_seg(ln, a, tiles);
   } else {
+    // the setup kernel's other workgroups clear the histograms ([pass][segment][replica][256]: at
+    // most 2^30 words) and, with lists, sample the segments (topk_seg.h)
     const size_t n = (size_t)kDigits * 256 * (size_t)num_segments * a.hist_copies;
     const unsigned fill_wgs = (unsigned)((n + 1023) / 1024 < 1024 ? (n + 1023) / 1024 : 1024);
-    if (a.list)  // (at most kListMaxSegments segments: n fits 32 bits)
-      ln.run("hist_zero", k_topk_init_seg, dim3((unsigned)num_segments + fill_wgs), dim3(kBlock), a, (uint32_t)n);
-    else
-      ln.run("hist_zero", k_fill_u32, dim3(fill_wgs), dim3(256), a.hist, n, 0u);
+    const unsigned samplers = a.list ? (unsigned)num_segments : 0u;
+    ln.run("seg_setup", k_topk_seg_setup, dim3(1 + samplers + fill_wgs), dim3(kBlock), a, (uint32_t)n, samplers);
     launch_topk_seg(ln, a, tiles);
   }
   if (ln.tr) ln.tr->ok = (ln.err == hipSuccess);

@@ -2,7 +2,7 @@
 // passes (8, 8, 8, 7 bits, most significant first) with per-wave histograms in LDS, a digit
 // choice after each pass, then compaction of {key > T} plus the lowest-index ties.  This file
 // holds the building blocks (digit layout, histogram flush, the accumulate kernel with the first
-// digit's histogram, one chunk of the ordered compaction) and the twelve-launch form of the
+// digit's histogram, one chunk of the ordered compaction) and the eleven-launch form of the
 // layer-wise calls in place: one single-workgroup "select" kernel per segment after each pass,
 // one more pass over acc that counts every tile's survivors and ties once the k-th key T is
 // known, and a per-segment scan of those counts.  The other forms are in topk_filter.h (flat),

@@ -57,6 +57,36 @@ __device__ inline uint32_t listing_key_from_sample(const uint32_t (&key)[16], in
   uint64_t want = ((uint64_t)kListAim * (uint64_t)k * (uint64_t)m + (uint64_t)n - 1) / (uint64_t)n;
   if (want < 16) want = 16;
   if (want > (uint64_t)m) want = (uint64_t)m;
+  {
+    // As a rule the key asked for lies within a factor of two of the sample's largest: then one
+    // histogram of the distance to it, in steps of the 16-bit key, finds it, and only the few
+    // keys that close to the largest are added (an exponent histogram of the whole sample puts
+    // half of its 4096 increments on one LDS address, one after the other).
+    uint32_t mx = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mx = (key[i] >> 15) > mx ? (key[i] >> 15) : mx;
+    mx = wave_max(mx);
+    lds_h[threadIdx.x] = 0;
+    if (lane_id() == 0) lds_sel[wave_id()] = mx;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) mx = lds_sel[w] > mx ? lds_sel[w] : mx;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t dist = mx - (key[i] >> 15);
+      if (dist < 255u) atomicAdd(&lds_h[dist], 1u);
+    }
+    __syncthreads();
+    const uint32_t v = threadIdx.x < 255u ? lds_h[threadIdx.x] : 0u;
+    if (threadIdx.x == 0) lds_sel[kWaves] = 0xFFFFFFFFu;
+    uint32_t total;
+    const uint32_t closer = block_exclusive_scan<kWaves>(v, lds_sel, &total);  // keys nearer to the largest
+    if (v != 0 && closer < (uint32_t)want && (uint32_t)want <= closer + v) lds_sel[kWaves] = threadIdx.x;
+    __syncthreads();
+    const uint32_t dist = lds_sel[kWaves];
+    __syncthreads();  // lds_h and lds_sel are used again below
+    if (dist != 0xFFFFFFFFu) return (mx - dist) << 15;  // block-uniform
+  }
   uint32_t prefix = 0, rank = (uint32_t)want;
 #pragma unroll 1
   for (int pass = 0; pass < 2; ++pass) {
@@ -328,23 +358,31 @@ __device__ inline void list_tile_counts(const Args& a, uint32_t T, bool rank_tie
 // a run; the lanes' counts are scanned across the wave, then every lane writes its run's
 // survivors one after the other and clears them in the residual.
 // The output range starts at slot `out0` and holds `cap` pairs (flat calls: 0 and the call's cap).
+// `head`: the head of these runs (lists.h) if the caller has fetched it, else null.
 __device__ inline void list_compact_runs(const Args& a, uint32_t r0, uint32_t r1, uint32_t T,
                                          uint32_t take, bool rank_ties, uint32_t out_run,
-                                         uint32_t tie_run, int64_t out0, int64_t cap) {
+                                         uint32_t tie_run, int64_t out0, int64_t cap,
+                                         const ListHead* head = nullptr) {
   for (uint32_t rb = r0; rb < r1; rb += 64) {
     const uint32_t r = rb + lane_id();
-    const uint2 rec = a.run_table[r < r1 ? r : r1 - 1u];
+    const bool first = head != nullptr && rb == r0;  // wave-uniform
+    const uint2 rec = first ? head->rec : a.run_table[r < r1 ? r : r1 - 1u];
     const uint32_t n = r < r1 ? rec.y : 0u, off = rec.x;
     const uint32_t last = n ? n - 1u : 0u;
     const uint32_t nmax = wave_max(n);
     uint32_t csel = 0, ceq = 0;
     for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
       uint2 e[kListBatch];
+      if (first && i0 == 0) {
 #pragma unroll
-      for (int u = 0; u < kListBatch; ++u) {
-        uint32_t i = off + (i0 + u < last ? i0 + u : last);
-        i = i < a.list_last ? i : a.list_last;
-        e[u] = a.list[i];
+        for (int u = 0; u < kListBatch; ++u) e[u] = head->e[u];
+      } else {
+#pragma unroll
+        for (int u = 0; u < kListBatch; ++u) {
+          uint32_t i = off + (i0 + u < last ? i0 + u : last);
+          i = i < a.list_last ? i : a.list_last;
+          e[u] = a.list[i];
+        }
       }
 #pragma unroll
       for (int u = 0; u < kListBatch; ++u) {
@@ -365,11 +403,16 @@ __device__ inline void list_compact_runs(const Args& a, uint32_t r0, uint32_t r1
     uint32_t tie_pos = ties_before;
     for (uint32_t i0 = 0; i0 < nmax; i0 += kListBatch) {
       uint2 e[kListBatch];
+      if (first && i0 == 0) {
 #pragma unroll
-      for (int u = 0; u < kListBatch; ++u) {
-        uint32_t i = off + (i0 + u < last ? i0 + u : last);
-        i = i < a.list_last ? i : a.list_last;
-        e[u] = a.list[i];
+        for (int u = 0; u < kListBatch; ++u) e[u] = head->e[u];
+      } else {
+#pragma unroll
+        for (int u = 0; u < kListBatch; ++u) {
+          uint32_t i = off + (i0 + u < last ? i0 + u : last);
+          i = i < a.list_last ? i : a.list_last;
+          e[u] = a.list[i];
+        }
       }
 #pragma unroll
       for (int u = 0; u < kListBatch; ++u) {

@@ -3,12 +3,12 @@
 // histograms ([pass][segment][replica][256]) and its own groups of 64 tiles (numbered by
 // k_seg_setup); a tile's candidate keys live in the tile's stretch of the idle residual buffer.
 // Each workgroup works for one tile and chooses its segment's digits itself; the workgroup of a
-// segment's first tile publishes them.  Launches: setup, histogram clear, accumulate, filter,
-// two list passes, final, ordered compaction.
+// segment's first tile publishes them.  Launches: setup (which also clears the histograms),
+// accumulate, filter, two list passes, final, ordered compaction.
 //
 // With short lists (topk_list.h, per segment; vectors of 6 M elements and more where the
-// workspace has room): the kernel that clears the histograms also takes a sample of every
-// segment and sets the segment's listing key; the accumulate kernel
+// workspace has room): beside the workgroup that numbers the tiles, the setup kernel has one
+// workgroup per segment that takes a sample of it and sets its listing key; the accumulate kernel
 // also writes the residual (as if nothing were selected) and lists the entries above their
 // segment's key, a stretch of the list buffer per wave of a tile's workgroup.  A segment whose
 // lists hold at least its k entries, none of its stretches having run out, is served from them
@@ -49,46 +49,60 @@ __device__ inline uint32_t sample_listing_key_seg(const Args& a, int64_t start, 
   uint32_t key[16];
   int64_t m = kListSample;
   if (n >= kSegListFrom) {  // block-uniform
-    const int64_t stride4 = (n / 4) / (kListSample / 4);
+    const int64_t stride16 = (n / 16) / kBlock;
+    const int64_t i = start + (int64_t)threadIdx.x * stride16 * 16;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t i = start + (int64_t)(u * kBlock + (int)threadIdx.x) * stride4 * 4;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) key[4 * u + q] = mag_key(a.grad[i + q] + a.resid[i + q]);
-    }
+    for (int q = 0; q < 16; ++q) key[q] = mag_key(a.grad[i + q] + a.resid[i + q]);
   } else {
-    m = n < kListSample ? n : (int64_t)kListSample;
+    static_assert(kListSample == 4096, "the spacing below is a shift");
+    const uint32_t n32 = (uint32_t)n;
+    const uint32_t m32 = n32 < (uint32_t)kListSample ? n32 : (uint32_t)kListSample;
+    m = m32;
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      const int64_t j = u * kBlock + (int)threadIdx.x;
-      const int64_t i = start + (j < m ? j : m - 1) * n / m;  // (a lane beyond the sample re-reads its last entry)
+      const uint32_t j = (uint32_t)(u * kBlock) + threadIdx.x;
+      const uint32_t jc = j < m32 ? j : m32 - 1u;  // (a lane beyond the sample re-reads its last entry)
+      const int64_t i = start + (n32 < (uint32_t)kListSample ? jc : (jc * n32) >> 12);
       const float x = a.grad[i] + a.resid[i];
-      key[u] = j < m ? mag_key(x) : 0u;
+      key[u] = j < m32 ? mag_key(x) : 0u;
     }
   }
   return listing_key_from_sample(key, k, n, m, lds_h, lds_sel);
 }
 
-// Clears the histograms (the workgroups from a.L on) and sets the listing key of every segment
-// whose lists would stay short (workgroup s: segment s); the setup kernel has left "nothing is
-// listed" in every segment.
-__global__ __launch_bounds__(kBlock) void k_topk_init_seg(const Args a, uint32_t hist_words) {
+// The listing keys live in a table that the layer-wise form with a separate acc does not use
+// otherwise (the in-place form's tie offsets: one word per tile, and there are more tiles than
+// segments).
+__device__ inline uint32_t* seg_listing_keys(const Args& a) { return a.tie_base; }
+
+// The setup kernel of the layer-wise Top_k call: workgroup 0 numbers the tiles (setup.h); with
+// lists, workgroup 1 + s sets the listing key of segment s from the layout arrays themselves
+// (it looks at the segment's own bounds only, which is all its loads need; what else makes a
+// segment invalid is workgroup 0's business, and an invalid segment's key is never read); the
+// remaining workgroups clear the histograms.
+__global__ __launch_bounds__(kBlock) void k_topk_seg_setup(const Args a, uint32_t hist_words, uint32_t samplers) {
   __shared__ uint32_t lds_h[256];
   __shared__ uint32_t lds_sel[kWaves + 3];
-  if (blockIdx.x >= (uint32_t)a.L) {
-    const uint32_t nb = gridDim.x - (uint32_t)a.L;
-    for (uint32_t i = (blockIdx.x - (uint32_t)a.L) * kBlock + threadIdx.x; i < hist_words; i += nb * kBlock)
+  if (blockIdx.x == 0) {
+    seg_setup_body(a, 0);
+    return;
+  }
+  if (blockIdx.x > samplers) {
+    const uint32_t nb = gridDim.x - 1u - samplers;
+    for (uint32_t i = (blockIdx.x - 1u - samplers) * kBlock + threadIdx.x; i < hist_words; i += nb * kBlock)
       a.hist[i] = 0;
     return;
   }
-  SegCtrl& c = a.ctrl[blockIdx.x];
-  if (c.bad || c.select_none) return;
-  const int64_t n = c.end - c.start;
+  const uint32_t s = blockIdx.x - 1u;
+  const int64_t start = a.seg_off[s], end = a.seg_off[s + 1], k = a.seg_k[s];
+  const int64_t n = end - start;
+  uint32_t tau = kNoListKey;
   // as the flat call: lists of about 8 k entries at most are to stay within a tenth of n (a
   // segment that fits a wave's stretch of the list buffer whole cannot make one run out)
-  if (2 * kListAim * c.k * 10 > n && n > (int64_t)a.list_cap) return;
-  const uint32_t tau = sample_listing_key_seg(a, c.start, n, c.k, lds_h, lds_sel);  // barriers
-  if (threadIdx.x == 0) c.tau_key = tau;
+  const bool sample = start >= 0 && end > start && end <= a.d_total && k >= 1 && k <= n &&
+                      !(2 * kListAim * k * 10 > n && n > (int64_t)a.list_cap);
+  if (sample) tau = sample_listing_key_seg(a, start, n, k, lds_h, lds_sel);  // block-uniform; barriers
+  if (threadIdx.x == 0) seg_listing_keys(a)[s] = tau;
 }
 
 // The accumulate kernel with lists: k_topk_accum_hist plus the residual write and the lists of
@@ -106,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_accum_list_seg(const Args a) {
   if (!locate_span<true>(a, tile, &sp_)) return;
   SegCtrl& c = a.ctrl[sp_.seg];
   if (c.bad) return;
-  const uint32_t tau = c.tau_key;
+  const uint32_t tau = seg_listing_keys(a)[sp_.seg];
   const uint32_t worker = tile * kWaves + wave_id();
   ListCursor lc;
   lc.cur = worker * a.list_cap;
@@ -146,14 +160,24 @@ __device__ inline void seg_tile_runs(const Args& a, uint32_t tile, const Span& s
   *r0 = tile * a.tile_chunks * kRunsPerChunk;
   *r1 = *r0 + s.nchunks * kRunsPerChunk;
 }
+// The five kernels after the accumulate kernel make two or three dependent trips to memory before
+// they know whether their tile's lists serve; the first wave of each workgroup has the head of
+// the tile's lists (lists.h) fetched meanwhile: the records before the tile is located (its run
+// slots follow from the tile number), the entries while the segment's control block and
+// histogram are on their way.
+__device__ inline bool seg_list_head_records(const Args& a, uint32_t tile, ListHead& head) {
+  if (!a.list || wave_id() != 0) return false;
+  list_head_records(a, tile * a.tile_chunks * kRunsPerChunk, a.tile_chunks * kRunsPerChunk, head);
+  return true;
+}
 // A digit pass over a tile's lists by the workgroup's first wave (list_digit_pass of topk_list.h).
-__device__ inline void seg_list_digit_pass(const Args& a, uint32_t r0, uint32_t r1, int pass,
-                                           uint32_t prefix, uint32_t* hw) {
+__device__ inline void seg_list_digit_pass(const Args& a, uint32_t r0, uint32_t r1, const ListHead& head,
+                                           int pass, uint32_t prefix, uint32_t* hw) {
   if (wave_id() != 0) return;
   const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);
   const int shift = digit_shift(pass);
   const uint32_t mask = (1u << digit_bits(pass)) - 1u;
-  for_each_list_entry_of_runs(a, r0, r1, [&](uint2 e, bool valid) {
+  for_each_list_entry_of_runs(a, r0, r1, &head, [&](uint2 e, bool valid) {
     const uint32_t key = e.y & 0x7FFFFFFFu;
     wave_hist_add(hw, (key >> shift) & mask, valid && (key >> hi_shift) == prefix);
   });
@@ -168,20 +192,24 @@ __global__ __launch_bounds__(kBlock) void k_topk_filter_seg(const Args a) {
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   if (threadIdx.x == 0) lds_cursor = 0;
   const uint32_t tile = gridDim.x - 1u - blockIdx.x;
+  ListHead head;
+  const bool heads = seg_list_head_records(a, tile, head);
   Span sp_;
   if (!locate_span<true>(a, tile, &sp_)) return;
+  if (heads) list_head_entries(a, head);
   SegCtrl& c = a.ctrl[sp_.seg];
+  const uint32_t bins = load_digit_bins(seg_pass_hist(a, 0, sp_.seg), a.hist_copies);
+  const bool usable = seg_lists_usable(a, c);
   if (c.bad || c.select_none) return;
-  const Digit dg = choose_digit_n(seg_pass_hist(a, 0, sp_.seg), a.hist_copies, 0, 0u, (uint32_t)c.k,
-                                  lds_sel);  // barriers
+  const Digit dg = digit_from_bins(bins, 0, 0u, (uint32_t)c.k, lds_sel);  // barriers
   if (tile == c.tile0 && threadIdx.x == 0) {
     c.sel_prefix[0] = dg.prefix;
     c.sel_krem[0] = dg.k_rem;
   }
-  if (seg_lists_usable(a, c)) {  // the second digit's histogram from the tile's lists
+  if (usable) {  // the second digit's histogram from the tile's lists
     uint32_t r0, r1;
     seg_tile_runs(a, tile, sp_, &r0, &r1);
-    seg_list_digit_pass(a, r0, r1, 1, dg.prefix, h[0]);
+    seg_list_digit_pass(a, r0, r1, head, 1, dg.prefix, h[0]);
     __syncthreads();
     flush_seg_hist(a, 1, sp_.seg, h);
     return;
@@ -213,20 +241,25 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist_seg(const Args a, int
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) h[w][threadIdx.x] = 0;
   const uint32_t tile = blockIdx.x;
+  ListHead head;
+  const bool heads = seg_list_head_records(a, tile, head);
   Span sp_;
   if (!locate_span<true>(a, tile, &sp_)) return;
+  if (heads) list_head_entries(a, head);
   SegCtrl& c = a.ctrl[sp_.seg];
+  const uint32_t bins = load_digit_bins(seg_pass_hist(a, pass - 1, sp_.seg), a.hist_copies);
+  const bool usable = seg_lists_usable(a, c);
   if (c.bad || c.select_none) return;
-  const Digit dg = choose_digit_n(seg_pass_hist(a, pass - 1, sp_.seg), a.hist_copies, pass - 1,
-                                  c.sel_prefix[pass - 2], c.sel_krem[pass - 2], lds_sel);  // barriers
+  const Digit dg = digit_from_bins(bins, pass - 1, c.sel_prefix[pass - 2], c.sel_krem[pass - 2],
+                                   lds_sel);  // barriers
   if (tile == c.tile0 && threadIdx.x == 0) {
     c.sel_prefix[pass - 1] = dg.prefix;
     c.sel_krem[pass - 1] = dg.k_rem;
   }
-  if (seg_lists_usable(a, c)) {
+  if (usable) {
     uint32_t r0, r1;
     seg_tile_runs(a, tile, sp_, &r0, &r1);
-    seg_list_digit_pass(a, r0, r1, pass, dg.prefix, h[0]);
+    seg_list_digit_pass(a, r0, r1, head, pass, dg.prefix, h[0]);
     __syncthreads();
     flush_seg_hist(a, pass, sp_.seg, h);
     return;
@@ -252,12 +285,16 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final_seg(const Args a) {
   __shared__ uint32_t lds_sel[kWaves + 3];
   __shared__ uint32_t lds_c[2 * kWaves];
   const uint32_t tile = blockIdx.x;
+  ListHead head;
+  const bool heads = seg_list_head_records(a, tile, head);
   Span sp_;
   if (!locate_span<true>(a, tile, &sp_)) return;
+  if (heads) list_head_entries(a, head);
   SegCtrl& c = a.ctrl[sp_.seg];
+  const uint32_t bins = load_digit_bins(seg_pass_hist(a, 3, sp_.seg), a.hist_copies);
+  const bool usable = seg_lists_usable(a, c);
   if (c.bad || c.select_none) return;
-  const Digit dg = choose_digit_n(seg_pass_hist(a, 3, sp_.seg), a.hist_copies, 3, c.sel_prefix[2],
-                                  c.sel_krem[2], lds_sel);
+  const Digit dg = digit_from_bins(bins, 3, c.sel_prefix[2], c.sel_krem[2], lds_sel);
   const uint32_t T = dg.prefix;
   const bool rank_ties = dg.count > dg.k_rem;
   if (tile == c.tile0 && threadIdx.x == 0) {
@@ -268,14 +305,14 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_final_seg(const Args a) {
     sparsify_result& r = a.result[sp_.seg];
     r.topk_key = T;
     r.topk_ties_taken = dg.k_rem;
-    if (a.list) r.flags |= seg_lists_usable(a, c) ? SPARSIFY_F_SHORTLIST : SPARSIFY_F_SHORTLIST_MISS;  // which way, no result
+    if (a.list) r.flags |= usable ? SPARSIFY_F_SHORTLIST : SPARSIFY_F_SHORTLIST_MISS;  // which way, no result
   }
   uint32_t gt = 0, eq = 0;
-  if (seg_lists_usable(a, c)) {  // the tile's counts from its lists, by one wave
+  if (usable) {  // the tile's counts from its lists, by one wave
     if (wave_id() != 0) return;
     uint32_t r0, r1;
     seg_tile_runs(a, tile, sp_, &r0, &r1);
-    for_each_list_entry_of_runs(a, r0, r1, [&](uint2 e, bool valid) {
+    for_each_list_entry_of_runs(a, r0, r1, &head, [&](uint2 e, bool valid) {
       const uint32_t key = e.y & 0x7FFFFFFFu;
       gt += (valid && key > T) ? 1u : 0u;
       eq += (valid && key == T) ? 1u : 0u;
@@ -332,8 +369,11 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered_seg(const Args 
   __shared__ uint32_t lds[kSlots * kWaves];
   __shared__ double lds_n[2 * kWaves];
   const uint32_t tile = blockIdx.x;
+  ListHead head;
+  const bool heads = seg_list_head_records(a, tile, head);
   Span sp_;
   if (!locate_span<true>(a, tile, &sp_)) return;
+  if (heads) list_head_entries(a, head);
   const SegCtrl& c = a.ctrl[sp_.seg];
   if (c.bad) return;
   const bool none = c.select_none != 0;
@@ -349,7 +389,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_compact_ordered_seg(const Args 
     if (wave_id() != 0) return;
     uint32_t r0, r1;
     seg_tile_runs(a, tile, sp_, &r0, &r1);
-    list_compact_runs(a, r0, r1, o.T, o.take, o.rank_ties, out_run, tie_run, o.out0, o.cap);
+    list_compact_runs(a, r0, r1, o.T, o.take, o.rank_ties, out_run, tie_run, o.out0, o.cap, &head);
     return;
   }
   NormAcc norms = {0.0, 0.0};

@@ -78,9 +78,9 @@ __device__ inline Digit choose_digit(const uint32_t* hist, int pass, uint32_t pr
   return digit_from_bins(v, pass, prefix, k_rem, lds);
 }
 
-// The same with a run-time number of replicas (layer-wise calls).
-__device__ inline Digit choose_digit_n(const uint32_t* hist, uint32_t copies, int pass,
-                                       uint32_t prefix, uint32_t k_rem, uint32_t* lds) {
+// The same with a run-time number of replicas (layer-wise calls), in two steps so that a caller
+// can have the histogram on order while it still waits for the prefix and the rank.
+__device__ inline uint32_t load_digit_bins(const uint32_t* hist, uint32_t copies) {
   const uint32_t bin = 255u - threadIdx.x;
   uint32_t v = 0;
   for (uint32_t r0 = 0; r0 < copies; r0 += 8) {
@@ -90,7 +90,11 @@ __device__ inline Digit choose_digit_n(const uint32_t* hist, uint32_t copies, in
 #pragma unroll
     for (int u = 0; u < 8; ++u) v += x[u];
   }
-  return digit_from_bins(v, pass, prefix, k_rem, lds);
+  return v;
+}
+__device__ inline Digit choose_digit_n(const uint32_t* hist, uint32_t copies, int pass,
+                                       uint32_t prefix, uint32_t k_rem, uint32_t* lds) {
+  return digit_from_bins(load_digit_bins(hist, copies), pass, prefix, k_rem, lds);
 }
 
 // `v`: this thread's bin count (thread order = descending digit).
