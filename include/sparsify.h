@@ -50,7 +50,7 @@ enum {
   SPARSIFY_F_BADSEGMENT = 8u, /* segmented call: this segment's offsets, k or output range are
                                 invalid (or its start lies before an earlier offset); no kernel
                                 touches its stretch of acc, residual or the output */
-  /* The next two say which way a flat call (or a segment of a layer-wise Gaussian_k call) took,
+  /* The next two say which way a flat call (or a segment of a layer-wise call) took,
      not what it computed (the results are the same either way); neither is set when the call
      built no short lists to begin with. */
   SPARSIFY_F_SHORTLIST = 16u,     /* the pairs (Top_k, DGC_k: and the digit passes) were taken from
@@ -99,7 +99,7 @@ typedef struct {
   int32_t sample_stride; /* DGC_k only.  0 (default): 100, a 1 % sample (Sec. 4.3).  Otherwise the
                       stratum length S >= 1: one sampled position per S consecutive elements */
   uint64_t sample_seed;  /* DGC_k only: seed of the counter-based choice of those positions */
-  int32_t short_list;    /* flat calls and layer-wise Gaussian_k.  0 (default): the library
+  int32_t short_list;    /* 0 (default): the library
                       decides.  -1: never build the short lists (below).  Results do not depend
                       on it. */
 } sparsify_opts;
@@ -123,8 +123,9 @@ typedef struct {
  *                                 residual and lists the entries above thres0, and when the
  *                                 refinement ends at thres0 or above, the pairs are written from
  *                                 those lists (20 bytes per element instead of 24, 16 instead of
- *                                 20 in place); in the layer-wise call every segment decides for
- *                                 itself.
+ *                                 20 in place).  In the layer-wise calls (Gaussian_k; Top_k with a
+ *                                 separate acc, where every segment is sampled for a key of its
+ *                                 own) every segment decides for itself.
  *   sparsify_workspace_bytes_min  the smallest size any call accepts; with less than the size
  *                                 above, no call builds the lists. */
 size_t sparsify_workspace_bytes(int64_t d_total, int32_t num_segments);
