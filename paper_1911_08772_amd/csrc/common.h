@@ -89,7 +89,7 @@ struct Args {
   uint32_t max_groups;
   double* norm_partial;   // [2][max_tiles]: per-tile sum of acc^2 and of residual'^2
   uint32_t* hist;         // [L][hist_copies][256]
-  uint32_t* tie_base;     // [max_tiles]
+  uint32_t* tie_base;     // [max_tiles] (layer-wise Top_k with lists: one listing key per segment instead)
   uint32_t* tile_hist;    // [up to 4096 tiles][128]: per-tile histogram of the last digit (Top_k in place)
   uint32_t hist_copies;   // replicas of each segment's histogram (spreads the atomics)
   uint32_t max_tiles;

@@ -49,10 +49,13 @@ __device__ inline uint32_t sample_listing_key_seg(const Args& a, int64_t start, 
   uint32_t key[16];
   int64_t m = kListSample;
   if (n >= kSegListFrom) {  // block-uniform
-    const int64_t stride16 = (n / 16) / kBlock;
-    const int64_t i = start + (int64_t)threadIdx.x * stride16 * 16;
+    const int64_t stride4 = (n / 4) / (kListSample / 4);
 #pragma unroll
-    for (int q = 0; q < 16; ++q) key[q] = mag_key(a.grad[i + q] + a.resid[i + q]);
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = start + (int64_t)(u * kBlock + (int)threadIdx.x) * stride4 * 4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) key[4 * u + q] = mag_key(a.grad[i + q] + a.resid[i + q]);
+    }
   } else {
     static_assert(kListSample == 4096, "the spacing below is a shift");
     const uint32_t n32 = (uint32_t)n;
