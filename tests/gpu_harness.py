@@ -80,16 +80,20 @@ def assert_pairs_match(got, idx_o, val_o, what=""):
 
 def assert_same_threshold(res, ro: O.Result, acc=None, what=""):
     """The fp32 threshold the final mask compared against.  GPU and oracle sum the moments in
-    fp64 in different orders, so their fp64 thresholds differ in the last bits (<= 1e-11
-    relative, far inside the 1e-6 the benchmark spec allows) and can, once in thousands of vectors,
-    round to neighbouring fp32 values.  That is accepted when no entry of `acc` lies between the
-    two (both thresholds then select the same entries, which the callers go on to compare bit
-    for bit); otherwise the bits must be equal."""
+    fp64 in different orders, so their fp64 thresholds differ in the last bits (the oracle's
+    plain running sums over d entries are themselves within d * 2^-53 relative of the exact
+    moments, the bound this check allows twice: 2e-11 was seen on a heavy-tailed vector of 6.9 M
+    entries, where the kernels' partial sums matched extended precision to 4e-16; far inside the
+    1e-6 the benchmark spec allows) and can, once in thousands of vectors, round to neighbouring
+    fp32 values.  That is accepted when no entry of `acc` lies between the two (both thresholds
+    then select the same entries, which the callers go on to compare bit for bit); otherwise the
+    bits must be equal."""
     g32, o32 = np.float32(res["thres_f32"]), np.float32(ro.thres_f32)
     if g32.view(np.uint32) == o32.view(np.uint32):
         return
     assert acc is not None and np.isfinite(g32) and np.isfinite(o32), (what, g32, o32)
-    assert abs(float(res["thres"]) - ro.thres) <= 1e-11 * abs(ro.thres), (what, res["thres"], ro.thres)
+    rtol = max(1e-11, 2.0 * acc.size * 2.0 ** -53)
+    assert abs(float(res["thres"]) - ro.thres) <= rtol * abs(ro.thres), (what, res["thres"], ro.thres)
     lo, hi = min(g32, o32), max(g32, o32)
     assert np.nextafter(lo, np.float32(np.inf)) == hi, (what, g32, o32)   # neighbours
     m = np.abs(acc)
