@@ -185,3 +185,45 @@ def test_a_layer_wise_call_with_lists_can_be_captured_in_a_hip_graph():
         assert same_bits(b.residual.cpu().numpy(), eps), step
         assert same_bits(b.acc.cpu().numpy(), acc_o), step
         _ = (b.acc * 2).sum().item()   # unrelated eager work between replays
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_invalid_segments_in_a_layout_with_lists_are_flagged_and_left_alone(mode):
+    """A layout of list-building length whose offsets step back: the segments that start before
+    an earlier offset are flagged and no kernel touches their stretches (Top_k's sampling
+    workgroups look at a segment's own bounds only, so they may read a flagged segment, never
+    write for it); the segments before the step and after the ground lost is made up are served."""
+    from gpu_harness import same_bits
+    from oracle import oracle as O
+    d = 7_000_000
+    #                   seg0 [0, 4 M)   seg1 backwards   seg2 [3 M, 3.5 M)   seg3 k > n   seg4 [5 M, 7 M)
+    seg_off = np.array([0, 4_000_000, 3_000_000, 3_500_000, 5_000_000, d], np.int64)
+    seg_k = np.array([4000, 1, 500, 1_500_001, 2000], np.int64)
+    caps = np.array([16_000, 100, 2000, 100, 8000], np.int64)
+    out_off = np.concatenate([[0], np.cumsum(caps)])
+    gpu = SegGpu(seg_off, seg_k, caps)
+    g = synth.normal(d, 176, 0, 0.01)
+    gpu.b.residual.zero_()
+    gpu.b.acc.fill_(float("nan"))
+    out = gpu.step(mode, g)
+    res = out["res"]
+    for l in (1, 2, 3):
+        assert int(res[l]["flags"]) == S.F_BADSEGMENT and int(res[l]["nnz"]) == 0, l
+    assert np.all(np.isnan(out["acc"][4_000_000:5_000_000]))
+    assert not out["eps"][4_000_000:5_000_000].any()
+    assert np.all(out["idx"][out_off[1]:out_off[4]] == -1)
+    for l, (lo, hi) in ((0, (0, 4_000_000)), (4, (5_000_000, d))):
+        assert int(res[l]["flags"]) & ~S.F_WAY == 0 and int(res[l]["flags"]) & S.F_WAY == LIST, l
+        acc_o = O.accumulate(g[lo:hi], np.zeros(hi - lo, np.float32))
+        assert same_bits(out["acc"][lo:hi], acc_o), l
+        k, cap = int(seg_k[l]), int(caps[l])
+        if mode == 0:
+            idx_o, val_o, eps_o, _ = O.topk(acc_o, k)
+        else:
+            idx_o, val_o, eps_o, _ = O.gaussiank(acc_o, k, cap=cap)
+        n, o0 = int(res[l]["nnz"]), int(out_off[l])
+        assert n == idx_o.size and n > 0, l
+        assert np.array_equal(out["idx"][o0:o0 + n].view(np.uint32), idx_o + np.uint32(lo)), l
+        assert same_bits(out["val"][o0:o0 + n], val_o), l
+        assert np.all(out["idx"][o0 + n:o0 + cap] == -1), l
+        assert same_bits(out["eps"][lo:hi], eps_o), l
