@@ -1,4 +1,5 @@
-// Gaussian_k, layer-wise calls: setup + three launches.  The same idea as gaussiank_flat.h, per
+// Gaussian_k, layer-wise calls: three launches for up to 256 segments (the accumulate kernel has
+// the setup in it), setup + three beyond.  The same idea as gaussiank_flat.h, per
 // segment: every workgroup of the count kernel merges the moment partials of its own segment's
 // tiles and derives the ten thresholds; every workgroup of the compact kernel totals its
 // segment's groups of 64 tiles, walks Algorithm 1 and finds its first output slot.  A segment's
@@ -19,6 +20,52 @@
 #include "tile_io.h"
 
 namespace sp {
+
+// Layer-wise calls of up to kBlock segments need no setup launch before the accumulate kernel:
+// every workgroup runs the one round of the setup walk itself (seg_setup_round of setup.h: the
+// layout arrays, two scans) and finds its tile's segment in what the round leaves; one more
+// workgroup, which streams nothing, is the setup kernel: it writes the control blocks, the tile
+// numbering, the cleared records and the group totals that the kernels after this one read.
+// (The quantile goes into a field of the control block that the setup does not write.)
+__global__ __launch_bounds__(kBlock) void k_accum_moments_seg_setup(const Args a) {
+  __shared__ double lds[4 * kWaves];
+  __shared__ uint32_t lds_scan[kWaves + 1];
+  __shared__ int64_t lds_max[kWaves];
+  __shared__ int64_t lds_seg[3];  // start, end, k of the tile's segment
+  __shared__ uint32_t lds_found[2];  // the segment, its first tile
+  if (blockIdx.x == gridDim.x - 1u) {
+    seg_setup_body(a, 1);
+    return;
+  }
+  const uint32_t tile = blockIdx.x;
+  if (threadIdx.x == 0) lds_found[0] = 0xFFFFFFFFu;
+  int64_t off_max = 0;
+  const SegRound r = seg_setup_round(a, 0, 0u, 0u, off_max, lds_scan, lds_max);  // barriers
+  if (r.s < a.L && tile >= r.tile0 && tile - r.tile0 < r.nt) {  // one thread at most: the tiles of valid segments are disjoint
+    lds_found[0] = (uint32_t)r.s;
+    lds_found[1] = r.tile0;
+    lds_seg[0] = r.start;
+    lds_seg[1] = r.end;
+    lds_seg[2] = r.k;
+  }
+  __syncthreads();
+  const uint32_t seg = lds_found[0];
+  if (seg == 0xFFFFFFFFu) return;  // a surplus workgroup, or a tile number an invalid segment left unused
+  const uint32_t tile0 = lds_found[1];
+  const int64_t start = lds_seg[0], end = lds_seg[1];
+  Span sp_;
+  make_span(&sp_, (int)seg, start, end,
+            seg_base(start) + (int64_t)(tile - tile0) * a.tile_chunks * kChunk, a.tile_chunks);
+  MomAcc m = {0.0, 0.0, 0.0, 0.0, false};
+  for (uint32_t u = 0; u < sp_.nchunks; ++u) {
+    const Tile t = chunk_of(sp_, u);
+    if (t.full) accum_moments_chunk<true>(a, t, m);
+    else accum_moments_chunk<false>(a, t, m);
+  }
+  store_moment_partial(a, m, tile, lds);
+  if (threadIdx.x == 0 && tile == tile0)
+    a.ctrl[seg].z = norm_isf((double)lds_seg[2] / (a.tail_div * (double)(end - start)));
+}
 
 // Counts: thresholds of the tile's segment from that segment's moment partials (one pass
 // around the provisional centre P = mean of the segment's first partial, as in

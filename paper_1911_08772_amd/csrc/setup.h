@@ -60,6 +60,66 @@ __device__ inline int64_t block_exclusive_max(int64_t v, int64_t lowest, int64_t
   return before;
 }
 
+// One round of the walk: what thread i learns of segment base + i.  Every workgroup that runs a
+// round on the same layout gets the same answers (same arithmetic on the same inputs).
+struct SegRound {
+  int s;                          // the segment (base + thread), >= a.L: none
+  int64_t start, end, k, o0, o1;
+  uint32_t nt, tile0, ng, group0; // tiles and groups of 64 tiles (0 if bad), the first of each
+  bool bad;
+  uint32_t total, gtotal;         // tiles and groups numbered in this round (block-uniform)
+};
+// `lds_scan` holds kWaves + 1 words, `lds_max` kWaves words of 8 bytes.  Barriers.
+__device__ inline SegRound seg_setup_round(const Args& a, int base, uint32_t carry, uint32_t gcarry,
+                                           int64_t& off_max, uint32_t* lds_scan, int64_t* lds_max) {
+  SegRound r;
+  r.s = base + (int)threadIdx.x;
+  const int s = r.s;
+  uint32_t nt = 0;
+  bool bad = true;
+  int64_t start = 0, end = 0, k = 0, o0 = 0, o1 = 0;
+  if (s < a.L) {
+    start = a.seg_off[s];
+    end = a.seg_off[s + 1];
+    k = a.seg_k[s];
+    o0 = a.out_off[s];
+    o1 = a.out_off[s + 1];
+    bad = !(start >= 0 && end > start && end <= a.d_total && k >= 1 && k <= end - start &&
+            o0 >= 0 && o1 >= o0 && o1 <= a.out_cap);
+    if (s == 0 && start != 0) bad = true;
+    if (s == a.L - 1 && end != a.d_total) bad = true;
+  }
+  {  // offsets must not step back behind an earlier one (seg_off non-decreasing up to here)
+    const int64_t lowest = (int64_t)1 << 63;
+    int64_t round_max;
+    const int64_t before = block_exclusive_max(s < a.L ? start : lowest, lowest, lds_max, &round_max);
+    if (s < a.L && (start < before || start < off_max)) bad = true;
+    if (round_max > off_max) off_max = round_max;
+  }
+  if (s < a.L && !bad) nt = seg_ntiles(start, end, a.tile_chunks);
+  uint32_t total, gtotal;
+  const uint32_t excl = block_exclusive_scan(nt, lds_scan, &total);
+  // a layout whose valid segments overlap could number more tiles than the workspace holds
+  if (s < a.L && !bad && (uint64_t)carry + excl + nt > (uint64_t)a.max_tiles) bad = true;
+  const uint32_t ng = bad ? 0u : (nt + kSegGroupTiles - 1) / kSegGroupTiles;
+  const uint32_t gexcl = block_exclusive_scan(ng, lds_scan, &gtotal);
+  const uint32_t group0 = gcarry + gexcl;
+  if (s < a.L && !bad && (uint64_t)group0 + ng > (uint64_t)a.max_groups) bad = true;  // cannot happen: see carve
+  r.start = start;
+  r.end = end;
+  r.k = k;
+  r.o0 = o0;
+  r.o1 = o1;
+  r.nt = bad ? 0u : nt;
+  r.tile0 = carry + excl;
+  r.ng = ng;
+  r.group0 = group0;
+  r.bad = bad;
+  r.total = total;
+  r.gtotal = gtotal;
+  return r;
+}
+
 __device__ inline void seg_setup_body(const Args& a, int mode) {
   __shared__ uint32_t lds_scan[kWaves + 1];
   __shared__ int64_t lds_max[kWaves];
@@ -67,74 +127,45 @@ __device__ inline void seg_setup_body(const Args& a, int mode) {
   uint32_t gcarry = 0;   // groups numbered so far
   int64_t off_max = 0;   // largest offset among the segments of earlier rounds
   for (int base = 0; base < a.L; base += kBlock) {
-    const int s = base + (int)threadIdx.x;
-    uint32_t nt = 0;
-    bool bad = true;
-    int64_t start = 0, end = 0, k = 0, o0 = 0, o1 = 0;
+    const SegRound r = seg_setup_round(a, base, carry, gcarry, off_max, lds_scan, lds_max);
+    const int s = r.s;
     if (s < a.L) {
-      start = a.seg_off[s];
-      end = a.seg_off[s + 1];
-      k = a.seg_k[s];
-      o0 = a.out_off[s];
-      o1 = a.out_off[s + 1];
-      bad = !(start >= 0 && end > start && end <= a.d_total && k >= 1 && k <= end - start &&
-              o0 >= 0 && o1 >= o0 && o1 <= a.out_cap);
-      if (s == 0 && start != 0) bad = true;
-      if (s == a.L - 1 && end != a.d_total) bad = true;
-    }
-    {  // offsets must not step back behind an earlier one (seg_off non-decreasing up to here)
-      const int64_t lowest = (int64_t)1 << 63;
-      int64_t round_max;
-      const int64_t before = block_exclusive_max(s < a.L ? start : lowest, lowest, lds_max, &round_max);
-      if (s < a.L && (start < before || start < off_max)) bad = true;
-      if (round_max > off_max) off_max = round_max;
-    }
-    if (s < a.L && !bad) nt = seg_ntiles(start, end, a.tile_chunks);
-    uint32_t total, gtotal;
-    const uint32_t excl = block_exclusive_scan(nt, lds_scan, &total);
-    // a layout whose valid segments overlap could number more tiles than the workspace holds
-    if (s < a.L && !bad && (uint64_t)carry + excl + nt > (uint64_t)a.max_tiles) bad = true;
-    const uint32_t ng = bad ? 0u : (nt + kSegGroupTiles - 1) / kSegGroupTiles;
-    const uint32_t gexcl = block_exclusive_scan(ng, lds_scan, &gtotal);
-    if (s < a.L) {
-      const uint32_t tile0 = carry + excl;
-      const uint32_t group0 = gcarry + gexcl;
-      if (!bad && (uint64_t)group0 + ng > (uint64_t)a.max_groups) bad = true;  // cannot happen: see carve
-      a.tile_start[s] = tile0;
+      const bool bad = r.bad;
+      a.tile_start[s] = r.tile0;
       SegCtrl& c = a.ctrl[s];
-      c.start = start;
-      c.end = end;
-      c.k = k;
-      c.cap = o1 - o0;
-      c.out_base = o0;
-      c.tile0 = tile0;
-      c.ntiles = bad ? 0u : nt;
+      c.start = r.start;
+      c.end = r.end;
+      c.k = r.k;
+      c.cap = r.o1 - r.o0;
+      c.out_base = r.o0;
+      c.tile0 = r.tile0;
+      c.ntiles = r.nt;
       c.bad = bad ? 1u : 0u;
-      c.group0 = group0;
+      c.group0 = r.group0;
       c.prefix = 0;
-      c.k_rem = (uint32_t)k;
+      c.k_rem = (uint32_t)r.k;
       c.n_eq = 0;
       c.rank_ties = 0;
       c.select_none = 0;
       c.t_final = 0.0f;
       c.list_mode = 0;  // layer-wise calls with lists: set when one of the segment's stretches ran out
       c.list_count = 0;
-      sparsify_result& r = a.result[s];
-      clear_result(r);
+      sparsify_result& res = a.result[s];
+      clear_result(res);
       if (bad) {
-        r.flags = SPARSIFY_F_BADSEGMENT;
+        res.flags = SPARSIFY_F_BADSEGMENT;
       } else if (mode == 0) {
-        if (c.cap < k) {
+        if (c.cap < r.k) {
           c.select_none = 1;
-          r.flags = SPARSIFY_F_OVERFLOW;
+          res.flags = SPARSIFY_F_OVERFLOW;
         } else {
-          r.nnz = (uint32_t)k;
+          res.nnz = (uint32_t)r.k;
         }
       }
     }
-    const uint64_t next = (uint64_t)carry + total;
+    const uint64_t next = (uint64_t)carry + r.total;
     carry = next > 0x40000000ull ? 0x40000000u : (uint32_t)next;
-    gcarry += gtotal;  // <= carry / 1 + L: no overflow
+    gcarry += r.gtotal;  // <= carry / 1 + L: no overflow
   }
   if (threadIdx.x == 0) a.tile_start[a.L] = carry;
   const uint32_t words = (gcarry < a.max_groups ? gcarry : a.max_groups) * (uint32_t)kNumThres;

@@ -313,10 +313,15 @@ bool stream_acc(const Args& a) { return a.d_total >= kStreamAccFrom && a.d_total
 // vector on: per call 4.5 % faster at 33.5 M elements, no difference at 30 M and below.
 constexpr int64_t kStreamAccListFrom = 32'000'000;
 
-// Layer-wise Gaussian_k: setup + three launches (gaussiank_seg.h).
+// Layer-wise Gaussian_k: three launches for up to 256 segments, setup + three beyond (gaussiank_seg.h).
 void launch_gaussiank_seg(Launcher& ln, const Args& a, uint32_t tiles) {
   const dim3 blk(kBlock);
-  ln.run("accum_moments", k_accum_moments_seg, dim3(tiles), blk, a);
+  if (a.L <= kBlock) {  // the accumulate kernel's workgroups find their segments themselves
+    ln.run("accum_moments", k_accum_moments_seg_setup, dim3(tiles + 1), blk, a);
+  } else {
+    ln.run("seg_setup", k_seg_setup, dim3(1), blk, a, 1);
+    ln.run("accum_moments", k_accum_moments_seg, dim3(tiles), blk, a);
+  }
   ln.run("gk_count", k_gk_count_seg, dim3(tiles), blk, a);
   if (a.norms) {
     ln.run("gk_compact", k_gk_compact_seg<true>, dim3(tiles), blk, a);
@@ -684,7 +689,6 @@ int sparsify_segmented(int32_t num_segments, int64_t d_total, const int64_t* seg
               opts ? static_cast<sparsify_trace*>(opts->trace) : nullptr};
   ln.begin();
   if (mode == 1) {
-    ln.run("seg_setup", k_seg_setup, dim3(1), dim3(kBlock), a, 1);
     launch_gaussiank_seg(ln, a, tiles);
   } else {
     // the setup kernel's other workgroups clear the histograms ([pass][segment][replica][256]: at

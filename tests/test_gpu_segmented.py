@@ -186,11 +186,11 @@ def test_cfg4_segmented_workload(mode):
 
 
 def test_layer_wise_calls_take_the_short_launch_sequences():
-    """The kernels behind a call are visible through the trace: setup + three launches for
-    Gaussian_k, seven launches for Top_k with a separate accumulator (candidate filtering; the
+    """The kernels behind a call are visible through the trace: three launches for
+    Gaussian_k (up to 256 segments: the accumulate kernel has the setup in it), seven launches for Top_k with a separate accumulator (candidate filtering; the
     setup kernel also clears the histograms), the long general sequence only in place."""
     seg_off, seg_k, caps = layout([100_000, 7, 250_001, 64])
-    want = {(1, False): ["seg_setup", "accum_moments", "gk_count", "gk_compact"],
+    want = {(1, False): ["accum_moments", "gk_count", "gk_compact"],
             (0, False): ["seg_setup", "topk_accum_hist", "topk_filter", "topk_cand2",
                          "topk_cand3", "topk_final", "topk_compact"]}
     g = seg_grad(seg_off, 5, 0, [1e-2, 1.0, 1e-3, 1e-1])
